@@ -1,0 +1,197 @@
+"""ctypes front of the C++ oracle (oracle/intsgd_oracle.cpp): numpy in, numpy out.
+
+Test infrastructure only.  Every function takes the slice start ``j0`` (global
+index of the first coordinate of the arrays handed in), so any window of a large
+vector can be checked on its own.  Rounding: 0 = nearest-even (Section 5.1),
+1 = randomized Int of Section 2.
+"""
+import ctypes as C
+
+import numpy as np
+
+from . import build as _build
+
+__all__ = [
+    "philox4x32_10", "random_word", "int_random", "int_nearest", "saturate", "compress",
+    "int_sum", "decode_update", "update_norm", "next_alpha", "step",
+    "ROUND_NEAREST_EVEN", "ROUND_STOCHASTIC",
+]
+
+ROUND_NEAREST_EVEN = 0
+ROUND_STOCHASTIC = 1
+
+_lib = C.CDLL(_build.build())
+
+_u32p = C.POINTER(C.c_uint32)
+_u64p = C.POINTER(C.c_uint64)
+_i32p = C.POINTER(C.c_int32)
+_f32p = C.POINTER(C.c_float)
+_f64p = C.POINTER(C.c_double)
+
+_lib.oracle_philox4x32_10.argtypes = [_u32p, _u32p, _u32p]
+_lib.oracle_philox4x32_10.restype = None
+_lib.oracle_random_word.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint64]
+_lib.oracle_random_word.restype = C.c_uint32
+_lib.oracle_int_random.argtypes = [C.c_float, C.c_uint32]
+_lib.oracle_int_random.restype = C.c_float
+_lib.oracle_int_nearest.argtypes = [C.c_float]
+_lib.oracle_int_nearest.restype = C.c_float
+_lib.oracle_saturate.argtypes = [C.c_float, C.c_int32, C.POINTER(C.c_int)]
+_lib.oracle_saturate.restype = C.c_int32
+_lib.oracle_compress.argtypes = [_f32p, C.c_uint64, C.c_uint64, _f32p, _u64p, C.c_uint32,
+                                 C.c_int, C.c_int32, C.c_uint64, C.c_uint32, C.c_uint32, _i32p]
+_lib.oracle_compress.restype = C.c_uint64
+_lib.oracle_int_sum.argtypes = [C.POINTER(_i32p), C.c_uint32, C.c_uint64, _i32p]
+_lib.oracle_int_sum.restype = C.c_uint64
+_lib.oracle_decode_update.argtypes = [_i32p, C.c_uint64, C.c_uint64, _f32p, _u64p, C.c_uint32,
+                                      C.c_uint32, C.c_double, _f32p, _f32p, _f32p]
+_lib.oracle_decode_update.restype = None
+_lib.oracle_update_norm.argtypes = [_f32p, _f32p, C.c_uint64, C.c_uint64, _u64p, C.c_uint32,
+                                    _f64p]
+_lib.oracle_update_norm.restype = None
+_lib.oracle_next_alpha.argtypes = [_f64p, _f64p, C.c_uint32, _u64p, C.c_uint64, C.c_uint32,
+                                   C.c_double, C.c_double, C.c_double, _f64p, _f32p]
+_lib.oracle_next_alpha.restype = C.c_int
+_lib.oracle_step.argtypes = [C.POINTER(_f32p), C.c_uint32, C.c_uint64, C.c_uint64, _f32p, _u64p,
+                             C.c_uint32, C.c_int, C.c_int32, C.c_uint64, C.c_uint32, C.c_double,
+                             _f32p, _f32p, _i32p, _u64p, _f64p]
+_lib.oracle_step.restype = C.c_uint64
+
+
+def _arr(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+def _ptr(a, ctype):
+    return a.ctypes.data_as(C.POINTER(ctype))
+
+
+def _offsets(offsets, B):
+    if offsets is None:
+        assert B == 1
+        return None, None
+    off = _arr(offsets, np.uint64)
+    assert off.shape == (B + 1,)
+    return off, _ptr(off, C.c_uint64)
+
+
+def _alpha(alpha):
+    a = np.atleast_1d(_arr(alpha, np.float32))
+    return a, _ptr(a, C.c_float)
+
+
+def philox4x32_10(counter, key):
+    c = _arr(counter, np.uint32)
+    k = _arr(key, np.uint32)
+    assert c.shape == (4,) and k.shape == (2,)
+    out = np.empty(4, np.uint32)
+    _lib.oracle_philox4x32_10(_ptr(c, C.c_uint32), _ptr(k, C.c_uint32), _ptr(out, C.c_uint32))
+    return out
+
+
+def random_word(seed, step, worker, j):
+    return int(_lib.oracle_random_word(int(seed), int(step), int(worker), int(j)))
+
+
+def int_random(t, word):
+    return float(_lib.oracle_int_random(float(np.float32(t)), int(word)))
+
+
+def int_nearest(t):
+    return float(_lib.oracle_int_nearest(float(np.float32(t))))
+
+
+def saturate(r, L):
+    flag = C.c_int(0)
+    q = _lib.oracle_saturate(float(np.float32(r)), int(L), C.byref(flag))
+    return int(q), int(flag.value)
+
+
+def compress(g, alpha, *, rounding, L, seed=0, step=0, worker=0, j0=0, offsets=None):
+    """Integer message of one worker on a slice -> (q int32[len], clip count)."""
+    g = _arr(g, np.float32)
+    a, ap = _alpha(alpha)
+    off, offp = _offsets(offsets, a.size)
+    q = np.empty(g.size, np.int32)
+    cnt = _lib.oracle_compress(_ptr(g, C.c_float), int(j0), g.size, ap, offp, a.size,
+                               int(rounding), int(L), int(seed), int(step), int(worker),
+                               _ptr(q, C.c_int32))
+    return q, int(cnt)
+
+
+def int_sum(qs):
+    """Exact sum of n int32 vectors -> (sum int32[len], number of int32 overflows)."""
+    qs = [_arr(q, np.int32) for q in qs]
+    n, ln = len(qs), qs[0].size
+    assert all(q.size == ln for q in qs)
+    ptrs = (_i32p * n)(*[_ptr(q, C.c_int32) for q in qs])
+    s = np.empty(ln, np.int32)
+    ovf = _lib.oracle_int_sum(ptrs, n, ln, _ptr(s, C.c_int32))
+    return s, int(ovf)
+
+
+def decode_update(S, alpha, x, *, n, eta, j0=0, offsets=None, want_gtilde=False):
+    S = _arr(S, np.int32)
+    x = _arr(x, np.float32)
+    assert S.size == x.size
+    a, ap = _alpha(alpha)
+    off, offp = _offsets(offsets, a.size)
+    xn = np.empty_like(x)
+    gt = np.empty_like(x) if want_gtilde else None
+    _lib.oracle_decode_update(_ptr(S, C.c_int32), int(j0), S.size, ap, offp, a.size, int(n),
+                              float(eta), _ptr(x, C.c_float), _ptr(xn, C.c_float),
+                              _ptr(gt, C.c_float) if want_gtilde else None)
+    return (xn, gt) if want_gtilde else xn
+
+
+def update_norm(x_new, x_old, *, j0=0, offsets=None, B=1, out=None):
+    xn = _arr(x_new, np.float32)
+    xo = _arr(x_old, np.float32)
+    assert xn.size == xo.size
+    off, offp = _offsets(offsets, B)
+    ns = np.zeros(B, np.float64) if out is None else out
+    _lib.oracle_update_norm(_ptr(xn, C.c_float), _ptr(xo, C.c_float), int(j0), xn.size, offp, B,
+                            _ptr(ns, C.c_double))
+    return ns
+
+
+def next_alpha(normsq, r, *, d, n, beta, eps, eta, offsets=None):
+    """-> (r_new f64[B], alpha f64[B], alpha f32[B], bad flag)."""
+    ns = np.atleast_1d(_arr(normsq, np.float64))
+    r_new = np.atleast_1d(np.array(r, dtype=np.float64, copy=True))
+    B = ns.size
+    assert r_new.size == B
+    off, offp = _offsets(offsets, B)
+    ad = np.empty(B, np.float64)
+    af = np.empty(B, np.float32)
+    bad = _lib.oracle_next_alpha(_ptr(ns, C.c_double), _ptr(r_new, C.c_double), B, offp, int(d),
+                                 int(n), float(beta), float(eps), float(eta),
+                                 _ptr(ad, C.c_double), _ptr(af, C.c_float))
+    return r_new, ad, af, int(bad)
+
+
+def step(grads, alpha, x, *, rounding, L, eta, seed=0, step=0, j0=0, offsets=None,
+         normsq=None):
+    """One whole IntSGD step on a slice.
+
+    -> dict(x_new, S, sat_count[n], normsq[B] (accumulated into ``normsq`` if given),
+    overflow).
+    """
+    gs = [_arr(g, np.float32) for g in grads]
+    n, ln = len(gs), gs[0].size
+    assert all(g.size == ln for g in gs)
+    x = _arr(x, np.float32)
+    assert x.size == ln
+    a, ap = _alpha(alpha)
+    B = a.size
+    off, offp = _offsets(offsets, B)
+    ptrs = (_f32p * n)(*[_ptr(g, C.c_float) for g in gs])
+    xn = np.empty_like(x)
+    S = np.empty(ln, np.int32)
+    sat = np.zeros(n, np.uint64)
+    ns = np.zeros(B, np.float64) if normsq is None else normsq
+    ovf = _lib.oracle_step(ptrs, n, int(j0), ln, ap, offp, B, int(rounding), int(L), int(seed),
+                           int(step), float(eta), _ptr(x, C.c_float), _ptr(xn, C.c_float),
+                           _ptr(S, C.c_int32), _ptr(sat, C.c_uint64), _ptr(ns, C.c_double))
+    return dict(x_new=xn, S=S, sat_count=sat, normsq=ns, overflow=int(ovf))
