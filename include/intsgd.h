@@ -1,0 +1,208 @@
+/*
+ * intsgd.h -- C ABI of the IntSGD compression hot path for AMD MI355X (gfx950).
+ *
+ * One IntSGD step (arXiv 2102.08374, Algorithm 1; block form: Algorithm 2 of
+ * Appendix A.1) for n workers whose fp32 gradients live in ONE device memory:
+ *
+ *   a1 scale      t = alpha_k * g_i^k[j]                 (Algorithm 1, "scale and round")
+ *   a2 round      Int(t), randomized (Section 2) or nearest-even (Section 5.1)
+ *   a3 clip       saturate to [-L, L] and count          (Section 5.1)
+ *   a4 aggregate  S[j] = sum_i q_i[j]                     (Algorithm 1, aggregation line;
+ *                                                         stands in for the integer all-reduce)
+ *   a5 decode     g~[j] = S[j] / (n alpha_k)              (Algorithm 1, estimator line)
+ *   a6 update     x[j] <- x[j] - eta_k g~[j]              (Algorithm 1, update line)
+ *   a7 norm       ||x^{k+1} - x^k||^2 (per block)         (Algorithm 1 / 2, moving-average line)
+ *   a8 next alpha r <- beta r + (1-beta)||.||^2, alpha    (Section 4.1, Proposition 2; Algorithm 2)
+ *
+ * Conventions that hold for every entry point
+ *   - "DEVICE" pointers address memory of the current HIP device; "HOST" pointers
+ *     address ordinary host memory.  The caller owns every buffer; the library
+ *     never frees or keeps a caller's pointer after the call returns.
+ *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream) and is asynchronous: results are in device memory once
+ *     the stream reaches that point.  Nothing synchronises with the host.
+ *   - Arguments are validated BEFORE anything is enqueued; on any error status
+ *     nothing was launched and no output was touched.
+ *   - Vectors of d coordinates must be 16-byte aligned (int8 vectors too).
+ *   - Saturation and non-finite gradients are data conditions: they are counted
+ *     in sat_count, never turned into an error.
+ *   - The only library-owned device memory is a small per-partition tile table
+ *     that is built the first time a descriptor with num_blocks > 1 is used (or
+ *     by intsgd_prepare) and freed by intsgd_release().  Descriptors with
+ *     num_blocks == 1 need none.
+ *   - Calls on different streams that share a workspace race; give each
+ *     concurrent call its own workspace.
+ */
+#ifndef INTSGD_H_
+#define INTSGD_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  INTSGD_OK = 0,
+  INTSGD_EINVAL = -1,     /* null pointer, zero size, bad enum, eta/beta/eps out of range */
+  INTSGD_EALIGN = -2,     /* a vector pointer is not 16-byte aligned */
+  INTSGD_ERANGE = -3,     /* clip bound or worker count outside what the wire / int32 sum can hold */
+  INTSGD_EHIP = -4,       /* a HIP runtime call failed (see intsgd_last_hip_error) */
+  INTSGD_EWORKSPACE = -5  /* workspace missing, misaligned or smaller than intsgd_workspace_bytes */
+} intsgd_status;
+
+typedef enum {
+  INTSGD_ROUND_NEAREST_EVEN = 0, /* Section 5.1: deterministic rounding, ties to even */
+  INTSGD_ROUND_STOCHASTIC = 1    /* Section 2: Int(t) = floor(t)+1 w.p. t-floor(t) */
+} intsgd_rounding;
+
+typedef enum {
+  INTSGD_WIRE_INT8 = 8,  /* per-worker integer vectors are int8_t  (clip <= 127) */
+  INTSGD_WIRE_INT32 = 32 /* per-worker integer vectors are int32_t */
+} intsgd_wire;
+
+#define INTSGD_MAX_WORKERS 128u
+
+/*
+ * Problem statement shared by all calls.
+ *   d, n        model dimension and number of workers (Section 1, eq. (1)); d > 0,
+ *               1 <= n <= INTSGD_MAX_WORKERS.
+ *   num_blocks  B >= 1.  B == 1 is Algorithm 1 (one alpha for the whole vector);
+ *               B > 1 is Algorithm 2 (one alpha per block).
+ *   block_offsets  HOST array of B+1 coordinate offsets, [0] = 0, [B] = d, strictly
+ *               increasing; may be NULL when B == 1.  Read during the call only.
+ *   rounding    a2.  wire: storage type of the per-worker integer vectors (a3).
+ *   clip        L >= 1: rounded values saturate to [-L, L].  Required:
+ *               n * L <= INT32_MAX so the int32 aggregate is the exact sum, and
+ *               L <= 127 when wire is INT8.
+ *   seed, step  randomized rounding draws, for worker i and GLOBAL coordinate j,
+ *               word (j mod 4) of Philox4x32-10 at counter
+ *               (lo32(j/4), hi32(j/4), i, step) with key (lo32(seed), hi32(seed));
+ *               the top 24 bits u of the word decide: round up iff u 2^-24 < t - floor(t).
+ */
+typedef struct intsgd_desc {
+  uint64_t d;
+  uint32_t n;
+  uint32_t num_blocks;
+  const uint64_t* block_offsets;
+  int32_t rounding; /* intsgd_rounding */
+  int32_t wire;     /* intsgd_wire */
+  int32_t clip;
+  uint32_t step;
+  uint64_t seed;
+} intsgd_desc;
+
+/* Bytes of DEVICE scratch (256-byte aligned) that any entry point taking a
+ * workspace needs for this descriptor; 0 if the descriptor is invalid.  The
+ * contents need not be initialised and are not meaningful afterwards. */
+size_t intsgd_workspace_bytes(const intsgd_desc* desc);
+
+/* Validates the descriptor and builds the library's tile table for its partition
+ * now (the only call that may allocate device memory), so that later calls on
+ * this partition only enqueue kernels.  Optional. */
+intsgd_status intsgd_prepare(const intsgd_desc* desc);
+
+/* Frees every cached tile table on every device.  Must not run concurrently with
+ * other calls. */
+void intsgd_release(void);
+
+/*
+ * a1-a3 (Algorithm 1 "scale and round the local gradient"; Algorithm 2 with B > 1).
+ *   grads     HOST array of n DEVICE pointers, each d floats (read only).
+ *   alpha     DEVICE float[B], alpha_k (per block).
+ *   q_out     HOST array of n DEVICE pointers, each d int8_t or int32_t per desc->wire.
+ *   sat_count DEVICE uint64_t[n], overwritten: clipped or non-finite coordinates per worker.
+ */
+intsgd_status intsgd_compress(const intsgd_desc* desc, const float* const* grads,
+                              const float* alpha, void* const* q_out, uint64_t* sat_count,
+                              void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * a4 (Algorithm 1 aggregation line, on one device): sum_out[j] = sum_i q[i][j].
+ *   q        HOST array of n DEVICE pointers to int8_t or int32_t vectors (desc->wire).
+ *   sum_out  DEVICE int32_t[d].  Exact whenever |q| <= desc->clip.
+ */
+intsgd_status intsgd_int_sum(const intsgd_desc* desc, const void* const* q, int32_t* sum_out,
+                             void* hip_stream);
+
+/*
+ * a5-a6 (Algorithm 1 estimator and update lines): in fp64 per coordinate,
+ * c = eta / (n alpha), x <- fl32(x - c S).
+ *   sum         DEVICE int32_t[d];  alpha DEVICE float[B];  eta > 0 finite.
+ *   x           DEVICE float[d], updated in place.
+ *   gtilde_out  DEVICE float[d] or NULL: g~ = fl32(S / (n alpha)).
+ */
+intsgd_status intsgd_decode_update(const intsgd_desc* desc, const int32_t* sum,
+                                   const float* alpha, double eta, float* x, float* gtilde_out,
+                                   void* hip_stream);
+
+/*
+ * a7 (Algorithm 1 / 2 moving-average line's norm): norm_sq_out[l] =
+ * sum over block l of (x_new[j] - x_old[j])^2, fp64 accumulation of the stored
+ * fp32 iterates.  norm_sq_out: DEVICE double[B], overwritten.
+ */
+intsgd_status intsgd_update_norm(const intsgd_desc* desc, const float* x_new, const float* x_old,
+                                 double* norm_sq_out, void* workspace, size_t workspace_bytes,
+                                 void* hip_stream);
+
+/*
+ * a8 (Section 4.1, Proposition 2; Algorithm 2 for B > 1), fp64:
+ *   r[l] <- beta r[l] + (1-beta) norm_sq[l]
+ *   B == 1: alpha = sqrt(d) / sqrt(2 n r / eta^2 + eps^2)
+ *   B  > 1: alpha_l = eta sqrt(d_l) / sqrt(2 n r_l + eta^2 (d_l/d) eps^2)
+ *   norm_sq DEVICE double[B]; r DEVICE double[B] in/out; alpha_out DEVICE float[B].
+ *   0 <= beta < 1, eps >= 0, eta > 0.  A zero denominator (r = 0 and eps = 0)
+ *   yields alpha = +Inf on the device: every coordinate then saturates and is counted.
+ */
+intsgd_status intsgd_next_alpha(const intsgd_desc* desc, const double* norm_sq, double* r,
+                                double beta, double eps, double eta, float* alpha_out,
+                                void* hip_stream);
+
+/* Host twin of intsgd_next_alpha: same arithmetic on HOST arrays, no device
+ * involved.  Returns INTSGD_ERANGE (and still writes +Inf) on a zero denominator. */
+intsgd_status intsgd_next_alpha_host(const intsgd_desc* desc, const double* norm_sq, double* r,
+                                     double beta, double eps, double eta, float* alpha_out);
+
+/*
+ * F1 = a1-a4 in one pass over the n gradient streams: sum_out DEVICE int32_t[d],
+ * sat_count DEVICE uint64_t[n].  Bit-identical to intsgd_compress + intsgd_int_sum.
+ */
+intsgd_status intsgd_compress_sum(const intsgd_desc* desc, const float* const* grads,
+                                  const float* alpha, int32_t* sum_out, uint64_t* sat_count,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * F2 = a5-a7 in one pass over S and x: x updated in place, norm_sq_out DEVICE
+ * double[B] = ||x_new - x_old||^2 per block.  Same x as intsgd_decode_update.
+ */
+intsgd_status intsgd_decode_update_norm(const intsgd_desc* desc, const int32_t* sum,
+                                        const float* alpha, double eta, float* x,
+                                        double* norm_sq_out, void* workspace,
+                                        size_t workspace_bytes, void* hip_stream);
+
+/*
+ * F3 = a1-a7 in a single sweep (the aggregate never leaves registers; legal on one
+ * device because no real all-reduce separates a4 from a5).  Same x, norms and
+ * counts as F1 followed by F2.
+ */
+intsgd_status intsgd_step_fused(const intsgd_desc* desc, const float* const* grads,
+                                const float* alpha, double eta, float* x, double* norm_sq_out,
+                                uint64_t* sat_count, void* workspace, size_t workspace_bytes,
+                                void* hip_stream);
+
+/* Tuning knobs (process-wide; not part of the numerical contract: results do not
+ * depend on them except for the summation order of the norm).  tile_coords:
+ * coordinates per work tile, a multiple of 1024 in [1024, 65536].  max_workgroups:
+ * cap of the launch grid, in [1, 16384].  0 keeps the current value. */
+intsgd_status intsgd_set_tuning(uint32_t tile_coords, uint32_t max_workgroups);
+void intsgd_get_tuning(uint32_t* tile_coords, uint32_t* max_workgroups);
+
+const char* intsgd_status_string(intsgd_status status);
+/* Text of the last HIP error seen by this thread's calls ("" if none). */
+const char* intsgd_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* INTSGD_H_ */

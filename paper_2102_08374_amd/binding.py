@@ -1,0 +1,255 @@
+"""ctypes binding of libintsgd.so -- same names as include/intsgd.h, marshalling only.
+
+Tensors are torch tensors on the current HIP device (torch.cuda); every call
+enqueues on torch's current stream unless ``stream`` (a raw hipStream_t handle,
+e.g. ``torch.cuda.Stream().cuda_stream``) is given.  A non-OK status raises
+IntSGDError.  There is no fallback: if the library is missing, importing fails.
+"""
+import ctypes as C
+import os
+
+import torch
+
+__all__ = [
+    "IntSGDError", "Desc", "ROUND_NEAREST_EVEN", "ROUND_STOCHASTIC", "WIRE_INT8", "WIRE_INT32",
+    "MAX_WORKERS", "default_clip", "library_path", "intsgd_workspace_bytes", "intsgd_prepare",
+    "intsgd_release", "intsgd_compress", "intsgd_int_sum", "intsgd_decode_update",
+    "intsgd_update_norm", "intsgd_next_alpha", "intsgd_next_alpha_host", "intsgd_compress_sum",
+    "intsgd_decode_update_norm", "intsgd_step_fused", "intsgd_set_tuning", "intsgd_get_tuning",
+    "intsgd_status_string", "new_workspace", "EXPORTED_SYMBOLS",
+]
+
+ROUND_NEAREST_EVEN = 0
+ROUND_STOCHASTIC = 1
+WIRE_INT8 = 8
+WIRE_INT32 = 32
+MAX_WORKERS = 128
+
+EXPORTED_SYMBOLS = [
+    "intsgd_workspace_bytes", "intsgd_prepare", "intsgd_release", "intsgd_compress",
+    "intsgd_int_sum", "intsgd_decode_update", "intsgd_update_norm", "intsgd_next_alpha",
+    "intsgd_next_alpha_host", "intsgd_compress_sum", "intsgd_decode_update_norm",
+    "intsgd_step_fused", "intsgd_set_tuning", "intsgd_get_tuning", "intsgd_status_string",
+    "intsgd_last_hip_error",
+]
+
+
+def library_path() -> str:
+    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libintsgd.so")
+
+
+def _load():
+    path = library_path()
+    if not os.path.exists(path):
+        raise ImportError(
+            "%s is not built; run `python -m paper_2102_08374_amd.build` "
+            "(or __graft_entry__.build()) first" % path)
+    return C.CDLL(path)
+
+
+_lib = _load()
+
+
+class _CDesc(C.Structure):
+    _fields_ = [("d", C.c_uint64), ("n", C.c_uint32), ("num_blocks", C.c_uint32),
+                ("block_offsets", C.POINTER(C.c_uint64)), ("rounding", C.c_int32),
+                ("wire", C.c_int32), ("clip", C.c_int32), ("step", C.c_uint32),
+                ("seed", C.c_uint64)]
+
+
+_P = C.c_void_p
+_DP = C.POINTER(_CDesc)
+_PP = C.POINTER(C.c_void_p)
+_lib.intsgd_workspace_bytes.argtypes = [_DP]
+_lib.intsgd_workspace_bytes.restype = C.c_size_t
+_lib.intsgd_prepare.argtypes = [_DP]
+_lib.intsgd_release.argtypes = []
+_lib.intsgd_release.restype = None
+_lib.intsgd_compress.argtypes = [_DP, _PP, _P, _PP, _P, _P, C.c_size_t, _P]
+_lib.intsgd_int_sum.argtypes = [_DP, _PP, _P, _P]
+_lib.intsgd_decode_update.argtypes = [_DP, _P, _P, C.c_double, _P, _P, _P]
+_lib.intsgd_update_norm.argtypes = [_DP, _P, _P, _P, _P, C.c_size_t, _P]
+_lib.intsgd_next_alpha.argtypes = [_DP, _P, _P, C.c_double, C.c_double, C.c_double, _P, _P]
+_lib.intsgd_next_alpha_host.argtypes = [_DP, C.POINTER(C.c_double), C.POINTER(C.c_double),
+                                        C.c_double, C.c_double, C.c_double, C.POINTER(C.c_float)]
+_lib.intsgd_compress_sum.argtypes = [_DP, _PP, _P, _P, _P, _P, C.c_size_t, _P]
+_lib.intsgd_decode_update_norm.argtypes = [_DP, _P, _P, C.c_double, _P, _P, _P, C.c_size_t, _P]
+_lib.intsgd_step_fused.argtypes = [_DP, _PP, _P, C.c_double, _P, _P, _P, _P, C.c_size_t, _P]
+_lib.intsgd_set_tuning.argtypes = [C.c_uint32, C.c_uint32]
+_lib.intsgd_get_tuning.argtypes = [C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
+_lib.intsgd_get_tuning.restype = None
+_lib.intsgd_status_string.argtypes = [C.c_int]
+_lib.intsgd_status_string.restype = C.c_char_p
+_lib.intsgd_last_hip_error.argtypes = []
+_lib.intsgd_last_hip_error.restype = C.c_char_p
+for _name in ("intsgd_prepare", "intsgd_compress", "intsgd_int_sum", "intsgd_decode_update",
+              "intsgd_update_norm", "intsgd_next_alpha", "intsgd_next_alpha_host",
+              "intsgd_compress_sum", "intsgd_decode_update_norm", "intsgd_step_fused",
+              "intsgd_set_tuning"):
+    getattr(_lib, _name).restype = C.c_int
+
+
+class IntSGDError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = int(status)
+        msg = _lib.intsgd_status_string(self.status).decode()
+        if self.status == -4:
+            msg += " (" + _lib.intsgd_last_hip_error().decode() + ")"
+        super().__init__("%s: %s [%d]" % (where, msg, self.status))
+
+
+def _check(status, where):
+    if status != 0:
+        raise IntSGDError(status, where)
+
+
+def default_clip(n: int, wire: int = WIRE_INT32) -> int:
+    """Largest per-worker bound whose n-fold sum fits the wire type (Section 5.1)."""
+    return ((1 << (wire - 1)) - 1) // max(1, int(n))
+
+
+class Desc:
+    """Problem statement of include/intsgd.h's intsgd_desc (keeps the offsets alive)."""
+
+    def __init__(self, d, n, *, rounding=ROUND_NEAREST_EVEN, wire=WIRE_INT32, clip=None, seed=0,
+                 step=0, block_offsets=None):
+        self._offsets = None
+        num_blocks = 1
+        ptr = None
+        if block_offsets is not None:
+            vals = [int(v) for v in block_offsets]
+            num_blocks = len(vals) - 1
+            self._offsets = (C.c_uint64 * len(vals))(*vals)
+            ptr = C.cast(self._offsets, C.POINTER(C.c_uint64))
+        if clip is None:
+            clip = default_clip(n, WIRE_INT32)
+        self.c = _CDesc(int(d), int(n), int(num_blocks), ptr, int(rounding), int(wire), int(clip),
+                        int(step) & 0xFFFFFFFF, int(seed) & 0xFFFFFFFFFFFFFFFF)
+
+    d = property(lambda self: self.c.d)
+    n = property(lambda self: self.c.n)
+    num_blocks = property(lambda self: self.c.num_blocks)
+    wire = property(lambda self: self.c.wire)
+
+    @property
+    def step(self):
+        return self.c.step
+
+    @step.setter
+    def step(self, k):
+        self.c.step = int(k) & 0xFFFFFFFF
+
+    def ref(self):
+        return C.byref(self.c)
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    return C.c_void_p(int(stream))
+
+
+def _ptr(t):
+    return C.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _ptr_array(tensors):
+    return (C.c_void_p * len(tensors))(*[t.data_ptr() for t in tensors])
+
+
+def _ws(workspace):
+    if workspace is None:
+        return C.c_void_p(0), 0
+    return C.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size()
+
+
+def intsgd_workspace_bytes(desc: Desc) -> int:
+    return int(_lib.intsgd_workspace_bytes(desc.ref()))
+
+
+def new_workspace(desc: Desc, device="cuda") -> torch.Tensor:
+    nbytes = intsgd_workspace_bytes(desc)
+    if nbytes == 0:
+        raise IntSGDError(-1, "intsgd_workspace_bytes")
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def intsgd_prepare(desc: Desc):
+    _check(_lib.intsgd_prepare(desc.ref()), "intsgd_prepare")
+
+
+def intsgd_release():
+    _lib.intsgd_release()
+
+
+def intsgd_compress(desc, grads, alpha, q_out, sat_count, workspace, stream=None):
+    w, wb = _ws(workspace)
+    _check(_lib.intsgd_compress(desc.ref(), _ptr_array(grads), _ptr(alpha), _ptr_array(q_out),
+                                _ptr(sat_count), w, wb, _stream(stream)), "intsgd_compress")
+
+
+def intsgd_int_sum(desc, q, sum_out, stream=None):
+    _check(_lib.intsgd_int_sum(desc.ref(), _ptr_array(q), _ptr(sum_out), _stream(stream)),
+           "intsgd_int_sum")
+
+
+def intsgd_decode_update(desc, sum_, alpha, eta, x, gtilde_out=None, stream=None):
+    _check(_lib.intsgd_decode_update(desc.ref(), _ptr(sum_), _ptr(alpha), float(eta), _ptr(x),
+                                     _ptr(gtilde_out), _stream(stream)), "intsgd_decode_update")
+
+
+def intsgd_update_norm(desc, x_new, x_old, norm_sq_out, workspace, stream=None):
+    w, wb = _ws(workspace)
+    _check(_lib.intsgd_update_norm(desc.ref(), _ptr(x_new), _ptr(x_old), _ptr(norm_sq_out), w, wb,
+                                   _stream(stream)), "intsgd_update_norm")
+
+
+def intsgd_next_alpha(desc, norm_sq, r, beta, eps, eta, alpha_out, stream=None):
+    _check(_lib.intsgd_next_alpha(desc.ref(), _ptr(norm_sq), _ptr(r), float(beta), float(eps),
+                                  float(eta), _ptr(alpha_out), _stream(stream)),
+           "intsgd_next_alpha")
+
+
+def intsgd_next_alpha_host(desc, norm_sq, r, beta, eps, eta):
+    """Host twin: lists/arrays of B doubles -> (status, r_new list, alpha list of fp32 values)."""
+    B = desc.num_blocks
+    ns = (C.c_double * B)(*[float(v) for v in norm_sq])
+    rr = (C.c_double * B)(*[float(v) for v in r])
+    al = (C.c_float * B)()
+    st = _lib.intsgd_next_alpha_host(desc.ref(), ns, rr, float(beta), float(eps), float(eta), al)
+    return int(st), list(rr), list(al)
+
+
+def intsgd_compress_sum(desc, grads, alpha, sum_out, sat_count, workspace, stream=None):
+    w, wb = _ws(workspace)
+    _check(_lib.intsgd_compress_sum(desc.ref(), _ptr_array(grads), _ptr(alpha), _ptr(sum_out),
+                                    _ptr(sat_count), w, wb, _stream(stream)),
+           "intsgd_compress_sum")
+
+
+def intsgd_decode_update_norm(desc, sum_, alpha, eta, x, norm_sq_out, workspace, stream=None):
+    w, wb = _ws(workspace)
+    _check(_lib.intsgd_decode_update_norm(desc.ref(), _ptr(sum_), _ptr(alpha), float(eta), _ptr(x),
+                                          _ptr(norm_sq_out), w, wb, _stream(stream)),
+           "intsgd_decode_update_norm")
+
+
+def intsgd_step_fused(desc, grads, alpha, eta, x, norm_sq_out, sat_count, workspace, stream=None):
+    w, wb = _ws(workspace)
+    _check(_lib.intsgd_step_fused(desc.ref(), _ptr_array(grads), _ptr(alpha), float(eta), _ptr(x),
+                                  _ptr(norm_sq_out), _ptr(sat_count), w, wb, _stream(stream)),
+           "intsgd_step_fused")
+
+
+def intsgd_set_tuning(tile_coords=0, max_workgroups=0):
+    _check(_lib.intsgd_set_tuning(int(tile_coords), int(max_workgroups)), "intsgd_set_tuning")
+
+
+def intsgd_get_tuning():
+    t, g = C.c_uint32(0), C.c_uint32(0)
+    _lib.intsgd_get_tuning(C.byref(t), C.byref(g))
+    return int(t.value), int(g.value)
+
+
+def intsgd_status_string(status: int) -> str:
+    return _lib.intsgd_status_string(int(status)).decode()

@@ -1,0 +1,475 @@
+// Host side of the C ABI declared in include/intsgd.h: argument validation (always
+// before anything touches the device), the tiling plan and its per-partition device
+// table, workspace carving, and the sequencing of kernel launches.
+
+#include <hip/hip_runtime_api.h>
+
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <list>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "intsgd.h"
+#include "intsgd_internal.h"
+
+namespace intsgd {
+namespace {
+
+constexpr uint32_t kMinTile = 1024;
+constexpr uint32_t kMaxTile = 65536;
+constexpr uint32_t kMaxGrid = 16384;
+constexpr uint64_t kMaxD = 1ull << 40;
+constexpr size_t kAlign = 256;
+
+uint32_t g_tile = 4096;
+uint32_t g_max_grid = 8192;
+
+thread_local std::string t_hip_error;
+
+intsgd_status hip_fail(hipError_t e) {
+  t_hip_error = std::string(hipGetErrorName(e)) + ": " + hipGetErrorString(e);
+  return INTSGD_EHIP;
+}
+
+size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+intsgd_status validate_desc(const intsgd_desc* desc) {
+  if (desc == nullptr) return INTSGD_EINVAL;
+  if (desc->d == 0 || desc->n == 0 || desc->num_blocks == 0) return INTSGD_EINVAL;
+  if (desc->d > kMaxD) return INTSGD_ERANGE;
+  if (desc->n > INTSGD_MAX_WORKERS) return INTSGD_ERANGE;
+  if (desc->num_blocks > desc->d) return INTSGD_EINVAL;
+  if (desc->rounding != INTSGD_ROUND_NEAREST_EVEN && desc->rounding != INTSGD_ROUND_STOCHASTIC)
+    return INTSGD_EINVAL;
+  if (desc->wire != INTSGD_WIRE_INT8 && desc->wire != INTSGD_WIRE_INT32) return INTSGD_EINVAL;
+  if (desc->clip < 1) return INTSGD_ERANGE;
+  if ((int64_t)desc->n * (int64_t)desc->clip > (int64_t)INT32_MAX) return INTSGD_ERANGE;
+  if (desc->wire == INTSGD_WIRE_INT8 && desc->clip > 127) return INTSGD_ERANGE;
+  if (desc->num_blocks > 1 || desc->block_offsets != nullptr) {
+    const uint64_t* off = desc->block_offsets;
+    if (off == nullptr) return INTSGD_EINVAL;
+    if (off[0] != 0 || off[desc->num_blocks] != desc->d) return INTSGD_EINVAL;
+    for (uint32_t l = 0; l < desc->num_blocks; ++l)
+      if (off[l + 1] <= off[l]) return INTSGD_EINVAL;
+  }
+  return INTSGD_OK;
+}
+
+intsgd_status validate_rule(double beta, double eps, double eta) {
+  if (!(beta >= 0.0 && beta < 1.0)) return INTSGD_EINVAL;
+  if (!(eps >= 0.0) || !std::isfinite(eps)) return INTSGD_EINVAL;
+  if (!(eta > 0.0) || !std::isfinite(eta)) return INTSGD_EINVAL;
+  return INTSGD_OK;
+}
+
+intsgd_status validate_worker_ptrs(const void* const* ptrs, uint32_t n) {
+  if (ptrs == nullptr) return INTSGD_EINVAL;
+  for (uint32_t i = 0; i < n; ++i) {
+    if (ptrs[i] == nullptr) return INTSGD_EINVAL;
+    if (!aligned16(ptrs[i])) return INTSGD_EALIGN;
+  }
+  return INTSGD_OK;
+}
+
+intsgd_status validate_vec(const void* p) {
+  if (p == nullptr) return INTSGD_EINVAL;
+  if (!aligned16(p)) return INTSGD_EALIGN;
+  return INTSGD_OK;
+}
+
+uint64_t tiles_of(uint64_t len, uint32_t tile) { return (len + tile - 1) / tile; }
+
+// Workspace carving; sized for the smallest tile and the largest grid so that it is
+// valid under any tuning.
+struct WorkspaceLayout {
+  size_t norm_bytes, sat_bytes, total;
+};
+
+WorkspaceLayout workspace_layout(const intsgd_desc* desc) {
+  WorkspaceLayout w;
+  const uint64_t max_tiles = tiles_of(desc->d, kMinTile) + desc->num_blocks;
+  w.norm_bytes = round_up((size_t)max_tiles * sizeof(double), kAlign);
+  w.sat_bytes = round_up((size_t)kMaxGrid * desc->n * sizeof(uint64_t), kAlign);
+  w.total = w.norm_bytes + w.sat_bytes;
+  return w;
+}
+
+intsgd_status validate_workspace(const intsgd_desc* desc, void* ws, size_t bytes) {
+  if (ws == nullptr) return INTSGD_EWORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(ws) & (kAlign - 1)) != 0) return INTSGD_EWORKSPACE;
+  if (bytes < workspace_layout(desc).total) return INTSGD_EWORKSPACE;
+  return INTSGD_OK;
+}
+
+double* ws_norm(void* ws) { return static_cast<double*>(ws); }
+uint64_t* ws_sat(const intsgd_desc* desc, void* ws) {
+  return reinterpret_cast<uint64_t*>(static_cast<char*>(ws) + workspace_layout(desc).norm_bytes);
+}
+
+RoundSpec round_spec(const intsgd_desc* desc) {
+  RoundSpec rs;
+  rs.rounding = desc->rounding;
+  rs.clip = desc->clip;
+  // smallest fp32 that is >= L+1 (L+1 itself need not be an fp32 number)
+  const double bound = (double)desc->clip + 1.0;
+  float thr = (float)bound;
+  if ((double)thr < bound) thr = std::nextafterf(thr, INFINITY);
+  rs.sat_threshold = thr;
+  rs.key0 = (uint32_t)desc->seed;
+  rs.key1 = (uint32_t)(desc->seed >> 32);
+  rs.step = desc->step;
+  return rs;
+}
+
+// ---------------------------------------------------------------- per-partition device table
+struct DevicePlan {
+  int device;
+  uint32_t tile;
+  uint64_t d;
+  std::vector<uint64_t> offsets;
+  uint32_t num_tiles;
+  TileEntry* table;        // device
+  uint32_t* tile_prefix;   // device, B+1
+  uint64_t* offsets_dev;   // device, B+1
+};
+
+std::mutex g_mutex;
+std::list<DevicePlan> g_plans;   // stable addresses: callers hold a pointer during their call
+
+void free_plan(DevicePlan& p) {
+  int cur = 0;
+  const bool have_cur = hipGetDevice(&cur) == hipSuccess;
+  if (hipSetDevice(p.device) == hipSuccess) {
+    (void)hipFree(p.table);
+    (void)hipFree(p.tile_prefix);
+    (void)hipFree(p.offsets_dev);
+  }
+  if (have_cur) (void)hipSetDevice(cur);
+}
+
+// Looks up or builds the device table of a multi-block partition.
+intsgd_status get_plan(const intsgd_desc* desc, uint32_t tile, const DevicePlan** out) {
+  int device = 0;
+  hipError_t e = hipGetDevice(&device);
+  if (e != hipSuccess) return hip_fail(e);
+  const uint32_t B = desc->num_blocks;
+  std::lock_guard<std::mutex> lock(g_mutex);
+  for (const DevicePlan& p : g_plans) {
+    if (p.device == device && p.tile == tile && p.d == desc->d && p.offsets.size() == B + 1 &&
+        std::memcmp(p.offsets.data(), desc->block_offsets, (B + 1) * sizeof(uint64_t)) == 0) {
+      *out = &p;
+      return INTSGD_OK;
+    }
+  }
+  std::vector<TileEntry> table;
+  std::vector<uint32_t> prefix(B + 1);
+  for (uint32_t l = 0; l < B; ++l) {
+    prefix[l] = (uint32_t)table.size();
+    const uint64_t s = desc->block_offsets[l], e2 = desc->block_offsets[l + 1];
+    for (uint64_t pos = s; pos < e2; pos += tile) {
+      const uint64_t len = (e2 - pos < tile) ? (e2 - pos) : tile;
+      table.push_back(TileEntry{pos, (uint32_t)len, l});
+    }
+  }
+  prefix[B] = (uint32_t)table.size();
+  DevicePlan p{};
+  p.device = device;
+  p.tile = tile;
+  p.d = desc->d;
+  p.offsets.assign(desc->block_offsets, desc->block_offsets + B + 1);
+  p.num_tiles = (uint32_t)table.size();
+  const size_t tb = table.size() * sizeof(TileEntry), pb = prefix.size() * sizeof(uint32_t),
+               ob = p.offsets.size() * sizeof(uint64_t);
+  e = hipMalloc((void**)&p.table, tb);
+  if (e == hipSuccess) e = hipMalloc((void**)&p.tile_prefix, pb);
+  if (e == hipSuccess) e = hipMalloc((void**)&p.offsets_dev, ob);
+  if (e == hipSuccess) e = hipMemcpy(p.table, table.data(), tb, hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemcpy(p.tile_prefix, prefix.data(), pb, hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemcpy(p.offsets_dev, p.offsets.data(), ob, hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    free_plan(p);
+    return hip_fail(e);
+  }
+  g_plans.push_back(std::move(p));
+  *out = &g_plans.back();
+  return INTSGD_OK;
+}
+
+// What a tiled launch needs: the map, the grid and (multi-block) the device tables.
+struct Tiling {
+  TileMap tm;
+  LaunchShape ls;
+  const uint32_t* tile_prefix;
+  const uint64_t* offsets_dev;
+};
+
+intsgd_status make_tiling(const intsgd_desc* desc, void* stream, Tiling* t) {
+  const uint32_t tile = g_tile;
+  t->tm.d = desc->d;
+  t->tm.tile = tile;
+  if (desc->num_blocks == 1) {
+    t->tm.num_tiles = (uint32_t)tiles_of(desc->d, tile);
+    t->tm.table = nullptr;
+    t->tile_prefix = nullptr;
+    t->offsets_dev = nullptr;
+  } else {
+    const DevicePlan* plan = nullptr;
+    const intsgd_status st = get_plan(desc, tile, &plan);
+    if (st != INTSGD_OK) return st;
+    t->tm.num_tiles = plan->num_tiles;
+    t->tm.table = plan->table;
+    t->tile_prefix = plan->tile_prefix;
+    t->offsets_dev = plan->offsets_dev;
+  }
+  t->ls.grid = t->tm.num_tiles < g_max_grid ? t->tm.num_tiles : g_max_grid;
+  t->ls.stream = static_cast<hipStream_t>(stream);
+  return INTSGD_OK;
+}
+
+void fill_ptrs(WorkerPtrs* w, const void* const* src, uint32_t n) {
+  std::memset(w, 0, sizeof(*w));
+  for (uint32_t i = 0; i < n; ++i) w->p[i] = src[i];
+}
+
+intsgd_status done(hipError_t e) { return e == hipSuccess ? INTSGD_OK : hip_fail(e); }
+
+#define INTSGD_TRY(expr)                        \
+  do {                                          \
+    const intsgd_status st_ = (expr);           \
+    if (st_ != INTSGD_OK) return st_;           \
+  } while (0)
+
+}  // namespace
+}  // namespace intsgd
+
+using namespace intsgd;
+
+extern "C" {
+
+size_t intsgd_workspace_bytes(const intsgd_desc* desc) {
+  if (validate_desc(desc) != INTSGD_OK) return 0;
+  return workspace_layout(desc).total;
+}
+
+intsgd_status intsgd_prepare(const intsgd_desc* desc) {
+  INTSGD_TRY(validate_desc(desc));
+  if (desc->num_blocks == 1) return INTSGD_OK;
+  const DevicePlan* plan = nullptr;
+  return get_plan(desc, g_tile, &plan);
+}
+
+void intsgd_release(void) {
+  std::lock_guard<std::mutex> lock(g_mutex);
+  for (DevicePlan& p : g_plans) free_plan(p);
+  g_plans.clear();
+}
+
+intsgd_status intsgd_compress(const intsgd_desc* desc, const float* const* grads,
+                              const float* alpha, void* const* q_out, uint64_t* sat_count,
+                              void* workspace, size_t workspace_bytes, void* hip_stream) {
+  INTSGD_TRY(validate_desc(desc));
+  INTSGD_TRY(validate_worker_ptrs((const void* const*)grads, desc->n));
+  INTSGD_TRY(validate_worker_ptrs((const void* const*)q_out, desc->n));
+  if (alpha == nullptr || sat_count == nullptr) return INTSGD_EINVAL;
+  INTSGD_TRY(validate_workspace(desc, workspace, workspace_bytes));
+  Tiling t;
+  INTSGD_TRY(make_tiling(desc, hip_stream, &t));
+  WorkerPtrs g;
+  WorkerOutPtrs q;
+  fill_ptrs(&g, (const void* const*)grads, desc->n);
+  std::memset(&q, 0, sizeof(q));
+  for (uint32_t i = 0; i < desc->n; ++i) q.p[i] = q_out[i];
+  uint64_t* sat_partial = ws_sat(desc, workspace);
+  hipError_t e = launch_compress(t.tm, t.ls, desc->n, desc->wire, round_spec(desc), g, alpha, q,
+                                 sat_partial);
+  if (e != hipSuccess) return hip_fail(e);
+  return done(launch_finalize(t.ls.stream, nullptr, nullptr, 0, 0, nullptr, sat_partial, t.ls.grid,
+                              desc->n, sat_count));
+}
+
+intsgd_status intsgd_int_sum(const intsgd_desc* desc, const void* const* q, int32_t* sum_out,
+                             void* hip_stream) {
+  INTSGD_TRY(validate_desc(desc));
+  INTSGD_TRY(validate_worker_ptrs(q, desc->n));
+  INTSGD_TRY(validate_vec(sum_out));
+  WorkerPtrs qp;
+  fill_ptrs(&qp, q, desc->n);
+  // about four quads per thread and pass of the grid-stride loop
+  const uint64_t want = tiles_of((desc->d >> 2) + 1, 256 * 4);
+  LaunchShape ls{(uint32_t)(want < g_max_grid ? want : g_max_grid),
+                 static_cast<hipStream_t>(hip_stream)};
+  return done(launch_int_sum(desc->d, ls, desc->n, desc->wire, qp, sum_out));
+}
+
+intsgd_status intsgd_decode_update(const intsgd_desc* desc, const int32_t* sum,
+                                   const float* alpha, double eta, float* x, float* gtilde_out,
+                                   void* hip_stream) {
+  INTSGD_TRY(validate_desc(desc));
+  INTSGD_TRY(validate_vec(sum));
+  INTSGD_TRY(validate_vec(x));
+  if (gtilde_out != nullptr) INTSGD_TRY(validate_vec(gtilde_out));
+  if (alpha == nullptr) return INTSGD_EINVAL;
+  INTSGD_TRY(validate_rule(0.0, 0.0, eta));
+  Tiling t;
+  INTSGD_TRY(make_tiling(desc, hip_stream, &t));
+  return done(launch_decode_update(t.tm, t.ls, desc->n, sum, alpha, eta, x, gtilde_out));
+}
+
+intsgd_status intsgd_update_norm(const intsgd_desc* desc, const float* x_new, const float* x_old,
+                                 double* norm_sq_out, void* workspace, size_t workspace_bytes,
+                                 void* hip_stream) {
+  INTSGD_TRY(validate_desc(desc));
+  INTSGD_TRY(validate_vec(x_new));
+  INTSGD_TRY(validate_vec(x_old));
+  if (norm_sq_out == nullptr) return INTSGD_EINVAL;
+  INTSGD_TRY(validate_workspace(desc, workspace, workspace_bytes));
+  Tiling t;
+  INTSGD_TRY(make_tiling(desc, hip_stream, &t));
+  hipError_t e = launch_update_norm(t.tm, t.ls, x_new, x_old, ws_norm(workspace));
+  if (e != hipSuccess) return hip_fail(e);
+  return done(launch_finalize(t.ls.stream, ws_norm(workspace), t.tile_prefix, t.tm.num_tiles,
+                              desc->num_blocks, norm_sq_out, nullptr, 0, 0, nullptr));
+}
+
+intsgd_status intsgd_next_alpha(const intsgd_desc* desc, const double* norm_sq, double* r,
+                                double beta, double eps, double eta, float* alpha_out,
+                                void* hip_stream) {
+  INTSGD_TRY(validate_desc(desc));
+  if (norm_sq == nullptr || r == nullptr || alpha_out == nullptr) return INTSGD_EINVAL;
+  INTSGD_TRY(validate_rule(beta, eps, eta));
+  const uint64_t* offsets_dev = nullptr;
+  if (desc->num_blocks > 1) {
+    const DevicePlan* plan = nullptr;
+    INTSGD_TRY(get_plan(desc, g_tile, &plan));
+    offsets_dev = plan->offsets_dev;
+  }
+  return done(launch_next_alpha(static_cast<hipStream_t>(hip_stream), norm_sq, r,
+                                desc->num_blocks, offsets_dev, desc->d, desc->n, beta, eps, eta,
+                                alpha_out));
+}
+
+intsgd_status intsgd_next_alpha_host(const intsgd_desc* desc, const double* norm_sq, double* r,
+                                     double beta, double eps, double eta, float* alpha_out) {
+  INTSGD_TRY(validate_desc(desc));
+  if (norm_sq == nullptr || r == nullptr || alpha_out == nullptr) return INTSGD_EINVAL;
+  INTSGD_TRY(validate_rule(beta, eps, eta));
+  const uint32_t B = desc->num_blocks;
+  bool zero_den = false;
+  for (uint32_t l = 0; l < B; ++l) {
+    const double keep = beta * r[l];
+    const double fresh = (1.0 - beta) * norm_sq[l];
+    const double rl = keep + fresh;
+    r[l] = rl;
+    double alpha;
+    if (B == 1) {
+      const double den = 2.0 * (double)desc->n * rl / (eta * eta) + eps * eps;
+      zero_den |= (den == 0.0);
+      alpha = std::sqrt((double)desc->d) / std::sqrt(den);
+    } else {
+      const double dl = (double)(desc->block_offsets[l + 1] - desc->block_offsets[l]);
+      const double den = 2.0 * (double)desc->n * rl + eta * eta * (dl / (double)desc->d) * eps * eps;
+      zero_den |= (den == 0.0);
+      alpha = eta * std::sqrt(dl) / std::sqrt(den);
+    }
+    alpha_out[l] = (float)alpha;
+  }
+  return zero_den ? INTSGD_ERANGE : INTSGD_OK;
+}
+
+intsgd_status intsgd_compress_sum(const intsgd_desc* desc, const float* const* grads,
+                                  const float* alpha, int32_t* sum_out, uint64_t* sat_count,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream) {
+  INTSGD_TRY(validate_desc(desc));
+  INTSGD_TRY(validate_worker_ptrs((const void* const*)grads, desc->n));
+  INTSGD_TRY(validate_vec(sum_out));
+  if (alpha == nullptr || sat_count == nullptr) return INTSGD_EINVAL;
+  INTSGD_TRY(validate_workspace(desc, workspace, workspace_bytes));
+  Tiling t;
+  INTSGD_TRY(make_tiling(desc, hip_stream, &t));
+  WorkerPtrs g;
+  fill_ptrs(&g, (const void* const*)grads, desc->n);
+  uint64_t* sat_partial = ws_sat(desc, workspace);
+  hipError_t e = launch_compress_sum(t.tm, t.ls, desc->n, round_spec(desc), g, alpha, sum_out,
+                                     sat_partial);
+  if (e != hipSuccess) return hip_fail(e);
+  return done(launch_finalize(t.ls.stream, nullptr, nullptr, 0, 0, nullptr, sat_partial, t.ls.grid,
+                              desc->n, sat_count));
+}
+
+intsgd_status intsgd_decode_update_norm(const intsgd_desc* desc, const int32_t* sum,
+                                        const float* alpha, double eta, float* x,
+                                        double* norm_sq_out, void* workspace,
+                                        size_t workspace_bytes, void* hip_stream) {
+  INTSGD_TRY(validate_desc(desc));
+  INTSGD_TRY(validate_vec(sum));
+  INTSGD_TRY(validate_vec(x));
+  if (alpha == nullptr || norm_sq_out == nullptr) return INTSGD_EINVAL;
+  INTSGD_TRY(validate_rule(0.0, 0.0, eta));
+  INTSGD_TRY(validate_workspace(desc, workspace, workspace_bytes));
+  Tiling t;
+  INTSGD_TRY(make_tiling(desc, hip_stream, &t));
+  hipError_t e = launch_decode_update_norm(t.tm, t.ls, desc->n, sum, alpha, eta, x,
+                                           ws_norm(workspace));
+  if (e != hipSuccess) return hip_fail(e);
+  return done(launch_finalize(t.ls.stream, ws_norm(workspace), t.tile_prefix, t.tm.num_tiles,
+                              desc->num_blocks, norm_sq_out, nullptr, 0, 0, nullptr));
+}
+
+intsgd_status intsgd_step_fused(const intsgd_desc* desc, const float* const* grads,
+                                const float* alpha, double eta, float* x, double* norm_sq_out,
+                                uint64_t* sat_count, void* workspace, size_t workspace_bytes,
+                                void* hip_stream) {
+  INTSGD_TRY(validate_desc(desc));
+  INTSGD_TRY(validate_worker_ptrs((const void* const*)grads, desc->n));
+  INTSGD_TRY(validate_vec(x));
+  if (alpha == nullptr || norm_sq_out == nullptr || sat_count == nullptr) return INTSGD_EINVAL;
+  INTSGD_TRY(validate_rule(0.0, 0.0, eta));
+  INTSGD_TRY(validate_workspace(desc, workspace, workspace_bytes));
+  Tiling t;
+  INTSGD_TRY(make_tiling(desc, hip_stream, &t));
+  WorkerPtrs g;
+  fill_ptrs(&g, (const void* const*)grads, desc->n);
+  uint64_t* sat_partial = ws_sat(desc, workspace);
+  hipError_t e = launch_step_fused(t.tm, t.ls, desc->n, round_spec(desc), g, alpha, eta, x,
+                                   ws_norm(workspace), sat_partial);
+  if (e != hipSuccess) return hip_fail(e);
+  return done(launch_finalize(t.ls.stream, ws_norm(workspace), t.tile_prefix, t.tm.num_tiles,
+                              desc->num_blocks, norm_sq_out, sat_partial, t.ls.grid, desc->n,
+                              sat_count));
+}
+
+intsgd_status intsgd_set_tuning(uint32_t tile_coords, uint32_t max_workgroups) {
+  if (tile_coords != 0 &&
+      (tile_coords < kMinTile || tile_coords > kMaxTile || tile_coords % kMinTile != 0))
+    return INTSGD_EINVAL;
+  if (max_workgroups > kMaxGrid) return INTSGD_EINVAL;
+  std::lock_guard<std::mutex> lock(g_mutex);
+  if (tile_coords != 0) g_tile = tile_coords;
+  if (max_workgroups != 0) g_max_grid = max_workgroups;
+  return INTSGD_OK;
+}
+
+void intsgd_get_tuning(uint32_t* tile_coords, uint32_t* max_workgroups) {
+  if (tile_coords) *tile_coords = g_tile;
+  if (max_workgroups) *max_workgroups = g_max_grid;
+}
+
+const char* intsgd_status_string(intsgd_status status) {
+  switch (status) {
+    case INTSGD_OK: return "ok";
+    case INTSGD_EINVAL: return "invalid argument";
+    case INTSGD_EALIGN: return "vector pointer not 16-byte aligned";
+    case INTSGD_ERANGE: return "value out of range";
+    case INTSGD_EHIP: return "HIP runtime error";
+    case INTSGD_EWORKSPACE: return "workspace missing, misaligned or too small";
+  }
+  return "unknown status";
+}
+
+const char* intsgd_last_hip_error(void) { return t_hip_error.c_str(); }
+
+}  // extern "C"

@@ -1,0 +1,770 @@
+// HIP kernels of the IntSGD step for gfx950 (CDNA4, 64-wide wavefronts).
+//
+// The whole path is a streaming scan (no reuse, no dense contraction), so the
+// design goal is HBM bandwidth: every thread moves 16 bytes per stream per
+// iteration (dwordx4), the n gradient streams are read with non-temporal loads
+// in groups of up to 8 independent loads in flight per lane, base addresses are
+// wave-uniform (SGPR) with a 32-bit lane offset, the integer aggregate stays in
+// registers in the fused forms, and the only cross-lane traffic is the norm
+// reduction (DPP inside a wavefront, then LDS across the four wavefronts).
+//
+// Work is cut into tiles of `tile` coordinates that never straddle a block of
+// Algorithm 2, so alpha is wave-uniform inside a tile.  A tile whose ends are not
+// multiples of four coordinates handles its <= 3 head and <= 3 tail coordinates
+// one by one; everything in between moves as aligned quads.
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "intsgd_internal.h"
+
+namespace intsgd {
+namespace {
+
+constexpr uint32_t kThreads = 256;
+constexpr uint32_t kWaves = kThreads / 64;
+
+// Native 16-byte vectors (one dwordx4 access each).
+typedef float vf4 __attribute__((ext_vector_type(4)));
+typedef int32_t vi4 __attribute__((ext_vector_type(4)));
+typedef uint32_t vu4 __attribute__((ext_vector_type(4)));
+
+// ------------------------------------------------------------------ Philox4x32-10
+// Counter-based generator of Salmon et al. (SC'11), written from its description:
+// ten rounds of two 32x32->64 multiplies, a word permutation and key injection,
+// with the key bumped by Weyl constants between rounds.
+__device__ __forceinline__ vu4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                               uint32_t k0, uint32_t k1) {
+#pragma unroll
+  for (int round = 0; round < 10; ++round) {
+    const uint64_t p0 = (uint64_t)0xD2511F53u * (uint64_t)c0;
+    const uint64_t p1 = (uint64_t)0xCD9E8D57u * (uint64_t)c2;
+    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    c1 = (uint32_t)p1;
+    c3 = (uint32_t)p0;
+    c0 = n0;
+    c2 = n2;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  return vu4{c0, c1, c2, c3};
+}
+
+__device__ __forceinline__ uint32_t pick_word(const vu4& w, uint32_t c) {
+  return c == 0 ? w.x : (c == 1 ? w.y : (c == 2 ? w.z : w.w));
+}
+
+// ------------------------------------------------------------------ rounding + clip
+// v_cvt_i32_f32 saturates out-of-range inputs and maps NaN to 0, which is the clip
+// contract's behaviour; a C++ cast would be undefined there.
+__device__ __forceinline__ int32_t cvt_i32_saturating(float r) {
+  int32_t q;
+  asm("v_cvt_i32_f32_e32 %0, %1" : "=v"(q) : "v"(r));
+  return q;
+}
+
+__device__ __forceinline__ int32_t clamp_sym(int32_t q, int32_t L) {
+  return min(max(q, -L), L);
+}
+
+// Section 5.1 deterministic rounding (nearest, ties to even) of t = alpha*g, clipped
+// to [-L, L].  `sat` = the rounded value did not fit (or was not finite).
+__device__ __forceinline__ int32_t round_nearest_clip(float t, const RoundSpec& rs, bool& sat) {
+  const float r = __builtin_rintf(t);
+  sat = !(__builtin_fabsf(r) < rs.sat_threshold);
+  return clamp_sym(cvt_i32_saturating(r), rs.clip);
+}
+
+// Section 2 randomized rounding Int(t): floor(t)+1 with probability t-floor(t).  The
+// draw u = (word>>8) 2^-24 rounds up iff u < p, evaluated as (word>>8) < p 2^24 (both
+// sides exact in fp32).
+__device__ __forceinline__ int32_t round_random_clip(float t, uint32_t word, const RoundSpec& rs,
+                                                     bool& sat) {
+  const float f = __builtin_floorf(t);
+  const float p = t - f;
+  const bool up = (float)(word >> 8) < p * 16777216.0f;
+  const int32_t q = cvt_i32_saturating(f) + (up ? 1 : 0);   // up is false whenever |f| >= 2^24
+  const int32_t qc = clamp_sym(q, rs.clip);
+  sat = (qc != q) | !(__builtin_fabsf(f) < 2147483648.0f);
+  return qc;
+}
+
+template <int ROUND>
+__device__ __forceinline__ int32_t round_clip(float t, uint32_t word, const RoundSpec& rs,
+                                              bool& sat) {
+  if (ROUND == INTSGD_ROUND_STOCHASTIC) return round_random_clip(t, word, rs, sat);
+  return round_nearest_clip(t, rs, sat);
+}
+
+__device__ __forceinline__ uint32_t count_lanes(bool pred) {
+  return (uint32_t)__popcll(__ballot(pred));
+}
+
+// ------------------------------------------------------------------ reductions
+template <int CTRL>
+__device__ __forceinline__ double dpp_move(double v) {
+  int lo = __double2loint(v);
+  int hi = __double2hiint(v);
+  lo = __builtin_amdgcn_update_dpp(0, lo, CTRL, 0xF, 0xF, false);
+  hi = __builtin_amdgcn_update_dpp(0, hi, CTRL, 0xF, 0xF, false);
+  return __hiloint2double(hi, lo);
+}
+
+__device__ __forceinline__ double read_lane(double v, int lane) {
+  const int lo = __builtin_amdgcn_readlane(__double2loint(v), lane);
+  const int hi = __builtin_amdgcn_readlane(__double2hiint(v), lane);
+  return __hiloint2double(hi, lo);
+}
+
+// Sum over the 64 lanes of a wavefront; every lane must be active.  Four DPP steps
+// (quad swaps, half-row mirror, row mirror) leave each 16-lane row holding its row
+// sum; the four row sums are then read through SGPRs and added in a fixed order.
+__device__ __forceinline__ double wave_sum(double v) {
+  v += dpp_move<0xB1>(v);    // quad_perm [1,0,3,2]
+  v += dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]
+  v += dpp_move<0x141>(v);   // row_half_mirror
+  v += dpp_move<0x140>(v);   // row_mirror
+  return (read_lane(v, 0) + read_lane(v, 16)) + (read_lane(v, 32) + read_lane(v, 48));
+}
+
+// Sum over the workgroup; the result is valid in thread 0 only.  `slot` must
+// alternate between consecutive calls (double-buffered LDS, one barrier per call).
+__device__ __forceinline__ double block_sum(double v, double (*lds)[kWaves], uint32_t slot) {
+  const double w = wave_sum(v);
+  if ((threadIdx.x & 63u) == 0) lds[slot][threadIdx.x >> 6] = w;
+  __syncthreads();
+  double total = 0.0;
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (uint32_t k = 0; k < kWaves; ++k) total += lds[slot][k];
+  }
+  return total;
+}
+
+// ------------------------------------------------------------------ tiles
+struct Tile {
+  uint64_t start;
+  uint32_t len;
+  uint32_t blk;
+};
+
+__device__ __forceinline__ Tile locate(const TileMap& tm, uint32_t t) {
+  Tile tl;
+  if (tm.table != nullptr) {
+    const TileEntry e = tm.table[t];
+    tl.start = e.start;
+    tl.len = e.len;
+    tl.blk = e.blk;
+  } else {
+    tl.start = (uint64_t)t * tm.tile;
+    const uint64_t rest = tm.d - tl.start;
+    tl.len = rest < tm.tile ? (uint32_t)rest : tm.tile;
+    tl.blk = 0;
+  }
+  return tl;
+}
+
+// Runs `op` over this workgroup's tiles (grid-stride).  Op provides
+//   begin_tile(blk), scalar(j), begin_body(q0), quad(lane_quad), end_tile(t, iter).
+template <class Op>
+__device__ __forceinline__ void drive_tiles(const TileMap& tm, Op& op) {
+  const uint32_t tid = threadIdx.x;
+  uint32_t iter = 0;
+  for (uint32_t t = blockIdx.x; t < tm.num_tiles; t += gridDim.x, ++iter) {
+    const Tile tl = locate(tm, t);
+    const uint64_t s = tl.start, e = tl.start + tl.len;
+    uint64_t a = (s + 3) & ~(uint64_t)3;
+    if (a > e) a = e;
+    uint64_t b = e & ~(uint64_t)3;
+    if (b < a) b = a;
+    op.begin_tile(tl.blk);
+    if (s + tid < a) op.scalar(s + tid);
+    const uint32_t nq = (uint32_t)((b - a) >> 2);
+    op.begin_body(a >> 2);
+    for (uint32_t ql = tid; ql < nq; ql += kThreads) op.quad(ql);
+    if (b + tid < e) op.scalar(b + tid);
+    op.end_tile(t, iter);
+  }
+}
+
+template <class T>
+__device__ __forceinline__ T load_stream(const void* base, uint32_t byte_off) {
+  return __builtin_nontemporal_load((const T*)((const char*)base + byte_off));
+}
+template <class T>
+__device__ __forceinline__ T load_plain(const void* base, uint32_t byte_off) {
+  return *(const T*)((const char*)base + byte_off);
+}
+template <class T>
+__device__ __forceinline__ void store_plain(void* base, uint32_t byte_off, const T& v) {
+  *(T*)((char*)base + byte_off) = v;
+}
+
+// ------------------------------------------------------------------ a1-a4 on one quad
+// Scales, rounds, clips and accumulates workers [i0, i0+W) for the quad at lane byte
+// offset `off` (16 bytes per quad) from the per-worker uniform bases.
+template <int ROUND, int W>
+__device__ __forceinline__ void accumulate_workers(const WorkerPtrs& grads, uint32_t i0,
+                                                   uint64_t q0, uint32_t ql, float alpha,
+                                                   const RoundSpec& rs, vi4& S,
+                                                   unsigned long long* lds_sat) {
+  vf4 g[W];
+#pragma unroll
+  for (int w = 0; w < W; ++w)
+    g[w] = load_stream<vf4>((const vf4*)grads.p[i0 + w] + q0, ql * 16u);
+  const uint64_t quad = q0 + ql;
+#pragma unroll
+  for (int w = 0; w < W; ++w) {
+    vu4 rw = vu4{0u, 0u, 0u, 0u};
+    if (ROUND == INTSGD_ROUND_STOCHASTIC)
+      rw = philox4x32_10((uint32_t)quad, (uint32_t)(quad >> 32), i0 + w, rs.step, rs.key0, rs.key1);
+    bool s0, s1, s2, s3;
+    S.x += round_clip<ROUND>(alpha * g[w].x, rw.x, rs, s0);
+    S.y += round_clip<ROUND>(alpha * g[w].y, rw.y, rs, s1);
+    S.z += round_clip<ROUND>(alpha * g[w].z, rw.z, rs, s2);
+    S.w += round_clip<ROUND>(alpha * g[w].w, rw.w, rs, s3);
+    const uint32_t cnt = count_lanes(s0) + count_lanes(s1) + count_lanes(s2) + count_lanes(s3);
+    if (cnt != 0 && (threadIdx.x & 63u) == 0) atomicAdd(&lds_sat[i0 + w], (unsigned long long)cnt);
+  }
+}
+
+template <int ROUND>
+__device__ __forceinline__ vi4 aggregate_quad(const WorkerPtrs& grads, uint32_t n, uint64_t q0,
+                                               uint32_t ql, float alpha, const RoundSpec& rs,
+                                               unsigned long long* lds_sat) {
+  vi4 S = vi4{0, 0, 0, 0};
+  uint32_t i = 0;
+  for (; i + 8 <= n; i += 8) accumulate_workers<ROUND, 8>(grads, i, q0, ql, alpha, rs, S, lds_sat);
+  if (n - i >= 4) { accumulate_workers<ROUND, 4>(grads, i, q0, ql, alpha, rs, S, lds_sat); i += 4; }
+  if (n - i >= 2) { accumulate_workers<ROUND, 2>(grads, i, q0, ql, alpha, rs, S, lds_sat); i += 2; }
+  if (n - i >= 1) { accumulate_workers<ROUND, 1>(grads, i, q0, ql, alpha, rs, S, lds_sat); }
+  return S;
+}
+
+// One coordinate of one worker (head / tail of an unaligned tile).
+template <int ROUND>
+__device__ __forceinline__ int32_t compress_scalar(const void* g, uint64_t j, uint32_t worker,
+                                                   float alpha, const RoundSpec& rs, bool& sat) {
+  const float gv = ((const float*)g)[j];
+  uint32_t word = 0;
+  if (ROUND == INTSGD_ROUND_STOCHASTIC) {
+    const uint64_t quad = j >> 2;
+    const vu4 rw = philox4x32_10((uint32_t)quad, (uint32_t)(quad >> 32), worker, rs.step,
+                                   rs.key0, rs.key1);
+    word = pick_word(rw, (uint32_t)(j & 3));
+  }
+  return round_clip<ROUND>(alpha * gv, word, rs, sat);
+}
+
+template <int ROUND>
+__device__ __forceinline__ int32_t aggregate_scalar(const WorkerPtrs& grads, uint32_t n, uint64_t j,
+                                                    float alpha, const RoundSpec& rs,
+                                                    unsigned long long* lds_sat) {
+  int32_t S = 0;
+  for (uint32_t i = 0; i < n; ++i) {
+    bool sat;
+    S += compress_scalar<ROUND>(grads.p[i], j, i, alpha, rs, sat);
+    if (sat) atomicAdd(&lds_sat[i], 1ull);
+  }
+  return S;
+}
+
+// ------------------------------------------------------------------ a5-a7 on one coordinate
+// fp64: x_new = fl32(x - c S); returns x_new and adds (x_new - x)^2 to acc.
+__device__ __forceinline__ float update_coord(float x, int32_t S, double c, double& acc) {
+  const double xo = (double)x;
+  const double prod = c * (double)S;
+  const float xn = (float)(xo - prod);
+  const double delta = (double)xn - xo;
+  acc = __builtin_fma(delta, delta, acc);
+  return xn;
+}
+
+__device__ __forceinline__ double decode_constant(double eta, uint32_t n, float alpha) {
+  return eta / ((double)n * (double)alpha);
+}
+
+__device__ __forceinline__ void zero_sat(unsigned long long* lds_sat) {
+  if (threadIdx.x < INTSGD_MAX_WORKERS) lds_sat[threadIdx.x] = 0ull;
+  __syncthreads();
+}
+
+// sat_partial layout: [worker][workgroup].
+__device__ __forceinline__ void flush_sat(const unsigned long long* lds_sat, uint32_t n,
+                                          uint64_t* sat_partial) {
+  __syncthreads();
+  if (threadIdx.x < n) sat_partial[(uint64_t)threadIdx.x * gridDim.x + blockIdx.x] = lds_sat[threadIdx.x];
+}
+
+// ================================================================== F3: a1-a7
+struct StepArgs {
+  TileMap tm;
+  RoundSpec rs;
+  uint32_t n;
+  const float* alpha;
+  double eta;
+  float* x;
+  double* norm_partial;
+  uint64_t* sat_partial;
+  WorkerPtrs grads;
+};
+
+template <int ROUND>
+struct StepFusedOp {
+  const StepArgs& a;
+  unsigned long long* lds_sat;
+  double (*lds_red)[kWaves];
+  float alpha;
+  double c, acc;
+  uint64_t q0;
+
+  __device__ __forceinline__ void begin_tile(uint32_t blk) {
+    alpha = a.alpha[blk];
+    c = decode_constant(a.eta, a.n, alpha);
+    acc = 0.0;
+  }
+  __device__ __forceinline__ void scalar(uint64_t j) {
+    const int32_t S = aggregate_scalar<ROUND>(a.grads, a.n, j, alpha, a.rs, lds_sat);
+    a.x[j] = update_coord(a.x[j], S, c, acc);
+  }
+  __device__ __forceinline__ void begin_body(uint64_t first_quad) { q0 = first_quad; }
+  __device__ __forceinline__ void quad(uint32_t ql) {
+    vf4* xb = (vf4*)a.x + q0;
+    const vf4 xv = load_plain<vf4>(xb, ql * 16u);
+    const vi4 S = aggregate_quad<ROUND>(a.grads, a.n, q0, ql, alpha, a.rs, lds_sat);
+    vf4 xn;
+    xn.x = update_coord(xv.x, S.x, c, acc);
+    xn.y = update_coord(xv.y, S.y, c, acc);
+    xn.z = update_coord(xv.z, S.z, c, acc);
+    xn.w = update_coord(xv.w, S.w, c, acc);
+    store_plain(xb, ql * 16u, xn);
+  }
+  __device__ __forceinline__ void end_tile(uint32_t t, uint32_t iter) {
+    const double total = block_sum(acc, lds_red, iter & 1u);
+    if (threadIdx.x == 0) a.norm_partial[t] = total;
+  }
+};
+
+template <int ROUND>
+__global__ __launch_bounds__(kThreads) void k_step_fused(const StepArgs a) {
+  __shared__ unsigned long long lds_sat[INTSGD_MAX_WORKERS];
+  __shared__ double lds_red[2][kWaves];
+  zero_sat(lds_sat);
+  StepFusedOp<ROUND> op{a, lds_sat, lds_red, 0.f, 0.0, 0.0, 0};
+  drive_tiles(a.tm, op);
+  flush_sat(lds_sat, a.n, a.sat_partial);
+}
+
+// ================================================================== F1: a1-a4
+struct CompressSumArgs {
+  TileMap tm;
+  RoundSpec rs;
+  uint32_t n;
+  const float* alpha;
+  int32_t* sum_out;
+  uint64_t* sat_partial;
+  WorkerPtrs grads;
+};
+
+template <int ROUND>
+struct CompressSumOp {
+  const CompressSumArgs& a;
+  unsigned long long* lds_sat;
+  float alpha;
+  uint64_t q0;
+
+  __device__ __forceinline__ void begin_tile(uint32_t blk) { alpha = a.alpha[blk]; }
+  __device__ __forceinline__ void scalar(uint64_t j) {
+    a.sum_out[j] = aggregate_scalar<ROUND>(a.grads, a.n, j, alpha, a.rs, lds_sat);
+  }
+  __device__ __forceinline__ void begin_body(uint64_t first_quad) { q0 = first_quad; }
+  __device__ __forceinline__ void quad(uint32_t ql) {
+    const vi4 S = aggregate_quad<ROUND>(a.grads, a.n, q0, ql, alpha, a.rs, lds_sat);
+    store_plain((vi4*)a.sum_out + q0, ql * 16u, S);
+  }
+  __device__ __forceinline__ void end_tile(uint32_t, uint32_t) {}
+};
+
+template <int ROUND>
+__global__ __launch_bounds__(kThreads) void k_compress_sum(const CompressSumArgs a) {
+  __shared__ unsigned long long lds_sat[INTSGD_MAX_WORKERS];
+  zero_sat(lds_sat);
+  CompressSumOp<ROUND> op{a, lds_sat, 0.f, 0};
+  drive_tiles(a.tm, op);
+  flush_sat(lds_sat, a.n, a.sat_partial);
+}
+
+// ================================================================== a1-a3 (one worker per blockIdx.y)
+struct CompressArgs {
+  TileMap tm;
+  RoundSpec rs;
+  uint32_t n;
+  const float* alpha;
+  uint64_t* sat_partial;
+  WorkerPtrs grads;
+  WorkerOutPtrs q_out;
+};
+
+template <int ROUND, int WIRE>
+struct CompressOp {
+  const CompressArgs& a;
+  uint32_t worker;
+  const void* g;
+  void* q;
+  float alpha;
+  uint64_t q0;
+  uint32_t cnt;   // wave-uniform running clip count of this wavefront
+
+  __device__ __forceinline__ void begin_tile(uint32_t blk) { alpha = a.alpha[blk]; }
+  __device__ __forceinline__ void scalar(uint64_t j) {
+    bool sat;
+    const int32_t v = compress_scalar<ROUND>(g, j, worker, alpha, a.rs, sat);
+    if (WIRE == INTSGD_WIRE_INT8) ((int8_t*)q)[j] = (int8_t)v;
+    else ((int32_t*)q)[j] = v;
+    // the head/tail branch is divergent: count per lane through LDS-free atomics
+    if (sat) atomicAdd(&a.sat_partial[(uint64_t)worker * gridDim.x + blockIdx.x], 1ull);
+  }
+  __device__ __forceinline__ void begin_body(uint64_t first_quad) { q0 = first_quad; }
+  __device__ __forceinline__ void quad(uint32_t ql) {
+    const vf4 gv = load_stream<vf4>((const vf4*)g + q0, ql * 16u);
+    const uint64_t quad = q0 + ql;
+    vu4 rw = vu4{0u, 0u, 0u, 0u};
+    if (ROUND == INTSGD_ROUND_STOCHASTIC)
+      rw = philox4x32_10((uint32_t)quad, (uint32_t)(quad >> 32), worker, a.rs.step, a.rs.key0,
+                         a.rs.key1);
+    bool s0, s1, s2, s3;
+    vi4 v;
+    v.x = round_clip<ROUND>(alpha * gv.x, rw.x, a.rs, s0);
+    v.y = round_clip<ROUND>(alpha * gv.y, rw.y, a.rs, s1);
+    v.z = round_clip<ROUND>(alpha * gv.z, rw.z, a.rs, s2);
+    v.w = round_clip<ROUND>(alpha * gv.w, rw.w, a.rs, s3);
+    cnt += count_lanes(s0) + count_lanes(s1) + count_lanes(s2) + count_lanes(s3);
+    if (WIRE == INTSGD_WIRE_INT8) {
+      const uint32_t packed = ((uint32_t)v.x & 0xFFu) | (((uint32_t)v.y & 0xFFu) << 8) |
+                              (((uint32_t)v.z & 0xFFu) << 16) | (((uint32_t)v.w & 0xFFu) << 24);
+      store_plain((uint32_t*)q + q0, ql * 4u, packed);
+    } else {
+      store_plain((vi4*)q + q0, ql * 16u, v);
+    }
+  }
+  __device__ __forceinline__ void end_tile(uint32_t, uint32_t) {}
+};
+
+template <int ROUND, int WIRE>
+__global__ __launch_bounds__(kThreads) void k_compress(const CompressArgs a) {
+  const uint32_t worker = blockIdx.y;
+  uint64_t* slot = &a.sat_partial[(uint64_t)worker * gridDim.x + blockIdx.x];
+  if (threadIdx.x == 0) *slot = 0ull;
+  __syncthreads();
+  CompressOp<ROUND, WIRE> op{a, worker, a.grads.p[worker], a.q_out.p[worker], 0.f, 0, 0};
+  drive_tiles(a.tm, op);
+  if ((threadIdx.x & 63u) == 0 && op.cnt != 0) atomicAdd(slot, (unsigned long long)op.cnt);
+}
+
+// ================================================================== a4
+struct IntSumArgs {
+  uint64_t d;
+  uint32_t n;
+  int32_t* sum_out;
+  WorkerPtrs q;
+};
+
+template <int WIRE>
+__device__ __forceinline__ vi4 load_q4(const void* base, uint64_t quad) {
+  if (WIRE == INTSGD_WIRE_INT8) {
+    const uint32_t p = __builtin_nontemporal_load((const uint32_t*)base + quad);
+    return vi4{(int32_t)(int8_t)(p & 0xFFu), (int32_t)(int8_t)((p >> 8) & 0xFFu),
+               (int32_t)(int8_t)((p >> 16) & 0xFFu), (int32_t)(int8_t)(p >> 24)};
+  }
+  return __builtin_nontemporal_load((const vi4*)base + quad);
+}
+
+template <int WIRE>
+__global__ __launch_bounds__(kThreads) void k_int_sum(const IntSumArgs a) {
+  const uint64_t nq = a.d >> 2;
+  const uint64_t stride = (uint64_t)gridDim.x * kThreads;
+  for (uint64_t quad = (uint64_t)blockIdx.x * kThreads + threadIdx.x; quad < nq; quad += stride) {
+    vi4 S = vi4{0, 0, 0, 0};
+    for (uint32_t i = 0; i < a.n; ++i) {
+      const vi4 v = load_q4<WIRE>(a.q.p[i], quad);
+      S.x += v.x; S.y += v.y; S.z += v.z; S.w += v.w;
+    }
+    ((vi4*)a.sum_out)[quad] = S;
+  }
+  // the d mod 4 last coordinates
+  if (blockIdx.x == 0) {
+    const uint64_t j = (nq << 2) + threadIdx.x;
+    if (j < a.d) {
+      int32_t S = 0;
+      for (uint32_t i = 0; i < a.n; ++i)
+        S += (WIRE == INTSGD_WIRE_INT8) ? (int32_t)((const int8_t*)a.q.p[i])[j]
+                                        : ((const int32_t*)a.q.p[i])[j];
+      a.sum_out[j] = S;
+    }
+  }
+}
+
+// ================================================================== a5-a6 (and F2 = a5-a7)
+struct DecodeArgs {
+  TileMap tm;
+  uint32_t n;
+  const int32_t* sum;
+  const float* alpha;
+  double eta;
+  float* x;
+  float* gtilde;         // decode_update only, may be null
+  double* norm_partial;  // F2 only
+};
+
+template <bool WITH_NORM, bool WITH_GTILDE>
+struct DecodeOp {
+  const DecodeArgs& a;
+  double (*lds_red)[kWaves];
+  double c, na, acc;
+  uint64_t q0;
+
+  __device__ __forceinline__ void begin_tile(uint32_t blk) {
+    const float alpha = a.alpha[blk];
+    na = (double)a.n * (double)alpha;
+    c = decode_constant(a.eta, a.n, alpha);
+    acc = 0.0;
+  }
+  __device__ __forceinline__ float gtilde_of(int32_t S) const { return (float)((double)S / na); }
+  __device__ __forceinline__ void scalar(uint64_t j) {
+    const int32_t S = a.sum[j];
+    a.x[j] = update_coord(a.x[j], S, c, acc);
+    if (WITH_GTILDE) a.gtilde[j] = gtilde_of(S);
+  }
+  __device__ __forceinline__ void begin_body(uint64_t first_quad) { q0 = first_quad; }
+  __device__ __forceinline__ void quad(uint32_t ql) {
+    vf4* xb = (vf4*)a.x + q0;
+    const vi4 S = load_stream<vi4>((const vi4*)a.sum + q0, ql * 16u);
+    const vf4 xv = load_plain<vf4>(xb, ql * 16u);
+    vf4 xn;
+    xn.x = update_coord(xv.x, S.x, c, acc);
+    xn.y = update_coord(xv.y, S.y, c, acc);
+    xn.z = update_coord(xv.z, S.z, c, acc);
+    xn.w = update_coord(xv.w, S.w, c, acc);
+    store_plain(xb, ql * 16u, xn);
+    if (WITH_GTILDE) {
+      const vf4 gt = vf4{gtilde_of(S.x), gtilde_of(S.y), gtilde_of(S.z), gtilde_of(S.w)};
+      store_plain((vf4*)a.gtilde + q0, ql * 16u, gt);
+    }
+  }
+  __device__ __forceinline__ void end_tile(uint32_t t, uint32_t iter) {
+    if (WITH_NORM) {
+      const double total = block_sum(acc, lds_red, iter & 1u);
+      if (threadIdx.x == 0) a.norm_partial[t] = total;
+    }
+  }
+};
+
+template <bool WITH_NORM, bool WITH_GTILDE>
+__global__ __launch_bounds__(kThreads) void k_decode(const DecodeArgs a) {
+  __shared__ double lds_red[2][kWaves];
+  DecodeOp<WITH_NORM, WITH_GTILDE> op{a, lds_red, 0.0, 0.0, 0.0, 0};
+  drive_tiles(a.tm, op);
+}
+
+// ================================================================== a7
+struct NormArgs {
+  TileMap tm;
+  const float* x_new;
+  const float* x_old;
+  double* norm_partial;
+};
+
+struct NormOp {
+  const NormArgs& a;
+  double (*lds_red)[kWaves];
+  double acc;
+  uint64_t q0;
+
+  __device__ __forceinline__ void add(float xn, float xo) {
+    const double delta = (double)xn - (double)xo;
+    acc = __builtin_fma(delta, delta, acc);
+  }
+  __device__ __forceinline__ void begin_tile(uint32_t) { acc = 0.0; }
+  __device__ __forceinline__ void scalar(uint64_t j) { add(a.x_new[j], a.x_old[j]); }
+  __device__ __forceinline__ void begin_body(uint64_t first_quad) { q0 = first_quad; }
+  __device__ __forceinline__ void quad(uint32_t ql) {
+    const vf4 n4 = load_stream<vf4>((const vf4*)a.x_new + q0, ql * 16u);
+    const vf4 o4 = load_stream<vf4>((const vf4*)a.x_old + q0, ql * 16u);
+    add(n4.x, o4.x); add(n4.y, o4.y); add(n4.z, o4.z); add(n4.w, o4.w);
+  }
+  __device__ __forceinline__ void end_tile(uint32_t t, uint32_t iter) {
+    const double total = block_sum(acc, lds_red, iter & 1u);
+    if (threadIdx.x == 0) a.norm_partial[t] = total;
+  }
+};
+
+__global__ __launch_bounds__(kThreads) void k_update_norm(const NormArgs a) {
+  __shared__ double lds_red[2][kWaves];
+  NormOp op{a, lds_red, 0.0, 0};
+  drive_tiles(a.tm, op);
+}
+
+// ================================================================== fixed-order final sums
+struct FinalizeArgs {
+  const double* norm_partial;
+  const uint32_t* tile_prefix;
+  uint32_t num_tiles;
+  uint32_t norm_blocks;   // B if norms are wanted, else 0
+  double* norm_sq_out;
+  const uint64_t* sat_partial;
+  uint32_t grid;
+  uint32_t n;             // n if counts are wanted, else 0
+  uint64_t* sat_count;
+};
+
+__global__ __launch_bounds__(kThreads) void k_finalize(const FinalizeArgs a) {
+  __shared__ double lds_red[2][kWaves];
+  __shared__ unsigned long long lds_cnt;
+  if (blockIdx.x < a.norm_blocks) {
+    const uint32_t l = blockIdx.x;
+    const uint32_t t0 = a.tile_prefix ? a.tile_prefix[l] : 0u;
+    const uint32_t t1 = a.tile_prefix ? a.tile_prefix[l + 1] : a.num_tiles;
+    double acc = 0.0;
+    for (uint32_t t = t0 + threadIdx.x; t < t1; t += kThreads) acc += a.norm_partial[t];
+    const double total = block_sum(acc, lds_red, 0);
+    if (threadIdx.x == 0) a.norm_sq_out[l] = total;
+  } else {
+    const uint32_t i = blockIdx.x - a.norm_blocks;
+    if (threadIdx.x == 0) lds_cnt = 0ull;
+    __syncthreads();
+    unsigned long long acc = 0ull;
+    for (uint32_t g = threadIdx.x; g < a.grid; g += kThreads)
+      acc += a.sat_partial[(uint64_t)i * a.grid + g];
+    if (acc != 0ull) atomicAdd(&lds_cnt, acc);
+    __syncthreads();
+    if (threadIdx.x == 0) a.sat_count[i] = lds_cnt;
+  }
+}
+
+// ================================================================== a8
+// Section 4.1 (Proposition 2) for one block, Algorithm 2 otherwise; fp64, same
+// operation order as written in the header.
+__global__ __launch_bounds__(kThreads) void k_next_alpha(const double* norm_sq, double* r, uint32_t B,
+                                                         const uint64_t* block_offsets, uint64_t d,
+                                                         uint32_t n, double beta, double eps,
+                                                         double eta, float* alpha_out) {
+  const uint32_t l = blockIdx.x * kThreads + threadIdx.x;
+  if (l >= B) return;
+  const double keep = beta * r[l];
+  const double fresh = (1.0 - beta) * norm_sq[l];
+  const double rl = keep + fresh;
+  r[l] = rl;
+  double alpha;
+  if (B == 1) {
+    const double den = 2.0 * (double)n * rl / (eta * eta) + eps * eps;
+    alpha = sqrt((double)d) / sqrt(den);
+  } else {
+    const double dl = (double)(block_offsets[l + 1] - block_offsets[l]);
+    const double den = 2.0 * (double)n * rl + eta * eta * (dl / (double)d) * eps * eps;
+    alpha = eta * sqrt(dl) / sqrt(den);
+  }
+  alpha_out[l] = (float)alpha;
+}
+
+inline hipError_t after_launch() { return hipGetLastError(); }
+
+}  // namespace
+
+// ------------------------------------------------------------------ launchers
+hipError_t launch_compress(const TileMap& tm, const LaunchShape& ls, uint32_t n, int32_t wire,
+                           const RoundSpec& rs, const WorkerPtrs& grads, const float* alpha,
+                           const WorkerOutPtrs& q_out, uint64_t* sat_partial) {
+  CompressArgs a{tm, rs, n, alpha, sat_partial, grads, q_out};
+  const dim3 grid(ls.grid, n), block(kThreads);
+  const bool random = rs.rounding == INTSGD_ROUND_STOCHASTIC;
+  if (wire == INTSGD_WIRE_INT8) {
+    if (random) hipLaunchKernelGGL((k_compress<1, 8>), grid, block, 0, ls.stream, a);
+    else hipLaunchKernelGGL((k_compress<0, 8>), grid, block, 0, ls.stream, a);
+  } else {
+    if (random) hipLaunchKernelGGL((k_compress<1, 32>), grid, block, 0, ls.stream, a);
+    else hipLaunchKernelGGL((k_compress<0, 32>), grid, block, 0, ls.stream, a);
+  }
+  return after_launch();
+}
+
+hipError_t launch_int_sum(uint64_t d, const LaunchShape& ls, uint32_t n, int32_t wire,
+                          const WorkerPtrs& q, int32_t* sum_out) {
+  IntSumArgs a{d, n, sum_out, q};
+  const dim3 grid(ls.grid), block(kThreads);
+  if (wire == INTSGD_WIRE_INT8) hipLaunchKernelGGL((k_int_sum<8>), grid, block, 0, ls.stream, a);
+  else hipLaunchKernelGGL((k_int_sum<32>), grid, block, 0, ls.stream, a);
+  return after_launch();
+}
+
+hipError_t launch_decode_update(const TileMap& tm, const LaunchShape& ls, uint32_t n,
+                                const int32_t* sum, const float* alpha, double eta, float* x,
+                                float* gtilde_out) {
+  DecodeArgs a{tm, n, sum, alpha, eta, x, gtilde_out, nullptr};
+  const dim3 grid(ls.grid), block(kThreads);
+  if (gtilde_out) hipLaunchKernelGGL((k_decode<false, true>), grid, block, 0, ls.stream, a);
+  else hipLaunchKernelGGL((k_decode<false, false>), grid, block, 0, ls.stream, a);
+  return after_launch();
+}
+
+hipError_t launch_update_norm(const TileMap& tm, const LaunchShape& ls, const float* x_new,
+                              const float* x_old, double* norm_partial) {
+  NormArgs a{tm, x_new, x_old, norm_partial};
+  hipLaunchKernelGGL(k_update_norm, dim3(ls.grid), dim3(kThreads), 0, ls.stream, a);
+  return after_launch();
+}
+
+hipError_t launch_compress_sum(const TileMap& tm, const LaunchShape& ls, uint32_t n,
+                               const RoundSpec& rs, const WorkerPtrs& grads, const float* alpha,
+                               int32_t* sum_out, uint64_t* sat_partial) {
+  CompressSumArgs a{tm, rs, n, alpha, sum_out, sat_partial, grads};
+  const dim3 grid(ls.grid), block(kThreads);
+  if (rs.rounding == INTSGD_ROUND_STOCHASTIC)
+    hipLaunchKernelGGL((k_compress_sum<1>), grid, block, 0, ls.stream, a);
+  else
+    hipLaunchKernelGGL((k_compress_sum<0>), grid, block, 0, ls.stream, a);
+  return after_launch();
+}
+
+hipError_t launch_decode_update_norm(const TileMap& tm, const LaunchShape& ls, uint32_t n,
+                                     const int32_t* sum, const float* alpha, double eta, float* x,
+                                     double* norm_partial) {
+  DecodeArgs a{tm, n, sum, alpha, eta, x, nullptr, norm_partial};
+  hipLaunchKernelGGL((k_decode<true, false>), dim3(ls.grid), dim3(kThreads), 0, ls.stream, a);
+  return after_launch();
+}
+
+hipError_t launch_step_fused(const TileMap& tm, const LaunchShape& ls, uint32_t n,
+                             const RoundSpec& rs, const WorkerPtrs& grads, const float* alpha,
+                             double eta, float* x, double* norm_partial, uint64_t* sat_partial) {
+  StepArgs a{tm, rs, n, alpha, eta, x, norm_partial, sat_partial, grads};
+  const dim3 grid(ls.grid), block(kThreads);
+  if (rs.rounding == INTSGD_ROUND_STOCHASTIC)
+    hipLaunchKernelGGL((k_step_fused<1>), grid, block, 0, ls.stream, a);
+  else
+    hipLaunchKernelGGL((k_step_fused<0>), grid, block, 0, ls.stream, a);
+  return after_launch();
+}
+
+hipError_t launch_finalize(hipStream_t stream, const double* norm_partial,
+                           const uint32_t* tile_prefix, uint32_t num_tiles, uint32_t B,
+                           double* norm_sq_out, const uint64_t* sat_partial, uint32_t grid,
+                           uint32_t n, uint64_t* sat_count) {
+  FinalizeArgs a{norm_partial, tile_prefix, num_tiles, norm_sq_out ? B : 0u, norm_sq_out,
+                 sat_partial, grid, sat_count ? n : 0u, sat_count};
+  const uint32_t blocks = a.norm_blocks + a.n;
+  if (blocks == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_finalize, dim3(blocks), dim3(kThreads), 0, stream, a);
+  return after_launch();
+}
+
+hipError_t launch_next_alpha(hipStream_t stream, const double* norm_sq, double* r, uint32_t B,
+                             const uint64_t* block_offsets, uint64_t d, uint32_t n, double beta,
+                             double eps, double eta, float* alpha_out) {
+  const uint32_t blocks = (B + kThreads - 1) / kThreads;
+  hipLaunchKernelGGL(k_next_alpha, dim3(blocks), dim3(kThreads), 0, stream, norm_sq, r, B,
+                     block_offsets, d, n, beta, eps, eta, alpha_out);
+  return after_launch();
+}
+
+}  // namespace intsgd

@@ -1,0 +1,175 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports every symbol
+the header declares, and rejects bad arguments before anything touches a device.
+No compute call is made here (there is no GPU in this environment)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2102_08374_amd as P
+from paper_2102_08374_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+lib = binding._lib
+
+OK, EINVAL, EALIGN, ERANGE, EHIP, EWORKSPACE = 0, -1, -2, -3, -4, -5
+FAKE = 0x7F0000001000        # aligned, never dereferenced: validation fails first
+FAKE_ODD = FAKE + 4
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "intsgd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(intsgd_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert len(names) >= 16
+    for name in names:
+        assert hasattr(lib, name), name
+    assert sorted(binding.EXPORTED_SYMBOLS) == names
+
+
+def test_python_binding_has_the_same_names():
+    for name in declared_functions():
+        if name == "intsgd_last_hip_error":
+            continue
+        assert hasattr(P, name), name
+
+
+def test_product_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2102_08374_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".cpp", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                where = os.path.join(dirpath, f)
+                assert not re.search(r"^\s*(import|from)\s+oracle\b", text, flags=re.M), where
+                assert not re.search(r"liboracle|oracle/|oracle_[a-z]+\s*\(", text), where
+
+
+def ptrs(n, value=FAKE):
+    return (C.c_void_p * n)(*[value + 0x1000 * i for i in range(n)])
+
+
+def call_step_fused(desc, grads=None, alpha=FAKE, eta=0.1, x=FAKE, ns=FAKE, sat=FAKE, ws=FAKE,
+                    ws_bytes=1 << 40):
+    n = max(1, min(desc.c.n, 128))
+    g = ptrs(n) if grads is None else grads
+    return lib.intsgd_step_fused(desc.ref(), g, alpha, eta, x, ns, sat, ws, ws_bytes, None)
+
+
+def test_descriptor_validation():
+    good = dict(d=1000, n=4)
+    assert P.intsgd_workspace_bytes(P.Desc(**good)) > 0
+    bad = [
+        (dict(d=0, n=4), EINVAL), (dict(d=1000, n=0), EINVAL), (dict(d=1000, n=129), ERANGE),
+        (dict(d=1 << 41, n=1), ERANGE),
+        (dict(d=1000, n=4, clip=0), ERANGE), (dict(d=1000, n=4, clip=-3), ERANGE),
+        (dict(d=1000, n=4, clip=(2**31 - 1) // 4 + 1), ERANGE),
+        (dict(d=1000, n=4, wire=8, clip=128), ERANGE),
+        (dict(d=1000, n=4, rounding=2), EINVAL), (dict(d=1000, n=4, wire=16), EINVAL),
+        (dict(d=1000, n=4, block_offsets=[0, 10, 10, 1000]), EINVAL),
+        (dict(d=1000, n=4, block_offsets=[0, 500, 400, 1000]), EINVAL),
+        (dict(d=1000, n=4, block_offsets=[1, 500, 1000]), EINVAL),
+        (dict(d=1000, n=4, block_offsets=[0, 500, 999]), EINVAL),
+    ]
+    for kw, want in bad:
+        desc = P.Desc(**kw)
+        assert P.intsgd_workspace_bytes(desc) == 0, kw
+        assert call_step_fused(desc) == want, kw
+        assert lib.intsgd_prepare(desc.ref()) == want, kw
+    # B > 1 without offsets, and B > d
+    desc = P.Desc(**good)
+    desc.c.num_blocks = 3
+    assert call_step_fused(desc) == EINVAL
+    assert lib.intsgd_step_fused(None, ptrs(1), FAKE, 0.1, FAKE, FAKE, FAKE, FAKE, 1 << 40, None) == EINVAL
+
+
+def test_pointer_alignment_eta_and_workspace_validation():
+    desc = P.Desc(1000, 4)
+    need = P.intsgd_workspace_bytes(desc)
+    assert call_step_fused(desc, grads=None, x=None) == EINVAL
+    assert call_step_fused(desc, x=FAKE_ODD) == EALIGN
+    assert call_step_fused(desc, grads=ptrs(4, FAKE_ODD)) == EALIGN
+    g = ptrs(4)
+    g[2] = None
+    assert call_step_fused(desc, grads=g) == EINVAL
+    assert lib.intsgd_step_fused(desc.ref(), None, FAKE, 0.1, FAKE, FAKE, FAKE, FAKE, need, None) == EINVAL
+    assert call_step_fused(desc, alpha=None) == EINVAL
+    assert call_step_fused(desc, ns=None) == EINVAL
+    assert call_step_fused(desc, sat=None) == EINVAL
+    for eta in (0.0, -0.1, float("nan"), float("inf")):
+        assert call_step_fused(desc, eta=eta) == EINVAL
+    assert call_step_fused(desc, ws=None) == EWORKSPACE
+    assert call_step_fused(desc, ws=FAKE + 16) == EWORKSPACE
+    assert call_step_fused(desc, ws_bytes=need - 1) == EWORKSPACE
+    # the other entry points share the same checks
+    assert lib.intsgd_compress(desc.ref(), ptrs(4), FAKE, ptrs(4, FAKE_ODD), FAKE, FAKE, need, None) == EALIGN
+    assert lib.intsgd_compress(desc.ref(), ptrs(4), FAKE, ptrs(4), None, FAKE, need, None) == EINVAL
+    assert lib.intsgd_int_sum(desc.ref(), ptrs(4), FAKE_ODD, None) == EALIGN
+    assert lib.intsgd_int_sum(desc.ref(), None, FAKE, None) == EINVAL
+    assert lib.intsgd_decode_update(desc.ref(), FAKE, FAKE, -1.0, FAKE, None, None) == EINVAL
+    assert lib.intsgd_decode_update(desc.ref(), FAKE, FAKE, 0.1, FAKE, FAKE_ODD, None) == EALIGN
+    assert lib.intsgd_decode_update(desc.ref(), None, FAKE, 0.1, FAKE, None, None) == EINVAL
+    assert lib.intsgd_update_norm(desc.ref(), FAKE, FAKE, None, FAKE, need, None) == EINVAL
+    assert lib.intsgd_update_norm(desc.ref(), FAKE, FAKE_ODD, FAKE, FAKE, need, None) == EALIGN
+    assert lib.intsgd_update_norm(desc.ref(), FAKE, FAKE, FAKE, FAKE, 8, None) == EWORKSPACE
+    assert lib.intsgd_compress_sum(desc.ref(), ptrs(4), FAKE, FAKE_ODD, FAKE, FAKE, need, None) == EALIGN
+    assert lib.intsgd_compress_sum(desc.ref(), ptrs(4), None, FAKE, FAKE, FAKE, need, None) == EINVAL
+    assert lib.intsgd_decode_update_norm(desc.ref(), FAKE, FAKE, 0.1, FAKE, FAKE, None, need, None) == EWORKSPACE
+    assert lib.intsgd_decode_update_norm(desc.ref(), FAKE, FAKE, 0.0, FAKE, FAKE, FAKE, need, None) == EINVAL
+    for beta, eps, eta in [(1.0, 1e-8, 0.1), (-0.1, 1e-8, 0.1), (0.9, -1.0, 0.1), (0.9, 1e-8, 0.0),
+                           (float("nan"), 0.0, 0.1)]:
+        assert lib.intsgd_next_alpha(desc.ref(), FAKE, FAKE, beta, eps, eta, FAKE, None) == EINVAL
+    assert lib.intsgd_next_alpha(desc.ref(), None, FAKE, 0.9, 1e-8, 0.1, FAKE, None) == EINVAL
+
+
+def test_tuning_knobs_are_validated():
+    tile, grid = P.intsgd_get_tuning()
+    for bad_tile in (1000, 512, 131072, 4097):
+        assert lib.intsgd_set_tuning(bad_tile, 0) == EINVAL
+    assert lib.intsgd_set_tuning(0, 16385) == EINVAL
+    assert P.intsgd_get_tuning() == (tile, grid)
+    P.intsgd_set_tuning(2048, 100)
+    assert P.intsgd_get_tuning() == (2048, 100)
+    P.intsgd_set_tuning(tile, grid)
+    # the workspace size does not depend on the tuning
+    desc = P.Desc(10**7, 8)
+    a = P.intsgd_workspace_bytes(desc)
+    P.intsgd_set_tuning(1024, 16384)
+    assert P.intsgd_workspace_bytes(desc) == a
+    P.intsgd_set_tuning(tile, grid)
+
+
+def test_status_strings():
+    for st in (0, -1, -2, -3, -4, -5):
+        assert P.intsgd_status_string(st) not in ("", "unknown status")
+    assert P.intsgd_status_string(-99) == "unknown status"
+    with pytest.raises(P.IntSGDError):
+        P.intsgd_prepare(P.Desc(0, 1))
+
+
+def test_host_alpha_rule_equals_the_oracle():
+    """The library's host twin of a8 against the oracle's (Section 4.1 / Algorithm 2)."""
+    rng = np.random.default_rng(2)
+    for offsets in (None, [0, 3, 700, 701, 5000]):
+        d, n = 5000, 6
+        B = 1 if offsets is None else len(offsets) - 1
+        off_np = None if offsets is None else np.array(offsets, np.uint64)
+        desc = P.Desc(d, n, block_offsets=offsets)
+        r = np.zeros(B)
+        for k in range(5):
+            ns = rng.uniform(1e-8, 1e-2, B)
+            st, r_h, a_h = P.intsgd_next_alpha_host(desc, ns, r, 0.9, 1e-8, 0.1)
+            r, ad, af, bad = oracle.next_alpha(ns, r, d=d, n=n, beta=0.9, eps=1e-8, eta=0.1,
+                                               offsets=off_np)
+            assert st == 0 and bad == 0
+            assert np.array_equal(np.array(r_h), r)
+            assert np.array_equal(np.array(a_h, np.float32), af)
+    st, _, a = P.intsgd_next_alpha_host(P.Desc(10, 1), [0.0], [0.0], 0.0, 0.0, 0.1)
+    assert st == ERANGE and np.isposinf(a[0])

@@ -1,0 +1,378 @@
+"""GPU parity: every entry point of the C ABI against the CPU oracle, element by element.
+
+Bars (written out where they are applied): integer vectors, aggregates and clip
+counts bit-exact; decoded gradient and updated parameters within 1 fp32 ulp;
+update norm and next alpha within 1e-5 relative.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2102_08374_amd as P
+from paper_2102_08374_amd import workloads as W
+from paper_2102_08374_amd.stepper import Stepper
+from tests.gpu_util import (F32, assert_within_ulp, host, rel_err, sprinkle_adversarial, u64)
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda"
+NORM_RTOL = 1e-5
+ALPHA_RTOL = 1e-5
+
+
+@pytest.fixture(autouse=True)
+def _default_tuning():
+    P.intsgd_set_tuning(4096, 8192)
+    yield
+    P.intsgd_set_tuning(4096, 8192)
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def rows_on_device(g):
+    """n separately allocated, 16-byte aligned device vectors."""
+    return [dev(g[i]) for i in range(g.shape[0])]
+
+
+SHAPES = [
+    # d, n, block offsets (None = one block), tile
+    (10007, 3, None, 1024),
+    (3 * 4096 + 5, 5, None, 4096),
+    (70001, 9, [0, 5, 1030, 1031, 40000, 70001], 1024),
+    (20480, 16, [0, 768, 8192, 20480], 4096),
+    (2, 1, None, 1024),
+    (4096 * 3, 8, None, 2048),
+    (33333, 7, [0, 33333], 1024),
+]
+
+
+def make_case(d, n, offsets, seed, alpha_scale=1.0):
+    rng = np.random.default_rng(seed)
+    B = 1 if offsets is None else len(offsets) - 1
+    alpha = (rng.uniform(50.0, 2000.0, B) * alpha_scale).astype(F32)
+    g = rng.normal(0.0, 0.01, (n, d)).astype(F32)
+    g = sprinkle_adversarial(rng, g, float(alpha[0]))
+    x = rng.normal(0.0, 1.0, d).astype(F32)
+    return alpha, g, x
+
+
+@pytest.mark.parametrize("rounding", [P.ROUND_NEAREST_EVEN, P.ROUND_STOCHASTIC])
+@pytest.mark.parametrize("wire,clip", [(P.WIRE_INT32, None), (P.WIRE_INT8, 127), (P.WIRE_INT8, 15),
+                                       (P.WIRE_INT32, 1)])
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "d%d-n%d" % (s[0], s[1]))
+def test_every_entry_point_matches_oracle(shape, wire, clip, rounding):
+    d, n, offsets, tile = shape
+    P.intsgd_set_tuning(tile, 8192)
+    L = P.default_clip(n) if clip is None else clip
+    seed, step, eta = 0x1234ABCD5678EF01, 11, 0.1
+    alpha, g, x = make_case(d, n, offsets, seed=d + n + rounding)
+    B = alpha.size
+    desc = P.Desc(d, n, rounding=rounding, wire=wire, clip=L, seed=seed, step=step,
+                  block_offsets=offsets)
+    ws = P.new_workspace(desc, DEV)
+    off_np = None if offsets is None else np.array(offsets, np.uint64)
+
+    # ---- oracle, stage by stage
+    o_q, o_cnt = [], []
+    for i in range(n):
+        q, c = oracle.compress(g[i], alpha, rounding=rounding, L=L, seed=seed, step=step, worker=i,
+                               offsets=off_np)
+        o_q.append(q)
+        o_cnt.append(c)
+    o_S, ovf = oracle.int_sum(o_q)
+    assert ovf == 0
+    o_x, o_gt = oracle.decode_update(o_S, alpha, x, n=n, eta=eta, offsets=off_np, want_gtilde=True)
+    o_ns = oracle.update_norm(o_x, x, offsets=off_np, B=B)
+    if d >= 1000:
+        assert sum(o_cnt) > 0      # the adversarial values do clip
+
+    # ---- a1-a3
+    d_alpha = dev(alpha)
+    d_g = rows_on_device(g)
+    qdt = torch.int8 if wire == P.WIRE_INT8 else torch.int32
+    d_q = [torch.full((d,), -77, dtype=qdt, device=DEV) for _ in range(n)]
+    d_cnt = torch.full((n,), -1, dtype=torch.int64, device=DEV)
+    P.intsgd_compress(desc, d_g, d_alpha, d_q, d_cnt, ws)
+    for i in range(n):
+        assert np.array_equal(host(d_q[i]).astype(np.int32), o_q[i]), "integer vector, worker %d" % i
+    assert u64(d_cnt).tolist() == o_cnt                      # bit-exact clip counts
+
+    # ---- a4
+    d_S = torch.full((d,), -5, dtype=torch.int32, device=DEV)
+    P.intsgd_int_sum(desc, d_q, d_S)
+    assert np.array_equal(host(d_S), o_S)                    # bit-exact aggregate
+
+    # ---- a5-a6 (+ optional decoded gradient)
+    d_x = dev(x)
+    d_gt = torch.zeros(d, dtype=torch.float32, device=DEV)
+    P.intsgd_decode_update(desc, d_S, d_alpha, eta, d_x, d_gt)
+    assert_within_ulp(host(d_x), o_x, 1, "x after decode_update")
+    assert_within_ulp(host(d_gt), o_gt, 1, "decoded gradient")
+    d_x2 = dev(x)
+    P.intsgd_decode_update(desc, d_S, d_alpha, eta, d_x2, None)
+    assert torch.equal(d_x2, d_x)
+
+    # ---- a7
+    d_ns = torch.full((B,), -1.0, dtype=torch.float64, device=DEV)
+    P.intsgd_update_norm(desc, d_x, dev(x), d_ns, ws)
+    o_ns_of_gpu_x = oracle.update_norm(host(d_x), x, offsets=off_np, B=B)
+    assert rel_err(host(d_ns), o_ns_of_gpu_x) <= NORM_RTOL
+    assert rel_err(host(d_ns), o_ns) <= NORM_RTOL
+
+    # ---- F1 == a1-a4
+    d_S1 = torch.full((d,), -5, dtype=torch.int32, device=DEV)
+    d_cnt1 = torch.full((n,), -1, dtype=torch.int64, device=DEV)
+    P.intsgd_compress_sum(desc, d_g, d_alpha, d_S1, d_cnt1, ws)
+    assert torch.equal(d_S1, d_S)
+    assert u64(d_cnt1).tolist() == o_cnt
+
+    # ---- F2 == a5-a7
+    d_x3 = dev(x)
+    d_ns3 = torch.full((B,), -1.0, dtype=torch.float64, device=DEV)
+    P.intsgd_decode_update_norm(desc, d_S1, d_alpha, eta, d_x3, d_ns3, ws)
+    assert torch.equal(d_x3, d_x)
+    assert rel_err(host(d_ns3), o_ns) <= NORM_RTOL
+
+    # ---- F3 == F1 + F2
+    d_x4 = dev(x)
+    d_ns4 = torch.full((B,), -1.0, dtype=torch.float64, device=DEV)
+    d_cnt4 = torch.full((n,), -1, dtype=torch.int64, device=DEV)
+    P.intsgd_step_fused(desc, d_g, d_alpha, eta, d_x4, d_ns4, d_cnt4, ws)
+    assert torch.equal(d_x4, d_x3)                           # same bits as the two-pass form
+    assert_within_ulp(host(d_x4), o_x, 1, "x after fused step")
+    assert u64(d_cnt4).tolist() == o_cnt
+    assert rel_err(host(d_ns4), o_ns) <= NORM_RTOL
+    assert rel_err(host(d_ns4), host(d_ns3)) <= 1e-12
+    # inputs are never modified
+    for i in range(n):
+        assert np.array_equal(host(d_g[i]).view(np.uint32), g[i].view(np.uint32))
+
+
+@pytest.mark.parametrize("tile,grid", [(1024, 1), (1024, 7), (4096, 8192), (16384, 64), (65536, 3)])
+def test_results_do_not_depend_on_tuning(tile, grid):
+    """Tile size and grid only change the summation order of the norm."""
+    d, n, offsets = 300007, 6, [0, 17, 100000, 100003, 300007]
+    alpha, g, x = make_case(d, n, offsets, seed=5)
+    desc = P.Desc(d, n, rounding=P.ROUND_STOCHASTIC, clip=1000, seed=9, step=2, block_offsets=offsets)
+    ws = P.new_workspace(desc, DEV)
+    off_np = np.array(offsets, np.uint64)
+    out = oracle.step(list(g), alpha, x, rounding=1, L=1000, eta=0.3, seed=9, step=2, offsets=off_np)
+    P.intsgd_set_tuning(tile, grid)
+    d_x = dev(x)
+    d_ns = torch.zeros(len(offsets) - 1, dtype=torch.float64, device=DEV)
+    d_cnt = torch.zeros(n, dtype=torch.int64, device=DEV)
+    P.intsgd_step_fused(desc, rows_on_device(g), dev(alpha), 0.3, d_x, d_ns, d_cnt, ws)
+    assert_within_ulp(host(d_x), out["x_new"], 1, "x")
+    assert u64(d_cnt).tolist() == out["sat_count"].tolist()
+    assert rel_err(host(d_ns), out["normsq"]) <= NORM_RTOL
+
+
+def test_empty_and_degenerate_inputs():
+    """Zero gradients leave x untouched; alpha = +Inf (the rule's zero denominator)
+    saturates everything that is not zero and counts NaNs from 0*Inf."""
+    d, n = 5000, 4
+    x = np.linspace(-1, 1, d).astype(F32)
+    desc = P.Desc(d, n, rounding=P.ROUND_STOCHASTIC, clip=100, seed=1, step=1)
+    ws = P.new_workspace(desc, DEV)
+    zeros = [torch.zeros(d, dtype=torch.float32, device=DEV) for _ in range(n)]
+    d_x = dev(x)
+    d_ns = torch.ones(1, dtype=torch.float64, device=DEV)
+    d_cnt = torch.ones(n, dtype=torch.int64, device=DEV)
+    P.intsgd_step_fused(desc, zeros, dev(np.array([123.0], F32)), 0.1, d_x, d_ns, d_cnt, ws)
+    assert np.array_equal(host(d_x), x) and host(d_ns)[0] == 0.0 and u64(d_cnt).sum() == 0
+    rng = np.random.default_rng(0)
+    g = rng.normal(0, 1, (n, d)).astype(F32)
+    g[:, ::7] = 0.0
+    a_inf = np.array([np.inf], F32)
+    out = oracle.step(list(g), a_inf, x, rounding=1, L=100, eta=0.1, seed=1, step=1)
+    d_x = dev(x)
+    P.intsgd_step_fused(desc, rows_on_device(g), dev(a_inf), 0.1, d_x, d_ns, d_cnt, ws)
+    assert u64(d_cnt).tolist() == out["sat_count"].tolist() == [d] * n
+    assert_within_ulp(host(d_x), out["x_new"], 1, "x at alpha=inf")
+
+
+def test_next_alpha_matches_oracle_and_host_twin():
+    rng = np.random.default_rng(3)
+    for offsets in (None, [0, 10, 250, 251, 100000]):
+        d, n = 100000, 8
+        B = 1 if offsets is None else len(offsets) - 1
+        desc = P.Desc(d, n, block_offsets=offsets)
+        off_np = None if offsets is None else np.array(offsets, np.uint64)
+        for beta, eps, eta in [(0.9, 1e-8, 0.1), (0.0, 0.0, 1.25), (0.5, 1e-3, 0.01)]:
+            ns = rng.uniform(1e-9, 1e-1, B)
+            r0 = rng.uniform(0, 1e-2, B)
+            o_r, o_ad, o_af, bad = oracle.next_alpha(ns, r0, d=d, n=n, beta=beta, eps=eps, eta=eta,
+                                                     offsets=off_np)
+            assert bad == 0
+            d_r = dev(r0.copy())
+            d_a = torch.zeros(B, dtype=torch.float32, device=DEV)
+            P.intsgd_next_alpha(desc, dev(ns), d_r, beta, eps, eta, d_a)
+            assert rel_err(host(d_r), o_r) <= 1e-14
+            assert rel_err(host(d_a), o_ad) <= ALPHA_RTOL       # within 1e-5 relative of the fp64 alpha
+            assert_within_ulp(host(d_a), o_af, 1, "alpha")
+            st, h_r, h_a = P.intsgd_next_alpha_host(desc, ns, r0, beta, eps, eta)
+            assert st == 0 and np.array_equal(np.array(h_a, F32), o_af) and np.allclose(h_r, o_r, rtol=1e-15)
+    # zero denominator: +Inf on the device, reported by the host twin
+    desc = P.Desc(1000, 2)
+    d_r = torch.zeros(1, dtype=torch.float64, device=DEV)
+    d_a = torch.zeros(1, dtype=torch.float32, device=DEV)
+    P.intsgd_next_alpha(desc, torch.zeros(1, dtype=torch.float64, device=DEV), d_r, 0.0, 0.0, 0.1, d_a)
+    assert np.isposinf(host(d_a)[0])
+    assert P.intsgd_next_alpha_host(desc, [0.0], [0.0], 0.0, 0.0, 0.1)[0] == -3
+
+
+# --------------------------------------------------------------------------- multi-step
+def lockstep_run(w: W.Workload, steps, mode="fused", free_running=True):
+    """Runs `steps` IntSGD steps on the GPU and replays each one in the oracle WITH THE
+    GPU's alpha (integers are only comparable under the same alpha).  Compares x (<= 1
+    ulp), clip counts (exact), norm and next alpha (1e-5).  With free_running, a second
+    oracle chain that never sees GPU values must also stay within 1e-5 on norm and alpha."""
+    desc = P.Desc(w.d, w.n, rounding=w.rounding, wire=w.wire, clip=w.clip, seed=w.philox_seed,
+                  block_offsets=w.block_offsets)
+    off_np = None if w.block_offsets is None else np.array(w.block_offsets, np.uint64)
+    st = Stepper(desc, eta=w.eta, beta=w.beta, eps=w.eps, device=DEV)
+    st.start(w.first_normsq)
+    x = W.make_params(w, DEV)
+    kw = dict(d=w.d, n=w.n, beta=w.beta, eps=w.eps, eta=w.eta, offsets=off_np)
+    # oracle chains
+    r_lock = np.zeros(w.num_blocks)
+    r_lock, ad, af, _ = oracle.next_alpha(w.first_normsq, r_lock, **kw)
+    assert rel_err(host(st.alpha), ad) <= ALPHA_RTOL
+    r_free, af_free, x_free = r_lock.copy(), af.copy(), host(x).copy()
+    sum_buf = torch.empty(w.d, dtype=torch.int32, device=DEV) if mode != "fused" else None
+    q_bufs = x_old_buf = None
+    if mode == "unfused":
+        qdt = torch.int8 if w.wire == 8 else torch.int32
+        q_bufs = [torch.empty(w.d, dtype=qdt, device=DEV) for _ in range(w.n)]
+        x_old_buf = torch.empty_like(x)
+    total_sat = 0
+    for k in range(1, steps + 1):
+        _, rows = W.make_gradients(w, k, DEV)
+        a_gpu = host(st.alpha).copy()
+        x_old = host(x).copy()
+        if mode == "fused":
+            st.step_fused(rows, x, k)
+        elif mode == "two_pass":
+            st.step_two_pass(rows, x, k, sum_buf)
+        else:
+            st.step_unfused(rows, x, k, q_bufs, sum_buf, x_old_buf)
+        g_host = [host(r_) for r_ in rows]
+        out = oracle.step(g_host, a_gpu, x_old, rounding=w.rounding, L=w.clip, eta=w.eta,
+                          seed=w.philox_seed, step=k, offsets=off_np)
+        assert out["overflow"] == 0
+        assert_within_ulp(host(x), out["x_new"], 1, "x at step %d" % k)
+        assert u64(st.sat_count).tolist() == out["sat_count"].tolist(), "clip counts at step %d" % k
+        assert rel_err(host(st.norm_sq), out["normsq"]) <= NORM_RTOL
+        total_sat += int(out["sat_count"].sum())
+        r_lock, ad, af, _ = oracle.next_alpha(out["normsq"], r_lock, **kw)
+        assert rel_err(host(st.r), r_lock) <= NORM_RTOL
+        assert rel_err(host(st.alpha), ad) <= ALPHA_RTOL
+        if free_running:
+            of = oracle.step(g_host, af_free, x_free, rounding=w.rounding, L=w.clip, eta=w.eta,
+                             seed=w.philox_seed, step=k, offsets=off_np)
+            x_free = of["x_new"]
+            assert rel_err(host(st.norm_sq), of["normsq"]) <= NORM_RTOL
+            r_free, adf, af_free, _ = oracle.next_alpha(of["normsq"], r_free, **kw)
+            assert rel_err(host(st.alpha), adf) <= ALPHA_RTOL
+    return total_sat
+
+
+def scaled_blocks(total):
+    """A small partition with the flavour of the BERT-base one: big matrices, 768-vectors."""
+    sizes = [768 * 96, 768, 768 * 32, 768, 768, 96 * 768, 30522, 768]
+    off = [0]
+    for s in sizes:
+        off.append(off[-1] + s)
+    return off
+
+
+@pytest.mark.parametrize("mode", ["fused", "two_pass", "unfused"])
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_configs_scaled_multi_step(cfg, mode):
+    """The five workloads' recipes at a size the oracle replays in seconds (several
+    tiles and a ragged tail), all three forms of the step, 6 consecutive steps."""
+    w = W.config(cfg)
+    if cfg == 4:
+        w = w.scaled(scaled_blocks(0)[-1], block_offsets=scaled_blocks(0))
+    else:
+        w = w.scaled(200_003 if cfg != 1 else 1 << 17)
+    sat = lockstep_run(w, steps=6, mode=mode)
+    if cfg == 3:
+        assert sat > 0        # the heavy-tailed int8 workload must actually clip
+
+
+def test_config4_global_alpha_variant():
+    w = W.config(4, per_bucket=False).scaled(scaled_blocks(0)[-1])
+    lockstep_run(w, steps=4)
+
+
+def test_config1_full_size():
+    lockstep_run(W.config(1), steps=1, free_running=False)
+
+
+def test_config2_full_size_three_steps():
+    """d = 25,557,032, n = 16, deterministic int32, in the launch configuration the
+    benchmark times (fused step + next alpha); the oracle replays the whole vector."""
+    lockstep_run(W.config(2), steps=3, free_running=False)
+
+
+def test_config3_full_size_two_steps():
+    sat = lockstep_run(W.config(3), steps=2, free_running=False)
+    assert sat > 0
+
+
+def sampled_check(w: W.Workload, steps, slices_per_step=48, slice_len=8192):
+    """Full-size run; the oracle recomputes sampled coordinate windows (tile edges,
+    block edges, the vector's ends, random places) with the GPU's alpha; the norm is
+    checked against a float64 torch reduction of the stored iterates."""
+    desc = P.Desc(w.d, w.n, rounding=w.rounding, wire=w.wire, clip=w.clip, seed=w.philox_seed,
+                  block_offsets=w.block_offsets)
+    off = [0, w.d] if w.block_offsets is None else w.block_offsets
+    off_np = None if w.block_offsets is None else np.array(w.block_offsets, np.uint64)
+    st = Stepper(desc, eta=w.eta, beta=w.beta, eps=w.eps, device=DEV)
+    st.start(w.first_normsq)
+    x = W.make_params(w, DEV)
+    buf = torch.empty((w.n, w.d), dtype=torch.float32, device=DEV)
+    rng = np.random.default_rng(w.config_id)
+    tile = P.intsgd_get_tuning()[0]
+    for k in range(1, steps + 1):
+        _, rows = W.make_gradients(w, k, DEV, out=buf)
+        a_gpu = host(st.alpha).copy()
+        x_old = x.clone()
+        st.step_fused(rows, x, k)
+        assert u64(st.sat_count).sum() == 0
+        # norm: property that holds at any size
+        for l in rng.choice(len(off) - 1, min(8, len(off) - 1), replace=False):
+            a, b = off[l], off[l + 1]
+            acc = 0.0
+            for c in range(a, b, 1 << 26):
+                e = min(b, c + (1 << 26))
+                acc += float((x[c:e].double() - x_old[c:e].double()).pow(2).sum())
+            assert rel_err(host(st.norm_sq)[l], acc) <= NORM_RTOL
+        starts = [0, max(0, w.d - slice_len), tile - 5, (w.d // tile) * tile - 3]
+        starts += [o - 7 for o in off[1:-1:max(1, len(off) // 10)]]
+        starts += list(rng.integers(0, w.d - slice_len, slices_per_step))
+        for s in starts:
+            s = int(max(0, min(s, w.d - slice_len)))
+            e = s + slice_len
+            out = oracle.step([host(r_[s:e]) for r_ in rows], a_gpu, host(x_old[s:e]),
+                              rounding=w.rounding, L=w.clip, eta=w.eta, seed=w.philox_seed, step=k,
+                              j0=s, offsets=off_np)
+            assert_within_ulp(host(x[s:e]), out["x_new"], 1, "x[%d:%d] at step %d" % (s, e, k))
+            assert out["sat_count"].sum() == 0
+        del x_old
+
+
+def test_config4_full_size_sampled():
+    sampled_check(W.config(4), steps=2)
+
+
+def test_config5_full_size_sampled():
+    """d = 1.3e9, n = 8: 41.6 GB of gradients + 5.2 GB of parameters resident."""
+    free, _ = torch.cuda.mem_get_info()
+    assert free > 70e9, "needs the 288 GB MI355X"
+    sampled_check(W.config(5), steps=1, slices_per_step=64)
+    torch.cuda.empty_cache()
