@@ -153,6 +153,36 @@ def _ptr(t):
     return C.c_void_p(0 if t is None else t.data_ptr())
 
 
+_ITEMSIZE = {torch.float32: 4, torch.int32: 4, torch.int8: 1, torch.float64: 8, torch.int64: 8,
+             torch.uint8: 1}
+
+
+def _need(t, numel, dtypes, what):
+    """Shape guard: a device tensor of one of `dtypes` with at least `numel` elements
+    (the C ABI sees raw pointers and cannot check extents itself)."""
+    if t is None:
+        return
+    if not isinstance(dtypes, tuple):
+        dtypes = (dtypes,)
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous()):
+        raise ValueError("%s must be a contiguous device tensor" % what)
+    if t.dtype not in dtypes:
+        raise ValueError("%s has dtype %s, expected %s" % (what, t.dtype, dtypes))
+    if t.numel() < numel:
+        raise ValueError("%s has %d elements, needs %d" % (what, t.numel(), numel))
+
+
+def _need_rows(desc, tensors, dtypes, what):
+    if len(tensors) != desc.n:
+        raise ValueError("%s: expected %d tensors, got %d" % (what, desc.n, len(tensors)))
+    for i, t in enumerate(tensors):
+        _need(t, desc.d, dtypes, "%s[%d]" % (what, i))
+
+
+def _wire_dtype(desc):
+    return torch.int8 if desc.wire == WIRE_INT8 else torch.int32
+
+
 def _ptr_array(tensors):
     return (C.c_void_p * len(tensors))(*[t.data_ptr() for t in tensors])
 
@@ -160,6 +190,7 @@ def _ptr_array(tensors):
 def _ws(workspace):
     if workspace is None:
         return C.c_void_p(0), 0
+    _need(workspace, 0, torch.uint8, "workspace")
     return C.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size()
 
 
@@ -183,28 +214,44 @@ def intsgd_release():
 
 
 def intsgd_compress(desc, grads, alpha, q_out, sat_count, workspace, stream=None):
+    _need_rows(desc, grads, torch.float32, "grads")
+    _need_rows(desc, q_out, _wire_dtype(desc), "q_out")
+    _need(alpha, desc.num_blocks, torch.float32, "alpha")
+    _need(sat_count, desc.n, torch.int64, "sat_count")
     w, wb = _ws(workspace)
     _check(_lib.intsgd_compress(desc.ref(), _ptr_array(grads), _ptr(alpha), _ptr_array(q_out),
                                 _ptr(sat_count), w, wb, _stream(stream)), "intsgd_compress")
 
 
 def intsgd_int_sum(desc, q, sum_out, stream=None):
+    _need_rows(desc, q, _wire_dtype(desc), "q")
+    _need(sum_out, desc.d, torch.int32, "sum_out")
     _check(_lib.intsgd_int_sum(desc.ref(), _ptr_array(q), _ptr(sum_out), _stream(stream)),
            "intsgd_int_sum")
 
 
 def intsgd_decode_update(desc, sum_, alpha, eta, x, gtilde_out=None, stream=None):
+    _need(sum_, desc.d, torch.int32, "sum")
+    _need(alpha, desc.num_blocks, torch.float32, "alpha")
+    _need(x, desc.d, torch.float32, "x")
+    _need(gtilde_out, desc.d, torch.float32, "gtilde_out")
     _check(_lib.intsgd_decode_update(desc.ref(), _ptr(sum_), _ptr(alpha), float(eta), _ptr(x),
                                      _ptr(gtilde_out), _stream(stream)), "intsgd_decode_update")
 
 
 def intsgd_update_norm(desc, x_new, x_old, norm_sq_out, workspace, stream=None):
+    _need(x_new, desc.d, torch.float32, "x_new")
+    _need(x_old, desc.d, torch.float32, "x_old")
+    _need(norm_sq_out, desc.num_blocks, torch.float64, "norm_sq_out")
     w, wb = _ws(workspace)
     _check(_lib.intsgd_update_norm(desc.ref(), _ptr(x_new), _ptr(x_old), _ptr(norm_sq_out), w, wb,
                                    _stream(stream)), "intsgd_update_norm")
 
 
 def intsgd_next_alpha(desc, norm_sq, r, beta, eps, eta, alpha_out, stream=None):
+    _need(norm_sq, desc.num_blocks, torch.float64, "norm_sq")
+    _need(r, desc.num_blocks, torch.float64, "r")
+    _need(alpha_out, desc.num_blocks, torch.float32, "alpha_out")
     _check(_lib.intsgd_next_alpha(desc.ref(), _ptr(norm_sq), _ptr(r), float(beta), float(eps),
                                   float(eta), _ptr(alpha_out), _stream(stream)),
            "intsgd_next_alpha")
@@ -221,6 +268,10 @@ def intsgd_next_alpha_host(desc, norm_sq, r, beta, eps, eta):
 
 
 def intsgd_compress_sum(desc, grads, alpha, sum_out, sat_count, workspace, stream=None):
+    _need_rows(desc, grads, torch.float32, "grads")
+    _need(alpha, desc.num_blocks, torch.float32, "alpha")
+    _need(sum_out, desc.d, torch.int32, "sum_out")
+    _need(sat_count, desc.n, torch.int64, "sat_count")
     w, wb = _ws(workspace)
     _check(_lib.intsgd_compress_sum(desc.ref(), _ptr_array(grads), _ptr(alpha), _ptr(sum_out),
                                     _ptr(sat_count), w, wb, _stream(stream)),
@@ -228,6 +279,10 @@ def intsgd_compress_sum(desc, grads, alpha, sum_out, sat_count, workspace, strea
 
 
 def intsgd_decode_update_norm(desc, sum_, alpha, eta, x, norm_sq_out, workspace, stream=None):
+    _need(sum_, desc.d, torch.int32, "sum")
+    _need(alpha, desc.num_blocks, torch.float32, "alpha")
+    _need(x, desc.d, torch.float32, "x")
+    _need(norm_sq_out, desc.num_blocks, torch.float64, "norm_sq_out")
     w, wb = _ws(workspace)
     _check(_lib.intsgd_decode_update_norm(desc.ref(), _ptr(sum_), _ptr(alpha), float(eta), _ptr(x),
                                           _ptr(norm_sq_out), w, wb, _stream(stream)),
@@ -235,6 +290,11 @@ def intsgd_decode_update_norm(desc, sum_, alpha, eta, x, norm_sq_out, workspace,
 
 
 def intsgd_step_fused(desc, grads, alpha, eta, x, norm_sq_out, sat_count, workspace, stream=None):
+    _need_rows(desc, grads, torch.float32, "grads")
+    _need(alpha, desc.num_blocks, torch.float32, "alpha")
+    _need(x, desc.d, torch.float32, "x")
+    _need(norm_sq_out, desc.num_blocks, torch.float64, "norm_sq_out")
+    _need(sat_count, desc.n, torch.int64, "sat_count")
     w, wb = _ws(workspace)
     _check(_lib.intsgd_step_fused(desc.ref(), _ptr_array(grads), _ptr(alpha), float(eta), _ptr(x),
                                   _ptr(norm_sq_out), _ptr(sat_count), w, wb, _stream(stream)),
