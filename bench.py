@@ -1,0 +1,186 @@
+#!/usr/bin/env python3
+"""Benchmark of the IntSGD compression hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic gradients:
+scale + round + clip + aggregate + decode + update + norm (one fused sweep), the
+fixed-order final sums, and the next alpha.  Gradients, parameters and all state
+are resident in HBM before the timed region; nothing is copied to the host inside
+it.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--mode fused]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = headline)")
+    ap.add_argument("--mode", default="fused", choices=["fused", "two_pass"])
+    ap.add_argument("--pool", type=int, default=0,
+                    help="distinct gradient sets resident in HBM, cycled (0 = auto)")
+    ap.add_argument("--tile", type=int, default=0)
+    ap.add_argument("--grid", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--global-alpha", action="store_true", help="config 4 with one alpha")
+    return ap.parse_args()
+
+
+def cpu_baseline(w, rows, alpha_host, x_host, max_wc=420_000_000):
+    """The oracle as it stands, single-threaded, on a bounded leading slice of the same
+    workload (the whole vector when it is small enough); reported in the metric's unit."""
+    import numpy as np
+
+    import oracle
+    ln = min(w.d, max(4096, max_wc // w.n))
+    off = None
+    if w.block_offsets is not None:
+        off = np.array(w.block_offsets, np.uint64)
+    g = [r[:ln].cpu().numpy() for r in rows]
+    t0 = time.perf_counter()
+    out = oracle.step(g, alpha_host, x_host[:ln], rounding=w.rounding, L=w.clip, eta=w.eta,
+                      seed=w.philox_seed, step=1, offsets=off)
+    oracle.next_alpha(out["normsq"], np.zeros(w.num_blocks), d=w.d, n=w.n, beta=w.beta, eps=w.eps,
+                      eta=w.eta, offsets=off)
+    dt = time.perf_counter() - t0
+    return {"value": 4.0 * w.n * ln / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": "one step on the first %d of %d coordinates x %d workers (%.1f s)" % (
+                ln, w.d, w.n, dt)}
+
+
+def load_traffic(name, mode):
+    """HBM bytes per launch of the dominant kernel from committed rocprofv3 counter
+    summaries (profiles/traffic.json), or None."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as fh:
+            table = json.load(fh)
+        return table.get("%s/%s" % (name, mode), {}).get("bytes_per_launch")
+    except (OSError, ValueError):
+        return None
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (the n workers are "
+              "n gradient buffers in one HBM); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    import paper_2102_08374_amd as P
+    from paper_2102_08374_amd import workloads as W
+    from paper_2102_08374_amd.stepper import Stepper
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = W.config(args.config, per_bucket=not args.global_alpha)
+    if args.tile or args.grid:
+        P.intsgd_set_tuning(args.tile, args.grid)
+    tile, grid = P.intsgd_get_tuning()
+
+    desc = P.Desc(w.d, w.n, rounding=w.rounding, wire=w.wire, clip=w.clip, seed=w.philox_seed,
+                  block_offsets=w.block_offsets)
+    st = Stepper(desc, eta=w.eta, beta=w.beta, eps=w.eps, device=dev)
+    x = W.make_params(w, dev)
+
+    grad_bytes = 4 * w.n * w.d
+    free, _ = torch.cuda.mem_get_info()
+    pool = args.pool or max(1, min(args.steps + args.warmup, 16, int(0.6 * free // grad_bytes)))
+    sets = []
+    for s in range(pool):
+        buf, rows = W.make_gradients(w, s + 1, dev)
+        sets.append((buf, rows))
+    sum_buf = torch.empty(w.d, dtype=torch.int32, device=dev) if args.mode == "two_pass" else None
+    torch.cuda.synchronize()
+
+    def one_step(k):
+        rows = sets[(k - 1) % pool][1]
+        if args.mode == "fused":
+            st.step_fused(rows, x, k, chain_alpha=False)
+        else:
+            st.step_two_pass(rows, x, k, sum_buf, chain_alpha=False)
+
+    st.start(w.first_normsq)
+    alpha0 = st.alpha.cpu().numpy().copy()
+    x0 = None if args.no_cpu_baseline else x.cpu().numpy().copy()
+
+    for k in range(1, args.warmup + 1):
+        one_step(k)
+        st.next_alpha()
+    torch.cuda.synchronize()
+
+    # timed region: exactly K steps; per-step events bracket the dominant call on the
+    # stream it is launched on
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        k = args.warmup + 1 + i
+        ev[i][0].record()
+        one_step(k)
+        ev[i][1].record()
+        st.next_alpha()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    kernel_ms = sorted(a.elapsed_time(b) for a, b in ev)
+    avg_kernel_ms = sum(kernel_ms) / len(kernel_ms)
+    per_coord = (4 * w.n + 8) if args.mode == "fused" else (4 * w.n + 16)
+    algo_bytes = per_coord * w.d
+    achieved = algo_bytes / (avg_kernel_ms * 1e-3) / 1e9
+    sat = int(st.sat_count.cpu().numpy().view("uint64").sum())
+    alpha_last = float(st.alpha.cpu()[0])
+
+    result = {
+        "metric": "fp32 gradient GB/s per IntSGD step (n workers)",
+        "value": grad_bytes * args.steps / dt / 1e9,
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": dt * 1e3 / args.steps,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": w.name, "d": w.d, "n_workers": w.n, "blocks": w.num_blocks,
+            "rounding": "stochastic" if w.rounding else "nearest-even", "wire": "int%d" % w.wire,
+            "clip": w.clip, "grad_dist": w.grad_kind, "mode": args.mode, "gradient_sets": pool,
+            "tile_coords": tile, "max_workgroups": grid, "alpha_last": alpha_last,
+            "clipped_last_step": sat,
+        },
+        "roofline": {
+            "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": load_traffic(w.name, args.mode),
+            "kernel": "k_step_fused (+ its final-sum kernel)" if args.mode == "fused"
+                      else "k_compress_sum + k_decode (+ final sums)",
+            "algorithmic_bytes_per_launch": algo_bytes,
+            "kernel_ms_avg": avg_kernel_ms, "kernel_ms_min": kernel_ms[0],
+            "kernel_ms_median": kernel_ms[len(kernel_ms) // 2],
+        },
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, sets[0][1], alpha0, x0)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
