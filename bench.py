@@ -2,10 +2,11 @@
 """Benchmark of the IntSGD compression hot path on one MI355X.
 
 A step is one pass of the whole path over one batch of synthetic gradients:
-scale + round + clip + aggregate + decode + update + norm (one fused sweep), the
-fixed-order final sums, and the next alpha.  Gradients, parameters and all state
-are resident in HBM before the timed region; nothing is copied to the host inside
-it.  Prints ONE JSON line.
+scale + round + clip + aggregate + decode + update + norm + next alpha, which the
+library runs as ONE kernel launch (the sweep's last workgroup does the fixed-order
+final sums and the alpha rule).  Gradients, parameters and all state are resident
+in HBM before the timed region; nothing is copied to the host inside it.  Prints
+ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--mode fused]
 """
@@ -33,6 +34,7 @@ def parse():
                     help="distinct gradient sets resident in HBM, cycled (0 = auto)")
     ap.add_argument("--tile", type=int, default=0)
     ap.add_argument("--grid", type=int, default=0)
+    ap.add_argument("--wgs-per-cu", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--global-alpha", action="store_true", help="config 4 with one alpha")
     return ap.parse_args()
@@ -88,9 +90,8 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     w = W.config(args.config, per_bucket=not args.global_alpha)
-    if args.tile or args.grid:
-        P.intsgd_set_tuning(args.tile, args.grid)
-    tile, grid = P.intsgd_get_tuning()
+    P.intsgd_set_tuning(args.tile, args.grid, args.wgs_per_cu)
+    tile, grid, wgs_per_cu = P.intsgd_get_tuning()
 
     desc = P.Desc(w.d, w.n, rounding=w.rounding, wire=w.wire, clip=w.clip, seed=w.philox_seed,
                   block_offsets=w.block_offsets)
@@ -110,9 +111,9 @@ def main():
     def one_step(k):
         rows = sets[(k - 1) % pool][1]
         if args.mode == "fused":
-            st.step_fused(rows, x, k, chain_alpha=False)
+            st.step_fused(rows, x, k)                    # a1-a8, one launch
         else:
-            st.step_two_pass(rows, x, k, sum_buf, chain_alpha=False)
+            st.step_two_pass(rows, x, k, sum_buf)        # F1, F2, a8: three launches
 
     st.start(w.first_normsq)
     alpha0 = st.alpha.cpu().numpy().copy()
@@ -120,10 +121,9 @@ def main():
 
     for k in range(1, args.warmup + 1):
         one_step(k)
-        st.next_alpha()
     torch.cuda.synchronize()
 
-    # timed region: exactly K steps; per-step events bracket the dominant call on the
+    # timed region: exactly K steps; per-step events bracket the step's kernel on the
     # stream it is launched on
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
           for _ in range(args.steps)]
@@ -134,7 +134,6 @@ def main():
         ev[i][0].record()
         one_step(k)
         ev[i][1].record()
-        st.next_alpha()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
@@ -163,15 +162,16 @@ def main():
             "workload": w.name, "d": w.d, "n_workers": w.n, "blocks": w.num_blocks,
             "rounding": "stochastic" if w.rounding else "nearest-even", "wire": "int%d" % w.wire,
             "clip": w.clip, "grad_dist": w.grad_kind, "mode": args.mode, "gradient_sets": pool,
-            "tile_coords": tile, "max_workgroups": grid, "alpha_last": alpha_last,
+            "tile_coords": tile, "max_workgroups": grid, "workgroups_per_cu": wgs_per_cu,
+            "alpha_last": alpha_last,
             "clipped_last_step": sat,
         },
         "roofline": {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
             "traffic": load_traffic(w.name, args.mode),
-            "kernel": "k_step_fused (+ its final-sum kernel)" if args.mode == "fused"
-                      else "k_compress_sum + k_decode (+ final sums)",
+            "kernel": "k_aggregate<ROUND, FUSED=true> (the whole step)" if args.mode == "fused"
+                      else "k_aggregate<ROUND, false> + k_decode<true, false> + k_next_alpha",
             "algorithmic_bytes_per_launch": algo_bytes,
             "kernel_ms_avg": avg_kernel_ms, "kernel_ms_min": kernel_ms[0],
             "kernel_ms_median": kernel_ms[len(kernel_ms) // 2],

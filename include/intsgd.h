@@ -30,8 +30,12 @@
  *     that is built the first time a descriptor with num_blocks > 1 is used (or
  *     by intsgd_prepare) and freed by intsgd_release().  Descriptors with
  *     num_blocks == 1 need none.
- *   - Calls on different streams that share a workspace race; give each
- *     concurrent call its own workspace.
+ *   - A workspace must be passed through intsgd_workspace_init once after it is
+ *     allocated (and again if anything else wrote to it); every call then leaves
+ *     it ready for the next one.  Calls on different streams that share a
+ *     workspace race; give each concurrent call its own workspace.
+ *   - For full bandwidth give every vector a 128-byte aligned start (only 16 is
+ *     required).
  */
 #ifndef INTSGD_H_
 #define INTSGD_H_
@@ -94,9 +98,13 @@ typedef struct intsgd_desc {
 } intsgd_desc;
 
 /* Bytes of DEVICE scratch (256-byte aligned) that any entry point taking a
- * workspace needs for this descriptor; 0 if the descriptor is invalid.  The
- * contents need not be initialised and are not meaningful afterwards. */
+ * workspace needs for this descriptor; 0 if the descriptor is invalid. */
 size_t intsgd_workspace_bytes(const intsgd_desc* desc);
+
+/* Enqueues the one-time initialisation of a workspace (zeroes the control words the
+ * kernels use to elect the workgroup that finishes their reductions; each call that
+ * uses the workspace resets them itself).  workspace_bytes >= 1024. */
+intsgd_status intsgd_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Validates the descriptor and builds the library's tile table for its partition
  * now (the only call that may allocate device memory), so that later calls on
@@ -191,12 +199,33 @@ intsgd_status intsgd_step_fused(const intsgd_desc* desc, const float* const* gra
                                 uint64_t* sat_count, void* workspace, size_t workspace_bytes,
                                 void* hip_stream);
 
+/*
+ * The whole step in ONE launch: F3 followed by a8 (Section 4.1 / Algorithm 2) applied
+ * by the kernel's last workgroup.  alpha: DEVICE float[B], read as alpha_k during the
+ * sweep and overwritten with alpha_{k+1} at the end; r: DEVICE double[B] in/out;
+ * norm_sq_out, sat_count as in intsgd_step_fused.  eta is eta_k for both the update
+ * and the rule.  Same results as intsgd_step_fused followed by intsgd_next_alpha.
+ */
+intsgd_status intsgd_step_fused_next_alpha(const intsgd_desc* desc, const float* const* grads,
+                                           float* alpha, double eta, float* x, double* r,
+                                           double beta, double eps, double* norm_sq_out,
+                                           uint64_t* sat_count, void* workspace,
+                                           size_t workspace_bytes, void* hip_stream);
+
 /* Tuning knobs (process-wide; not part of the numerical contract: results do not
- * depend on them except for the summation order of the norm).  tile_coords:
- * coordinates per work tile, a multiple of 1024 in [1024, 65536].  max_workgroups:
- * cap of the launch grid, in [1, 16384].  0 keeps the current value. */
-intsgd_status intsgd_set_tuning(uint32_t tile_coords, uint32_t max_workgroups);
-void intsgd_get_tuning(uint32_t* tile_coords, uint32_t* max_workgroups);
+ * depend on them except for the summation order of the norm).  A field that is 0
+ * keeps the current value.
+ *   tile_coords        coordinates per work tile, a multiple of 1024 in [1024, 65536]
+ *   max_workgroups     cap of the launch grid, in [1, 1048576]; tiles beyond it are
+ *                      taken by striding
+ *   workgroups_per_cu  residency cap of the streaming kernels, 2..8 (8 = no cap) */
+typedef struct intsgd_tuning {
+  uint32_t tile_coords;
+  uint32_t max_workgroups;
+  uint32_t workgroups_per_cu;
+} intsgd_tuning;
+intsgd_status intsgd_set_tuning(const intsgd_tuning* tuning);
+void intsgd_get_tuning(intsgd_tuning* tuning);
 
 const char* intsgd_status_string(intsgd_status status);
 /* Text of the last HIP error seen by this thread's calls ("" if none). */

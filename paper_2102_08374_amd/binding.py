@@ -15,8 +15,9 @@ __all__ = [
     "MAX_WORKERS", "default_clip", "library_path", "intsgd_workspace_bytes", "intsgd_prepare",
     "intsgd_release", "intsgd_compress", "intsgd_int_sum", "intsgd_decode_update",
     "intsgd_update_norm", "intsgd_next_alpha", "intsgd_next_alpha_host", "intsgd_compress_sum",
-    "intsgd_decode_update_norm", "intsgd_step_fused", "intsgd_set_tuning", "intsgd_get_tuning",
-    "intsgd_status_string", "new_workspace", "EXPORTED_SYMBOLS",
+    "intsgd_decode_update_norm", "intsgd_step_fused", "intsgd_step_fused_next_alpha",
+    "intsgd_workspace_init", "intsgd_set_tuning", "intsgd_get_tuning", "intsgd_status_string",
+    "new_workspace", "EXPORTED_SYMBOLS",
 ]
 
 ROUND_NEAREST_EVEN = 0
@@ -26,7 +27,8 @@ WIRE_INT32 = 32
 MAX_WORKERS = 128
 
 EXPORTED_SYMBOLS = [
-    "intsgd_workspace_bytes", "intsgd_prepare", "intsgd_release", "intsgd_compress",
+    "intsgd_workspace_bytes", "intsgd_workspace_init", "intsgd_prepare", "intsgd_release",
+    "intsgd_compress", "intsgd_step_fused_next_alpha",
     "intsgd_int_sum", "intsgd_decode_update", "intsgd_update_norm", "intsgd_next_alpha",
     "intsgd_next_alpha_host", "intsgd_compress_sum", "intsgd_decode_update_norm",
     "intsgd_step_fused", "intsgd_set_tuning", "intsgd_get_tuning", "intsgd_status_string",
@@ -57,6 +59,11 @@ class _CDesc(C.Structure):
                 ("seed", C.c_uint64)]
 
 
+class _CTuning(C.Structure):
+    _fields_ = [("tile_coords", C.c_uint32), ("max_workgroups", C.c_uint32),
+                ("workgroups_per_cu", C.c_uint32)]
+
+
 _P = C.c_void_p
 _DP = C.POINTER(_CDesc)
 _PP = C.POINTER(C.c_void_p)
@@ -75,8 +82,11 @@ _lib.intsgd_next_alpha_host.argtypes = [_DP, C.POINTER(C.c_double), C.POINTER(C.
 _lib.intsgd_compress_sum.argtypes = [_DP, _PP, _P, _P, _P, _P, C.c_size_t, _P]
 _lib.intsgd_decode_update_norm.argtypes = [_DP, _P, _P, C.c_double, _P, _P, _P, C.c_size_t, _P]
 _lib.intsgd_step_fused.argtypes = [_DP, _PP, _P, C.c_double, _P, _P, _P, _P, C.c_size_t, _P]
-_lib.intsgd_set_tuning.argtypes = [C.c_uint32, C.c_uint32]
-_lib.intsgd_get_tuning.argtypes = [C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
+_lib.intsgd_step_fused_next_alpha.argtypes = [_DP, _PP, _P, C.c_double, _P, _P, C.c_double,
+                                              C.c_double, _P, _P, _P, C.c_size_t, _P]
+_lib.intsgd_workspace_init.argtypes = [_P, C.c_size_t, _P]
+_lib.intsgd_set_tuning.argtypes = [C.POINTER(_CTuning)]
+_lib.intsgd_get_tuning.argtypes = [C.POINTER(_CTuning)]
 _lib.intsgd_get_tuning.restype = None
 _lib.intsgd_status_string.argtypes = [C.c_int]
 _lib.intsgd_status_string.restype = C.c_char_p
@@ -85,7 +95,7 @@ _lib.intsgd_last_hip_error.restype = C.c_char_p
 for _name in ("intsgd_prepare", "intsgd_compress", "intsgd_int_sum", "intsgd_decode_update",
               "intsgd_update_norm", "intsgd_next_alpha", "intsgd_next_alpha_host",
               "intsgd_compress_sum", "intsgd_decode_update_norm", "intsgd_step_fused",
-              "intsgd_set_tuning"):
+              "intsgd_step_fused_next_alpha", "intsgd_workspace_init", "intsgd_set_tuning"):
     getattr(_lib, _name).restype = C.c_int
 
 
@@ -198,11 +208,19 @@ def intsgd_workspace_bytes(desc: Desc) -> int:
     return int(_lib.intsgd_workspace_bytes(desc.ref()))
 
 
+def intsgd_workspace_init(workspace, stream=None):
+    w, wb = _ws(workspace)
+    _check(_lib.intsgd_workspace_init(w, wb, _stream(stream)), "intsgd_workspace_init")
+
+
 def new_workspace(desc: Desc, device="cuda") -> torch.Tensor:
+    """Allocates and initialises a workspace for `desc`."""
     nbytes = intsgd_workspace_bytes(desc)
     if nbytes == 0:
         raise IntSGDError(-1, "intsgd_workspace_bytes")
-    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    intsgd_workspace_init(ws)
+    return ws
 
 
 def intsgd_prepare(desc: Desc):
@@ -301,14 +319,31 @@ def intsgd_step_fused(desc, grads, alpha, eta, x, norm_sq_out, sat_count, worksp
            "intsgd_step_fused")
 
 
-def intsgd_set_tuning(tile_coords=0, max_workgroups=0):
-    _check(_lib.intsgd_set_tuning(int(tile_coords), int(max_workgroups)), "intsgd_set_tuning")
+def intsgd_step_fused_next_alpha(desc, grads, alpha, eta, x, r, beta, eps, norm_sq_out, sat_count,
+                                 workspace, stream=None):
+    _need_rows(desc, grads, torch.float32, "grads")
+    _need(alpha, desc.num_blocks, torch.float32, "alpha")
+    _need(x, desc.d, torch.float32, "x")
+    _need(r, desc.num_blocks, torch.float64, "r")
+    _need(norm_sq_out, desc.num_blocks, torch.float64, "norm_sq_out")
+    _need(sat_count, desc.n, torch.int64, "sat_count")
+    w, wb = _ws(workspace)
+    _check(_lib.intsgd_step_fused_next_alpha(desc.ref(), _ptr_array(grads), _ptr(alpha), float(eta),
+                                             _ptr(x), _ptr(r), float(beta), float(eps),
+                                             _ptr(norm_sq_out), _ptr(sat_count), w, wb,
+                                             _stream(stream)), "intsgd_step_fused_next_alpha")
+
+
+def intsgd_set_tuning(tile_coords=0, max_workgroups=0, workgroups_per_cu=0):
+    t = _CTuning(int(tile_coords), int(max_workgroups), int(workgroups_per_cu))
+    _check(_lib.intsgd_set_tuning(C.byref(t)), "intsgd_set_tuning")
 
 
 def intsgd_get_tuning():
-    t, g = C.c_uint32(0), C.c_uint32(0)
-    _lib.intsgd_get_tuning(C.byref(t), C.byref(g))
-    return int(t.value), int(g.value)
+    """-> (tile_coords, max_workgroups, workgroups_per_cu)"""
+    t = _CTuning()
+    _lib.intsgd_get_tuning(C.byref(t))
+    return int(t.tile_coords), int(t.max_workgroups), int(t.workgroups_per_cu)
 
 
 def intsgd_status_string(status: int) -> str:

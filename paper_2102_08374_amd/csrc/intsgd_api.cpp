@@ -20,12 +20,15 @@ namespace {
 
 constexpr uint32_t kMinTile = 1024;
 constexpr uint32_t kMaxTile = 65536;
-constexpr uint32_t kMaxGrid = 16384;
+constexpr uint32_t kMaxGrid = 1u << 20;
 constexpr uint64_t kMaxD = 1ull << 40;
 constexpr size_t kAlign = 256;
+constexpr size_t kControlBytes = 1024;          // tickets: one word per worker, padded
+constexpr uint32_t kLdsPerCu = 160u * 1024u;    // gfx950
 
-uint32_t g_tile = 4096;
-uint32_t g_max_grid = 8192;
+// Measured on MI355X (d = 25.6 M, n = 16): 8 KB per stream and workgroup, two resident
+// workgroups of 512 threads per CU, one workgroup per tile.
+intsgd_tuning g_tuning = {2048, kMaxGrid, 2};
 
 thread_local std::string t_hip_error;
 
@@ -83,18 +86,20 @@ intsgd_status validate_vec(const void* p) {
 
 uint64_t tiles_of(uint64_t len, uint32_t tile) { return (len + tile - 1) / tile; }
 
-// Workspace carving; sized for the smallest tile and the largest grid so that it is
-// valid under any tuning.
+// Workspace carving: [control words][norm partial per tile][clip flag per workgroup]
+// [clip counts per workgroup and worker]; sized for the smallest tile so that it is
+// valid under any tuning (the grid never exceeds the number of tiles).
 struct WorkspaceLayout {
-  size_t norm_bytes, sat_bytes, total;
+  size_t norm_off, any_off, rows_off, total;
 };
 
 WorkspaceLayout workspace_layout(const intsgd_desc* desc) {
   WorkspaceLayout w;
   const uint64_t max_tiles = tiles_of(desc->d, kMinTile) + desc->num_blocks;
-  w.norm_bytes = round_up((size_t)max_tiles * sizeof(double), kAlign);
-  w.sat_bytes = round_up((size_t)kMaxGrid * desc->n * sizeof(uint64_t), kAlign);
-  w.total = w.norm_bytes + w.sat_bytes;
+  w.norm_off = kControlBytes;
+  w.any_off = w.norm_off + round_up((size_t)max_tiles * sizeof(double), kAlign);
+  w.rows_off = w.any_off + round_up((size_t)max_tiles * sizeof(uint32_t), kAlign);
+  w.total = w.rows_off + round_up((size_t)max_tiles * desc->n * sizeof(uint64_t), kAlign);
   return w;
 }
 
@@ -105,9 +110,10 @@ intsgd_status validate_workspace(const intsgd_desc* desc, void* ws, size_t bytes
   return INTSGD_OK;
 }
 
-double* ws_norm(void* ws) { return static_cast<double*>(ws); }
-uint64_t* ws_sat(const intsgd_desc* desc, void* ws) {
-  return reinterpret_cast<uint64_t*>(static_cast<char*>(ws) + workspace_layout(desc).norm_bytes);
+uint32_t* ws_tickets(void* ws) { return static_cast<uint32_t*>(ws); }
+template <class T>
+T* ws_at(void* ws, size_t off) {
+  return reinterpret_cast<T*>(static_cast<char*>(ws) + off);
 }
 
 RoundSpec round_spec(const intsgd_desc* desc) {
@@ -207,8 +213,14 @@ struct Tiling {
   const uint64_t* offsets_dev;
 };
 
+// Dynamic LDS that makes exactly k workgroups fit a CU (0 when k is no cap).
+uint32_t lds_reserve_for(uint32_t k) {
+  if (k == 0 || k >= 8) return 0;
+  return kLdsPerCu / (k + 1) + 1024u;
+}
+
 intsgd_status make_tiling(const intsgd_desc* desc, void* stream, Tiling* t) {
-  const uint32_t tile = g_tile;
+  const uint32_t tile = g_tuning.tile_coords;
   t->tm.d = desc->d;
   t->tm.tile = tile;
   if (desc->num_blocks == 1) {
@@ -225,7 +237,8 @@ intsgd_status make_tiling(const intsgd_desc* desc, void* stream, Tiling* t) {
     t->tile_prefix = plan->tile_prefix;
     t->offsets_dev = plan->offsets_dev;
   }
-  t->ls.grid = t->tm.num_tiles < g_max_grid ? t->tm.num_tiles : g_max_grid;
+  t->ls.grid = t->tm.num_tiles < g_tuning.max_workgroups ? t->tm.num_tiles : g_tuning.max_workgroups;
+  t->ls.lds_reserve = lds_reserve_for(g_tuning.workgroups_per_cu);
   t->ls.stream = static_cast<hipStream_t>(stream);
   return INTSGD_OK;
 }
@@ -233,6 +246,28 @@ intsgd_status make_tiling(const intsgd_desc* desc, void* stream, Tiling* t) {
 void fill_ptrs(WorkerPtrs* w, const void* const* src, uint32_t n) {
   std::memset(w, 0, sizeof(*w));
   for (uint32_t i = 0; i < n; ++i) w->p[i] = src[i];
+}
+
+// The end-of-kernel reduction descriptor.  norm_sq_out / sat_count may be null when the
+// kernel does not produce them.
+Finish make_finish(const intsgd_desc* desc, const Tiling& t, void* ws, double* norm_sq_out,
+                   uint64_t* sat_count) {
+  const WorkspaceLayout w = workspace_layout(desc);
+  Finish f{};
+  f.ticket = ws_tickets(ws);
+  f.norm_partial = ws_at<double>(ws, w.norm_off);
+  f.tile_prefix = t.tile_prefix;
+  f.num_tiles = t.tm.num_tiles;
+  f.B = desc->num_blocks;
+  f.norm_sq_out = norm_sq_out;
+  f.sat_any = ws_at<uint32_t>(ws, w.any_off);
+  f.sat_rows = ws_at<uint64_t>(ws, w.rows_off);
+  f.n = desc->n;
+  f.sat_count = sat_count;
+  f.n_workers = desc->n;
+  f.d = desc->d;
+  f.rule = AlphaRule{nullptr, nullptr, nullptr, 0.0, 0.0, 0.0};
+  return f;
 }
 
 intsgd_status done(hipError_t e) { return e == hipSuccess ? INTSGD_OK : hip_fail(e); }
@@ -248,6 +283,31 @@ intsgd_status done(hipError_t e) { return e == hipSuccess ? INTSGD_OK : hip_fail
 
 using namespace intsgd;
 
+namespace {
+
+// Shared body of intsgd_step_fused and intsgd_step_fused_next_alpha.
+intsgd_status step_fused_impl(const intsgd_desc* desc, const float* const* grads,
+                              const float* alpha, double eta, float* x, double* norm_sq_out,
+                              uint64_t* sat_count, void* workspace, size_t workspace_bytes,
+                              void* hip_stream, double* r, float* alpha_out, double beta,
+                              double eps) {
+  INTSGD_TRY(validate_desc(desc));
+  INTSGD_TRY(validate_worker_ptrs((const void* const*)grads, desc->n));
+  INTSGD_TRY(validate_vec(x));
+  if (alpha == nullptr || norm_sq_out == nullptr || sat_count == nullptr) return INTSGD_EINVAL;
+  INTSGD_TRY(validate_rule(beta, eps, eta));
+  INTSGD_TRY(validate_workspace(desc, workspace, workspace_bytes));
+  Tiling t;
+  INTSGD_TRY(make_tiling(desc, hip_stream, &t));
+  WorkerPtrs g;
+  fill_ptrs(&g, (const void* const*)grads, desc->n);
+  Finish fin = make_finish(desc, t, workspace, norm_sq_out, sat_count);
+  if (r != nullptr) fin.rule = AlphaRule{r, alpha_out, t.offsets_dev, beta, eps, eta};
+  return done(launch_step_fused(t.tm, t.ls, desc->n, round_spec(desc), g, alpha, eta, x, fin));
+}
+
+}  // namespace
+
 extern "C" {
 
 size_t intsgd_workspace_bytes(const intsgd_desc* desc) {
@@ -255,11 +315,18 @@ size_t intsgd_workspace_bytes(const intsgd_desc* desc) {
   return workspace_layout(desc).total;
 }
 
+intsgd_status intsgd_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (workspace == nullptr || workspace_bytes < kControlBytes) return INTSGD_EWORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0) return INTSGD_EWORKSPACE;
+  return done(launch_zero_control(static_cast<hipStream_t>(hip_stream), ws_tickets(workspace),
+                                  (uint32_t)(kControlBytes / sizeof(uint32_t))));
+}
+
 intsgd_status intsgd_prepare(const intsgd_desc* desc) {
   INTSGD_TRY(validate_desc(desc));
   if (desc->num_blocks == 1) return INTSGD_OK;
   const DevicePlan* plan = nullptr;
-  return get_plan(desc, g_tile, &plan);
+  return get_plan(desc, g_tuning.tile_coords, &plan);
 }
 
 void intsgd_release(void) {
@@ -283,12 +350,10 @@ intsgd_status intsgd_compress(const intsgd_desc* desc, const float* const* grads
   fill_ptrs(&g, (const void* const*)grads, desc->n);
   std::memset(&q, 0, sizeof(q));
   for (uint32_t i = 0; i < desc->n; ++i) q.p[i] = q_out[i];
-  uint64_t* sat_partial = ws_sat(desc, workspace);
-  hipError_t e = launch_compress(t.tm, t.ls, desc->n, desc->wire, round_spec(desc), g, alpha, q,
-                                 sat_partial);
-  if (e != hipSuccess) return hip_fail(e);
-  return done(launch_finalize(t.ls.stream, nullptr, nullptr, 0, 0, nullptr, sat_partial, t.ls.grid,
-                              desc->n, sat_count));
+  const WorkspaceLayout w = workspace_layout(desc);
+  return done(launch_compress(t.tm, t.ls, desc->n, desc->wire, round_spec(desc), g, alpha, q,
+                              ws_tickets(workspace), ws_at<uint64_t>(workspace, w.rows_off),
+                              sat_count));
 }
 
 intsgd_status intsgd_int_sum(const intsgd_desc* desc, const void* const* q, int32_t* sum_out,
@@ -299,8 +364,8 @@ intsgd_status intsgd_int_sum(const intsgd_desc* desc, const void* const* q, int3
   WorkerPtrs qp;
   fill_ptrs(&qp, q, desc->n);
   // about four quads per thread and pass of the grid-stride loop
-  const uint64_t want = tiles_of((desc->d >> 2) + 1, 256 * 4);
-  LaunchShape ls{(uint32_t)(want < g_max_grid ? want : g_max_grid),
+  const uint64_t want = tiles_of((desc->d >> 2) + 1, INTSGD_THREADS_PER_WORKGROUP * 4);
+  LaunchShape ls{(uint32_t)(want < g_tuning.max_workgroups ? want : g_tuning.max_workgroups), 0,
                  static_cast<hipStream_t>(hip_stream)};
   return done(launch_int_sum(desc->d, ls, desc->n, desc->wire, qp, sum_out));
 }
@@ -329,10 +394,8 @@ intsgd_status intsgd_update_norm(const intsgd_desc* desc, const float* x_new, co
   INTSGD_TRY(validate_workspace(desc, workspace, workspace_bytes));
   Tiling t;
   INTSGD_TRY(make_tiling(desc, hip_stream, &t));
-  hipError_t e = launch_update_norm(t.tm, t.ls, x_new, x_old, ws_norm(workspace));
-  if (e != hipSuccess) return hip_fail(e);
-  return done(launch_finalize(t.ls.stream, ws_norm(workspace), t.tile_prefix, t.tm.num_tiles,
-                              desc->num_blocks, norm_sq_out, nullptr, 0, 0, nullptr));
+  return done(launch_update_norm(t.tm, t.ls, x_new, x_old,
+                                 make_finish(desc, t, workspace, norm_sq_out, nullptr)));
 }
 
 intsgd_status intsgd_next_alpha(const intsgd_desc* desc, const double* norm_sq, double* r,
@@ -344,12 +407,12 @@ intsgd_status intsgd_next_alpha(const intsgd_desc* desc, const double* norm_sq, 
   const uint64_t* offsets_dev = nullptr;
   if (desc->num_blocks > 1) {
     const DevicePlan* plan = nullptr;
-    INTSGD_TRY(get_plan(desc, g_tile, &plan));
+    INTSGD_TRY(get_plan(desc, g_tuning.tile_coords, &plan));
     offsets_dev = plan->offsets_dev;
   }
-  return done(launch_next_alpha(static_cast<hipStream_t>(hip_stream), norm_sq, r,
-                                desc->num_blocks, offsets_dev, desc->d, desc->n, beta, eps, eta,
-                                alpha_out));
+  const AlphaRule rule{r, alpha_out, offsets_dev, beta, eps, eta};
+  return done(launch_next_alpha(static_cast<hipStream_t>(hip_stream), norm_sq, rule,
+                                desc->num_blocks, desc->n, desc->d));
 }
 
 intsgd_status intsgd_next_alpha_host(const intsgd_desc* desc, const double* norm_sq, double* r,
@@ -392,12 +455,8 @@ intsgd_status intsgd_compress_sum(const intsgd_desc* desc, const float* const* g
   INTSGD_TRY(make_tiling(desc, hip_stream, &t));
   WorkerPtrs g;
   fill_ptrs(&g, (const void* const*)grads, desc->n);
-  uint64_t* sat_partial = ws_sat(desc, workspace);
-  hipError_t e = launch_compress_sum(t.tm, t.ls, desc->n, round_spec(desc), g, alpha, sum_out,
-                                     sat_partial);
-  if (e != hipSuccess) return hip_fail(e);
-  return done(launch_finalize(t.ls.stream, nullptr, nullptr, 0, 0, nullptr, sat_partial, t.ls.grid,
-                              desc->n, sat_count));
+  return done(launch_compress_sum(t.tm, t.ls, desc->n, round_spec(desc), g, alpha, sum_out,
+                                  make_finish(desc, t, workspace, nullptr, sat_count)));
 }
 
 intsgd_status intsgd_decode_update_norm(const intsgd_desc* desc, const int32_t* sum,
@@ -412,50 +471,44 @@ intsgd_status intsgd_decode_update_norm(const intsgd_desc* desc, const int32_t* 
   INTSGD_TRY(validate_workspace(desc, workspace, workspace_bytes));
   Tiling t;
   INTSGD_TRY(make_tiling(desc, hip_stream, &t));
-  hipError_t e = launch_decode_update_norm(t.tm, t.ls, desc->n, sum, alpha, eta, x,
-                                           ws_norm(workspace));
-  if (e != hipSuccess) return hip_fail(e);
-  return done(launch_finalize(t.ls.stream, ws_norm(workspace), t.tile_prefix, t.tm.num_tiles,
-                              desc->num_blocks, norm_sq_out, nullptr, 0, 0, nullptr));
+  return done(launch_decode_update_norm(t.tm, t.ls, desc->n, sum, alpha, eta, x,
+                                        make_finish(desc, t, workspace, norm_sq_out, nullptr)));
 }
 
 intsgd_status intsgd_step_fused(const intsgd_desc* desc, const float* const* grads,
                                 const float* alpha, double eta, float* x, double* norm_sq_out,
                                 uint64_t* sat_count, void* workspace, size_t workspace_bytes,
                                 void* hip_stream) {
-  INTSGD_TRY(validate_desc(desc));
-  INTSGD_TRY(validate_worker_ptrs((const void* const*)grads, desc->n));
-  INTSGD_TRY(validate_vec(x));
-  if (alpha == nullptr || norm_sq_out == nullptr || sat_count == nullptr) return INTSGD_EINVAL;
-  INTSGD_TRY(validate_rule(0.0, 0.0, eta));
-  INTSGD_TRY(validate_workspace(desc, workspace, workspace_bytes));
-  Tiling t;
-  INTSGD_TRY(make_tiling(desc, hip_stream, &t));
-  WorkerPtrs g;
-  fill_ptrs(&g, (const void* const*)grads, desc->n);
-  uint64_t* sat_partial = ws_sat(desc, workspace);
-  hipError_t e = launch_step_fused(t.tm, t.ls, desc->n, round_spec(desc), g, alpha, eta, x,
-                                   ws_norm(workspace), sat_partial);
-  if (e != hipSuccess) return hip_fail(e);
-  return done(launch_finalize(t.ls.stream, ws_norm(workspace), t.tile_prefix, t.tm.num_tiles,
-                              desc->num_blocks, norm_sq_out, sat_partial, t.ls.grid, desc->n,
-                              sat_count));
+  return step_fused_impl(desc, grads, alpha, eta, x, norm_sq_out, sat_count, workspace,
+                         workspace_bytes, hip_stream, nullptr, nullptr, 0.0, 0.0);
 }
 
-intsgd_status intsgd_set_tuning(uint32_t tile_coords, uint32_t max_workgroups) {
-  if (tile_coords != 0 &&
-      (tile_coords < kMinTile || tile_coords > kMaxTile || tile_coords % kMinTile != 0))
-    return INTSGD_EINVAL;
-  if (max_workgroups > kMaxGrid) return INTSGD_EINVAL;
+intsgd_status intsgd_step_fused_next_alpha(const intsgd_desc* desc, const float* const* grads,
+                                           float* alpha, double eta, float* x, double* r,
+                                           double beta, double eps, double* norm_sq_out,
+                                           uint64_t* sat_count, void* workspace,
+                                           size_t workspace_bytes, void* hip_stream) {
+  if (r == nullptr) return INTSGD_EINVAL;
+  return step_fused_impl(desc, grads, alpha, eta, x, norm_sq_out, sat_count, workspace,
+                         workspace_bytes, hip_stream, r, alpha, beta, eps);
+}
+
+intsgd_status intsgd_set_tuning(const intsgd_tuning* tuning) {
+  if (tuning == nullptr) return INTSGD_EINVAL;
+  const uint32_t tile = tuning->tile_coords, grid = tuning->max_workgroups,
+                 wgs = tuning->workgroups_per_cu;
+  if (tile != 0 && (tile < kMinTile || tile > kMaxTile || tile % kMinTile != 0)) return INTSGD_EINVAL;
+  if (grid > kMaxGrid) return INTSGD_EINVAL;
+  if (wgs != 0 && (wgs < 2 || wgs > 8)) return INTSGD_EINVAL;
   std::lock_guard<std::mutex> lock(g_mutex);
-  if (tile_coords != 0) g_tile = tile_coords;
-  if (max_workgroups != 0) g_max_grid = max_workgroups;
+  if (tile != 0) g_tuning.tile_coords = tile;
+  if (grid != 0) g_tuning.max_workgroups = grid;
+  if (wgs != 0) g_tuning.workgroups_per_cu = wgs;
   return INTSGD_OK;
 }
 
-void intsgd_get_tuning(uint32_t* tile_coords, uint32_t* max_workgroups) {
-  if (tile_coords) *tile_coords = g_tile;
-  if (max_workgroups) *max_workgroups = g_max_grid;
+void intsgd_get_tuning(intsgd_tuning* tuning) {
+  if (tuning) *tuning = g_tuning;
 }
 
 const char* intsgd_status_string(intsgd_status status) {

@@ -43,45 +43,63 @@ struct RoundSpec {
   uint32_t step;
 };
 
+#define INTSGD_THREADS_PER_WORKGROUP 512
+
 struct LaunchShape {
   uint32_t grid;         // workgroups along x
+  uint32_t lds_reserve;  // extra dynamic LDS per workgroup (caps workgroups per CU), heavy kernels
   hipStream_t stream;
+};
+
+// The alpha rule of step a8 on device arrays; r == nullptr means "do not apply".
+struct AlphaRule {
+  double* r;                      // B, in/out
+  float* alpha_out;               // B
+  const uint64_t* block_offsets;  // device, B+1, or null when B == 1
+  double beta, eps, eta;
+};
+
+// What the last workgroup of a kernel needs to finish the reductions.
+struct Finish {
+  uint32_t* ticket;               // control word: zero at entry, zero again at exit
+  double* norm_partial;           // one slot per tile
+  const uint32_t* tile_prefix;    // device, B+1: tile range of each block; unused when B == 1
+  uint32_t num_tiles;
+  uint32_t B;
+  double* norm_sq_out;            // B
+  uint32_t* sat_any;              // one flag per workgroup
+  uint64_t* sat_rows;             // [workgroup][n], written only where the flag is set
+  uint32_t n;                     // workers (clip counts)
+  uint64_t* sat_count;            // n
+  uint32_t n_workers;             // n of the problem (alpha rule)
+  uint64_t d;
+  AlphaRule rule;
 };
 
 // Every launcher only enqueues; the return value is hipGetLastError() after the launch.
 hipError_t launch_compress(const TileMap& tm, const LaunchShape& ls, uint32_t n, int32_t wire,
                            const RoundSpec& rs, const WorkerPtrs& grads, const float* alpha,
-                           const WorkerOutPtrs& q_out, uint64_t* sat_partial);
+                           const WorkerOutPtrs& q_out, uint32_t* tickets, uint64_t* sat_partial,
+                           uint64_t* sat_count);
 hipError_t launch_int_sum(uint64_t d, const LaunchShape& ls, uint32_t n, int32_t wire,
                           const WorkerPtrs& q, int32_t* sum_out);
 hipError_t launch_decode_update(const TileMap& tm, const LaunchShape& ls, uint32_t n,
                                 const int32_t* sum, const float* alpha, double eta, float* x,
                                 float* gtilde_out);
 hipError_t launch_update_norm(const TileMap& tm, const LaunchShape& ls, const float* x_new,
-                              const float* x_old, double* norm_partial);
+                              const float* x_old, const Finish& fin);
 hipError_t launch_compress_sum(const TileMap& tm, const LaunchShape& ls, uint32_t n,
                                const RoundSpec& rs, const WorkerPtrs& grads, const float* alpha,
-                               int32_t* sum_out, uint64_t* sat_partial);
+                               int32_t* sum_out, const Finish& fin);
 hipError_t launch_decode_update_norm(const TileMap& tm, const LaunchShape& ls, uint32_t n,
                                      const int32_t* sum, const float* alpha, double eta, float* x,
-                                     double* norm_partial);
+                                     const Finish& fin);
 hipError_t launch_step_fused(const TileMap& tm, const LaunchShape& ls, uint32_t n,
                              const RoundSpec& rs, const WorkerPtrs& grads, const float* alpha,
-                             double eta, float* x, double* norm_partial, uint64_t* sat_partial);
-
-// Fixed-order reduction of the per-tile norm partials into norm_sq_out[B] (skipped
-// when norm_sq_out is null) and of the per-workgroup clip counts into sat_count[n]
-// (skipped when sat_count is null).  tile_prefix (device, B+1 entries) gives each
-// block's tile range; null means one block owning [0, num_tiles).
-hipError_t launch_finalize(hipStream_t stream, const double* norm_partial,
-                           const uint32_t* tile_prefix, uint32_t num_tiles, uint32_t B,
-                           double* norm_sq_out, const uint64_t* sat_partial, uint32_t grid,
-                           uint32_t n, uint64_t* sat_count);
-
-// block_offsets: device array of B+1 offsets, or null when B == 1.
-hipError_t launch_next_alpha(hipStream_t stream, const double* norm_sq, double* r, uint32_t B,
-                             const uint64_t* block_offsets, uint64_t d, uint32_t n, double beta,
-                             double eps, double eta, float* alpha_out);
+                             double eta, float* x, const Finish& fin);
+hipError_t launch_next_alpha(hipStream_t stream, const double* norm_sq, const AlphaRule& rule,
+                             uint32_t B, uint32_t n, uint64_t d);
+hipError_t launch_zero_control(hipStream_t stream, uint32_t* words, uint32_t count);
 
 }  // namespace intsgd
 

@@ -1,17 +1,26 @@
 // HIP kernels of the IntSGD step for gfx950 (CDNA4, 64-wide wavefronts).
 //
 // The whole path is a streaming scan (no reuse, no dense contraction), so the
-// design goal is HBM bandwidth: every thread moves 16 bytes per stream per
-// iteration (dwordx4), the n gradient streams are read with non-temporal loads
-// in groups of up to 8 independent loads in flight per lane, base addresses are
-// wave-uniform (SGPR) with a 32-bit lane offset, the integer aggregate stays in
-// registers in the fused forms, and the only cross-lane traffic is the norm
-// reduction (DPP inside a wavefront, then LDS across the four wavefronts).
+// design goal is HBM bandwidth:
+//   * every lane moves 16 bytes per stream per access (buffer_load/store_dwordx4)
+//     through a wave-uniform buffer descriptor + 32-bit lane offset; the descriptor
+//     covers exactly the tile, so a stray lane offset cannot leave it;
+//   * gradient streams are read non-temporally, up to 8 independent loads in flight
+//     per lane; x is written through (sc1) so that no dirty lines pile up in L2;
+//   * the integer aggregate stays in registers in the fused forms;
+//   * a workgroup is 512 threads and normally handles ONE tile of 2048 coordinates
+//     (8 KB per stream), and residency is capped (by an LDS reservation) at two
+//     workgroups per CU: with a write stream mixed into the reads, fewer, larger
+//     requests in flight measured faster than full occupancy;
+//   * each kernel finishes its own reductions: per-tile norm partials and per-
+//     workgroup clip counts go to the workspace, a ticket makes the last workgroup
+//     sum them in a fixed order (and, if asked, apply the alpha rule), so one step is
+//     one launch and nothing is zeroed between steps (the ticket resets itself).
 //
-// Work is cut into tiles of `tile` coordinates that never straddle a block of
-// Algorithm 2, so alpha is wave-uniform inside a tile.  A tile whose ends are not
-// multiples of four coordinates handles its <= 3 head and <= 3 tail coordinates
-// one by one; everything in between moves as aligned quads.
+// Work is cut into tiles that never straddle a block of Algorithm 2, so alpha is
+// wave-uniform inside a tile.  A tile whose ends are not multiples of four
+// coordinates handles its <= 3 head and <= 3 tail coordinates one by one;
+// everything in between moves as aligned quads.
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -21,7 +30,7 @@
 namespace intsgd {
 namespace {
 
-constexpr uint32_t kThreads = 256;
+constexpr uint32_t kThreads = INTSGD_THREADS_PER_WORKGROUP;
 constexpr uint32_t kWaves = kThreads / 64;
 
 // Native 16-byte vectors (one dwordx4 access each).
@@ -29,12 +38,50 @@ typedef float vf4 __attribute__((ext_vector_type(4)));
 typedef int32_t vi4 __attribute__((ext_vector_type(4)));
 typedef uint32_t vu4 __attribute__((ext_vector_type(4)));
 
+// Cache-policy bits of buffer instructions on gfx950 (the aux operand).
+constexpr int kPlain = 0;
+constexpr int kNonTemporal = 2;    // nt: streaming data, not reused
+constexpr int kWriteThrough = 16;  // sc1: store goes through L2 to memory
+
+#ifndef INTSGD_GRAD_LOAD_POLICY
+#define INTSGD_GRAD_LOAD_POLICY kNonTemporal
+#endif
+#ifndef INTSGD_X_LOAD_POLICY
+#define INTSGD_X_LOAD_POLICY kPlain
+#endif
+#ifndef INTSGD_X_STORE_POLICY
+#define INTSGD_X_STORE_POLICY kWriteThrough
+#endif
+
+// ------------------------------------------------------------------ buffer access
+// Raw buffer descriptor over [base, base+bytes): dword 3 = 0x00020000 selects the
+// 32-bit raw format on gfx90a/gfx94x/gfx950.  Out-of-range lanes read 0 / are dropped.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_stream(const void* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+template <int POLICY>
+__device__ __forceinline__ vu4 load128(__amdgpu_buffer_rsrc_t s, uint32_t byte_off) {
+  return __builtin_amdgcn_raw_buffer_load_b128(s, (int)byte_off, 0, POLICY);
+}
+template <int POLICY>
+__device__ __forceinline__ void store128(__amdgpu_buffer_rsrc_t s, uint32_t byte_off, vu4 v) {
+  __builtin_amdgcn_raw_buffer_store_b128(v, s, (int)byte_off, 0, POLICY);
+}
+template <int POLICY>
+__device__ __forceinline__ void store32(__amdgpu_buffer_rsrc_t s, uint32_t byte_off, uint32_t v) {
+  __builtin_amdgcn_raw_buffer_store_b32(v, s, (int)byte_off, 0, POLICY);
+}
+__device__ __forceinline__ vf4 as_f(vu4 v) { return __builtin_bit_cast(vf4, v); }
+__device__ __forceinline__ vi4 as_i(vu4 v) { return __builtin_bit_cast(vi4, v); }
+__device__ __forceinline__ vu4 as_u(vf4 v) { return __builtin_bit_cast(vu4, v); }
+__device__ __forceinline__ vu4 as_u(vi4 v) { return __builtin_bit_cast(vu4, v); }
+
 // ------------------------------------------------------------------ Philox4x32-10
 // Counter-based generator of Salmon et al. (SC'11), written from its description:
 // ten rounds of two 32x32->64 multiplies, a word permutation and key injection,
 // with the key bumped by Weyl constants between rounds.
 __device__ __forceinline__ vu4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
-                                               uint32_t k0, uint32_t k1) {
+                                             uint32_t k0, uint32_t k1) {
 #pragma unroll
   for (int round = 0; round < 10; ++round) {
     const uint64_t p0 = (uint64_t)0xD2511F53u * (uint64_t)c0;
@@ -128,16 +175,23 @@ __device__ __forceinline__ double wave_sum(double v) {
   return (read_lane(v, 0) + read_lane(v, 16)) + (read_lane(v, 32) + read_lane(v, 48));
 }
 
+// LDS shared by the reductions of one kernel.
+struct ReduceLds {
+  double red[2][kWaves];            // double-buffered wave sums
+  unsigned long long sat[INTSGD_MAX_WORKERS];
+  uint32_t is_last;
+};
+
 // Sum over the workgroup; the result is valid in thread 0 only.  `slot` must
 // alternate between consecutive calls (double-buffered LDS, one barrier per call).
-__device__ __forceinline__ double block_sum(double v, double (*lds)[kWaves], uint32_t slot) {
+__device__ __forceinline__ double block_sum(double v, ReduceLds& lds, uint32_t slot) {
   const double w = wave_sum(v);
-  if ((threadIdx.x & 63u) == 0) lds[slot][threadIdx.x >> 6] = w;
+  if ((threadIdx.x & 63u) == 0) lds.red[slot][threadIdx.x >> 6] = w;
   __syncthreads();
   double total = 0.0;
   if (threadIdx.x == 0) {
 #pragma unroll
-    for (uint32_t k = 0; k < kWaves; ++k) total += lds[slot][k];
+    for (uint32_t k = 0; k < kWaves; ++k) total += lds.red[slot][k];
   }
   return total;
 }
@@ -166,7 +220,8 @@ __device__ __forceinline__ Tile locate(const TileMap& tm, uint32_t t) {
 }
 
 // Runs `op` over this workgroup's tiles (grid-stride).  Op provides
-//   begin_tile(blk), scalar(j), begin_body(q0), quad(lane_quad), end_tile(t, iter).
+//   begin_tile(blk), scalar(j), begin_body(first_quad, quads), quad(lane_quad),
+//   end_tile(t, iter).
 template <class Op>
 __device__ __forceinline__ void drive_tiles(const TileMap& tm, Op& op) {
   const uint32_t tid = threadIdx.x;
@@ -181,38 +236,27 @@ __device__ __forceinline__ void drive_tiles(const TileMap& tm, Op& op) {
     op.begin_tile(tl.blk);
     if (s + tid < a) op.scalar(s + tid);
     const uint32_t nq = (uint32_t)((b - a) >> 2);
-    op.begin_body(a >> 2);
+    op.begin_body(a >> 2, nq);
     for (uint32_t ql = tid; ql < nq; ql += kThreads) op.quad(ql);
     if (b + tid < e) op.scalar(b + tid);
     op.end_tile(t, iter);
   }
 }
 
-template <class T>
-__device__ __forceinline__ T load_stream(const void* base, uint32_t byte_off) {
-  return __builtin_nontemporal_load((const T*)((const char*)base + byte_off));
-}
-template <class T>
-__device__ __forceinline__ T load_plain(const void* base, uint32_t byte_off) {
-  return *(const T*)((const char*)base + byte_off);
-}
-template <class T>
-__device__ __forceinline__ void store_plain(void* base, uint32_t byte_off, const T& v) {
-  *(T*)((char*)base + byte_off) = v;
-}
-
 // ------------------------------------------------------------------ a1-a4 on one quad
-// Scales, rounds, clips and accumulates workers [i0, i0+W) for the quad at lane byte
-// offset `off` (16 bytes per quad) from the per-worker uniform bases.
+// Scales, rounds, clips and accumulates workers [i0, i0+W) for lane quad `ql` of the
+// tile body that starts at quad q0 and holds nq quads.
 template <int ROUND, int W>
 __device__ __forceinline__ void accumulate_workers(const WorkerPtrs& grads, uint32_t i0,
-                                                   uint64_t q0, uint32_t ql, float alpha,
-                                                   const RoundSpec& rs, vi4& S,
+                                                   uint64_t q0, uint32_t nq, uint32_t ql,
+                                                   float alpha, const RoundSpec& rs, vi4& S,
                                                    unsigned long long* lds_sat) {
   vf4 g[W];
 #pragma unroll
-  for (int w = 0; w < W; ++w)
-    g[w] = load_stream<vf4>((const vf4*)grads.p[i0 + w] + q0, ql * 16u);
+  for (int w = 0; w < W; ++w) {
+    const __amdgpu_buffer_rsrc_t src = make_stream((const vf4*)grads.p[i0 + w] + q0, nq * 16u);
+    g[w] = as_f(load128<INTSGD_GRAD_LOAD_POLICY>(src, ql * 16u));
+  }
   const uint64_t quad = q0 + ql;
 #pragma unroll
   for (int w = 0; w < W; ++w) {
@@ -231,14 +275,14 @@ __device__ __forceinline__ void accumulate_workers(const WorkerPtrs& grads, uint
 
 template <int ROUND>
 __device__ __forceinline__ vi4 aggregate_quad(const WorkerPtrs& grads, uint32_t n, uint64_t q0,
-                                               uint32_t ql, float alpha, const RoundSpec& rs,
-                                               unsigned long long* lds_sat) {
+                                              uint32_t nq, uint32_t ql, float alpha,
+                                              const RoundSpec& rs, unsigned long long* lds_sat) {
   vi4 S = vi4{0, 0, 0, 0};
   uint32_t i = 0;
-  for (; i + 8 <= n; i += 8) accumulate_workers<ROUND, 8>(grads, i, q0, ql, alpha, rs, S, lds_sat);
-  if (n - i >= 4) { accumulate_workers<ROUND, 4>(grads, i, q0, ql, alpha, rs, S, lds_sat); i += 4; }
-  if (n - i >= 2) { accumulate_workers<ROUND, 2>(grads, i, q0, ql, alpha, rs, S, lds_sat); i += 2; }
-  if (n - i >= 1) { accumulate_workers<ROUND, 1>(grads, i, q0, ql, alpha, rs, S, lds_sat); }
+  for (; i + 8 <= n; i += 8) accumulate_workers<ROUND, 8>(grads, i, q0, nq, ql, alpha, rs, S, lds_sat);
+  if (n - i >= 4) { accumulate_workers<ROUND, 4>(grads, i, q0, nq, ql, alpha, rs, S, lds_sat); i += 4; }
+  if (n - i >= 2) { accumulate_workers<ROUND, 2>(grads, i, q0, nq, ql, alpha, rs, S, lds_sat); i += 2; }
+  if (n - i >= 1) { accumulate_workers<ROUND, 1>(grads, i, q0, nq, ql, alpha, rs, S, lds_sat); }
   return S;
 }
 
@@ -251,7 +295,7 @@ __device__ __forceinline__ int32_t compress_scalar(const void* g, uint64_t j, ui
   if (ROUND == INTSGD_ROUND_STOCHASTIC) {
     const uint64_t quad = j >> 2;
     const vu4 rw = philox4x32_10((uint32_t)quad, (uint32_t)(quad >> 32), worker, rs.step,
-                                   rs.key0, rs.key1);
+                                 rs.key0, rs.key1);
     word = pick_word(rw, (uint32_t)(j & 3));
   }
   return round_clip<ROUND>(alpha * gv, word, rs, sat);
@@ -281,127 +325,190 @@ __device__ __forceinline__ float update_coord(float x, int32_t S, double c, doub
   return xn;
 }
 
+__device__ __forceinline__ vf4 update_quad(vf4 xv, vi4 S, double c, double& acc) {
+  vf4 xn;
+  xn.x = update_coord(xv.x, S.x, c, acc);
+  xn.y = update_coord(xv.y, S.y, c, acc);
+  xn.z = update_coord(xv.z, S.z, c, acc);
+  xn.w = update_coord(xv.w, S.w, c, acc);
+  return xn;
+}
+
 __device__ __forceinline__ double decode_constant(double eta, uint32_t n, float alpha) {
   return eta / ((double)n * (double)alpha);
 }
 
-__device__ __forceinline__ void zero_sat(unsigned long long* lds_sat) {
-  if (threadIdx.x < INTSGD_MAX_WORKERS) lds_sat[threadIdx.x] = 0ull;
+// ------------------------------------------------------------------ a8
+// Section 4.1 (Proposition 2) for one block, Algorithm 2 otherwise; fp64, in the
+// operation order written in the public header.
+__device__ __forceinline__ void apply_alpha_rule(const AlphaRule& rule, uint32_t B, uint32_t n,
+                                                 uint64_t d, uint32_t l, double norm_sq) {
+  const double keep = rule.beta * rule.r[l];
+  const double fresh = (1.0 - rule.beta) * norm_sq;
+  const double rl = keep + fresh;
+  rule.r[l] = rl;
+  double alpha;
+  if (B == 1) {
+    const double den = 2.0 * (double)n * rl / (rule.eta * rule.eta) + rule.eps * rule.eps;
+    alpha = sqrt((double)d) / sqrt(den);
+  } else {
+    const double dl = (double)(rule.block_offsets[l + 1] - rule.block_offsets[l]);
+    const double den =
+        2.0 * (double)n * rl + rule.eta * rule.eta * (dl / (double)d) * rule.eps * rule.eps;
+    alpha = rule.eta * sqrt(dl) / sqrt(den);
+  }
+  rule.alpha_out[l] = (float)alpha;
+}
+
+// ------------------------------------------------------------------ end-of-kernel reductions
+// Clip counts of this workgroup -> workspace row (only when some are non-zero).
+__device__ __forceinline__ void publish_sat(const Finish& f, const ReduceLds& lds, uint32_t wg) {
+  bool any = false;
+  for (uint32_t i = 0; i < f.n; ++i) any |= lds.sat[i] != 0ull;
+  f.sat_any[wg] = any ? 1u : 0u;
+  if (any)
+    for (uint32_t i = 0; i < f.n; ++i) f.sat_rows[(uint64_t)wg * f.n + i] = lds.sat[i];
+}
+
+// Takes a ticket; true in every thread of the workgroup that arrived last, after
+// which all workgroups' published partials are visible to it.  Thread 0 must have
+// issued this workgroup's partial stores itself.
+__device__ __forceinline__ bool arrive_last(uint32_t* ticket, uint32_t total, ReduceLds& lds) {
+  if (threadIdx.x == 0) {
+    __threadfence();                                   // release this workgroup's partials
+    const uint32_t t = atomicAdd(ticket, 1u);
+    lds.is_last = (t == total - 1u) ? 1u : 0u;
+  }
+  __syncthreads();
+  const bool last = lds.is_last != 0u;
+  if (last) __threadfence();                           // acquire everyone else's
+  return last;
+}
+
+// Run by the last workgroup: fixed-order sums of the norm partials (per block), the
+// optional alpha rule, the clip counts, and the ticket reset.
+template <bool WITH_NORM, bool WITH_SAT>
+__device__ __forceinline__ void final_sums(const Finish& f, ReduceLds& lds, uint32_t workgroups) {
+  const uint32_t tid = threadIdx.x;
+  if (WITH_NORM) {
+    if (f.B == 1) {
+      double acc = 0.0;
+      for (uint32_t t = tid; t < f.num_tiles; t += kThreads) acc += f.norm_partial[t];
+      const double total = block_sum(acc, lds, 0);
+      if (tid == 0) {
+        f.norm_sq_out[0] = total;
+        if (f.rule.r != nullptr) apply_alpha_rule(f.rule, 1, f.n_workers, f.d, 0, total);
+      }
+    } else {
+      const uint32_t lane = tid & 63u;
+      for (uint32_t l = tid >> 6; l < f.B; l += kWaves) {     // one wavefront per block
+        const uint32_t t0 = f.tile_prefix[l], t1 = f.tile_prefix[l + 1];
+        double acc = 0.0;
+        for (uint32_t t = t0 + lane; t < t1; t += 64u) acc += f.norm_partial[t];
+        const double total = wave_sum(acc);
+        if (lane == 0) {
+          f.norm_sq_out[l] = total;
+          if (f.rule.r != nullptr) apply_alpha_rule(f.rule, f.B, f.n_workers, f.d, l, total);
+        }
+      }
+    }
+  }
+  if (WITH_SAT) {
+    __syncthreads();
+    if (tid < INTSGD_MAX_WORKERS) lds.sat[tid] = 0ull;
+    __syncthreads();
+    for (uint32_t g = tid; g < workgroups; g += kThreads) {
+      if (f.sat_any[g] != 0u)
+        for (uint32_t i = 0; i < f.n; ++i) {
+          const unsigned long long c = f.sat_rows[(uint64_t)g * f.n + i];
+          if (c != 0ull) atomicAdd(&lds.sat[i], c);
+        }
+    }
+    __syncthreads();
+    if (tid < f.n) f.sat_count[tid] = lds.sat[tid];
+  }
+  if (tid == 0) *f.ticket = 0u;                       // ready for the next launch
+}
+
+__device__ __forceinline__ void zero_sat(ReduceLds& lds) {
+  if (threadIdx.x < INTSGD_MAX_WORKERS) lds.sat[threadIdx.x] = 0ull;
   __syncthreads();
 }
 
-// sat_partial layout: [worker][workgroup].
-__device__ __forceinline__ void flush_sat(const unsigned long long* lds_sat, uint32_t n,
-                                          uint64_t* sat_partial) {
-  __syncthreads();
-  if (threadIdx.x < n) sat_partial[(uint64_t)threadIdx.x * gridDim.x + blockIdx.x] = lds_sat[threadIdx.x];
-}
-
-// ================================================================== F3: a1-a7
-struct StepArgs {
+// ================================================================== F3 (a1-a7) and F1 (a1-a4)
+struct AggregateArgs {
   TileMap tm;
   RoundSpec rs;
   uint32_t n;
   const float* alpha;
-  double eta;
-  float* x;
-  double* norm_partial;
-  uint64_t* sat_partial;
+  double eta;            // F3
+  float* x;              // F3
+  int32_t* sum_out;      // F1
+  Finish fin;
   WorkerPtrs grads;
 };
 
-template <int ROUND>
-struct StepFusedOp {
-  const StepArgs& a;
-  unsigned long long* lds_sat;
-  double (*lds_red)[kWaves];
+template <int ROUND, bool FUSED>
+struct AggregateOp {
+  const AggregateArgs& a;
+  ReduceLds& lds;
   float alpha;
   double c, acc;
   uint64_t q0;
+  uint32_t nq;
+  __amdgpu_buffer_rsrc_t out;   // x (F3) or the aggregate (F1) of this tile body
 
+  __device__ __forceinline__ AggregateOp(const AggregateArgs& args, ReduceLds& l)
+      : a(args), lds(l), alpha(0.f), c(0.0), acc(0.0), q0(0), nq(0) {}
   __device__ __forceinline__ void begin_tile(uint32_t blk) {
     alpha = a.alpha[blk];
-    c = decode_constant(a.eta, a.n, alpha);
+    if (FUSED) c = decode_constant(a.eta, a.n, alpha);
     acc = 0.0;
   }
   __device__ __forceinline__ void scalar(uint64_t j) {
-    const int32_t S = aggregate_scalar<ROUND>(a.grads, a.n, j, alpha, a.rs, lds_sat);
-    a.x[j] = update_coord(a.x[j], S, c, acc);
+    const int32_t S = aggregate_scalar<ROUND>(a.grads, a.n, j, alpha, a.rs, lds.sat);
+    if (FUSED) a.x[j] = update_coord(a.x[j], S, c, acc);
+    else a.sum_out[j] = S;
   }
-  __device__ __forceinline__ void begin_body(uint64_t first_quad) { q0 = first_quad; }
+  __device__ __forceinline__ void begin_body(uint64_t first_quad, uint32_t quads) {
+    q0 = first_quad;
+    nq = quads;
+    out = FUSED ? make_stream((vf4*)a.x + q0, nq * 16u) : make_stream((vi4*)a.sum_out + q0, nq * 16u);
+  }
   __device__ __forceinline__ void quad(uint32_t ql) {
-    vf4* xb = (vf4*)a.x + q0;
-    const vf4 xv = load_plain<vf4>(xb, ql * 16u);
-    const vi4 S = aggregate_quad<ROUND>(a.grads, a.n, q0, ql, alpha, a.rs, lds_sat);
-    vf4 xn;
-    xn.x = update_coord(xv.x, S.x, c, acc);
-    xn.y = update_coord(xv.y, S.y, c, acc);
-    xn.z = update_coord(xv.z, S.z, c, acc);
-    xn.w = update_coord(xv.w, S.w, c, acc);
-    store_plain(xb, ql * 16u, xn);
+    vf4 xv = vf4{0.f, 0.f, 0.f, 0.f};
+    if (FUSED) xv = as_f(load128<INTSGD_X_LOAD_POLICY>(out, ql * 16u));
+    const vi4 S = aggregate_quad<ROUND>(a.grads, a.n, q0, nq, ql, alpha, a.rs, lds.sat);
+    if (FUSED) store128<INTSGD_X_STORE_POLICY>(out, ql * 16u, as_u(update_quad(xv, S, c, acc)));
+    else store128<INTSGD_X_STORE_POLICY>(out, ql * 16u, as_u(S));
   }
   __device__ __forceinline__ void end_tile(uint32_t t, uint32_t iter) {
-    const double total = block_sum(acc, lds_red, iter & 1u);
-    if (threadIdx.x == 0) a.norm_partial[t] = total;
+    if (FUSED) {
+      const double total = block_sum(acc, lds, iter & 1u);
+      if (threadIdx.x == 0) a.fin.norm_partial[t] = total;
+    }
   }
 };
 
-template <int ROUND>
-__global__ __launch_bounds__(kThreads) void k_step_fused(const StepArgs a) {
-  __shared__ unsigned long long lds_sat[INTSGD_MAX_WORKERS];
-  __shared__ double lds_red[2][kWaves];
-  zero_sat(lds_sat);
-  StepFusedOp<ROUND> op{a, lds_sat, lds_red, 0.f, 0.0, 0.0, 0};
+template <int ROUND, bool FUSED>
+__global__ __launch_bounds__(kThreads) void k_aggregate(const AggregateArgs a) {
+  __shared__ ReduceLds lds;
+  zero_sat(lds);
+  AggregateOp<ROUND, FUSED> op(a, lds);
   drive_tiles(a.tm, op);
-  flush_sat(lds_sat, a.n, a.sat_partial);
-}
-
-// ================================================================== F1: a1-a4
-struct CompressSumArgs {
-  TileMap tm;
-  RoundSpec rs;
-  uint32_t n;
-  const float* alpha;
-  int32_t* sum_out;
-  uint64_t* sat_partial;
-  WorkerPtrs grads;
-};
-
-template <int ROUND>
-struct CompressSumOp {
-  const CompressSumArgs& a;
-  unsigned long long* lds_sat;
-  float alpha;
-  uint64_t q0;
-
-  __device__ __forceinline__ void begin_tile(uint32_t blk) { alpha = a.alpha[blk]; }
-  __device__ __forceinline__ void scalar(uint64_t j) {
-    a.sum_out[j] = aggregate_scalar<ROUND>(a.grads, a.n, j, alpha, a.rs, lds_sat);
-  }
-  __device__ __forceinline__ void begin_body(uint64_t first_quad) { q0 = first_quad; }
-  __device__ __forceinline__ void quad(uint32_t ql) {
-    const vi4 S = aggregate_quad<ROUND>(a.grads, a.n, q0, ql, alpha, a.rs, lds_sat);
-    store_plain((vi4*)a.sum_out + q0, ql * 16u, S);
-  }
-  __device__ __forceinline__ void end_tile(uint32_t, uint32_t) {}
-};
-
-template <int ROUND>
-__global__ __launch_bounds__(kThreads) void k_compress_sum(const CompressSumArgs a) {
-  __shared__ unsigned long long lds_sat[INTSGD_MAX_WORKERS];
-  zero_sat(lds_sat);
-  CompressSumOp<ROUND> op{a, lds_sat, 0.f, 0};
-  drive_tiles(a.tm, op);
-  flush_sat(lds_sat, a.n, a.sat_partial);
+  __syncthreads();
+  if (threadIdx.x == 0) publish_sat(a.fin, lds, blockIdx.x);
+  if (arrive_last(a.fin.ticket, gridDim.x, lds)) final_sums<FUSED, true>(a.fin, lds, gridDim.x);
 }
 
 // ================================================================== a1-a3 (one worker per blockIdx.y)
 struct CompressArgs {
   TileMap tm;
   RoundSpec rs;
-  uint32_t n;
   const float* alpha;
-  uint64_t* sat_partial;
+  uint32_t* tickets;       // one per worker
+  uint64_t* sat_partial;   // [worker][workgroup]
+  uint64_t* sat_count;
   WorkerPtrs grads;
   WorkerOutPtrs q_out;
 };
@@ -409,25 +516,32 @@ struct CompressArgs {
 template <int ROUND, int WIRE>
 struct CompressOp {
   const CompressArgs& a;
+  ReduceLds& lds;
   uint32_t worker;
   const void* g;
   void* q;
   float alpha;
   uint64_t q0;
-  uint32_t cnt;   // wave-uniform running clip count of this wavefront
+  __amdgpu_buffer_rsrc_t src, dst;
 
+  __device__ __forceinline__ CompressOp(const CompressArgs& args, ReduceLds& l, uint32_t w)
+      : a(args), lds(l), worker(w), g(args.grads.p[w]), q(args.q_out.p[w]), alpha(0.f), q0(0) {}
   __device__ __forceinline__ void begin_tile(uint32_t blk) { alpha = a.alpha[blk]; }
   __device__ __forceinline__ void scalar(uint64_t j) {
     bool sat;
     const int32_t v = compress_scalar<ROUND>(g, j, worker, alpha, a.rs, sat);
     if (WIRE == INTSGD_WIRE_INT8) ((int8_t*)q)[j] = (int8_t)v;
     else ((int32_t*)q)[j] = v;
-    // the head/tail branch is divergent: count per lane through LDS-free atomics
-    if (sat) atomicAdd(&a.sat_partial[(uint64_t)worker * gridDim.x + blockIdx.x], 1ull);
+    if (sat) atomicAdd(&lds.sat[0], 1ull);
   }
-  __device__ __forceinline__ void begin_body(uint64_t first_quad) { q0 = first_quad; }
+  __device__ __forceinline__ void begin_body(uint64_t first_quad, uint32_t quads) {
+    q0 = first_quad;
+    src = make_stream((const vf4*)g + q0, quads * 16u);
+    dst = (WIRE == INTSGD_WIRE_INT8) ? make_stream((uint32_t*)q + q0, quads * 4u)
+                                     : make_stream((vi4*)q + q0, quads * 16u);
+  }
   __device__ __forceinline__ void quad(uint32_t ql) {
-    const vf4 gv = load_stream<vf4>((const vf4*)g + q0, ql * 16u);
+    const vf4 gv = as_f(load128<INTSGD_GRAD_LOAD_POLICY>(src, ql * 16u));
     const uint64_t quad = q0 + ql;
     vu4 rw = vu4{0u, 0u, 0u, 0u};
     if (ROUND == INTSGD_ROUND_STOCHASTIC)
@@ -439,13 +553,14 @@ struct CompressOp {
     v.y = round_clip<ROUND>(alpha * gv.y, rw.y, a.rs, s1);
     v.z = round_clip<ROUND>(alpha * gv.z, rw.z, a.rs, s2);
     v.w = round_clip<ROUND>(alpha * gv.w, rw.w, a.rs, s3);
-    cnt += count_lanes(s0) + count_lanes(s1) + count_lanes(s2) + count_lanes(s3);
+    const uint32_t cnt = count_lanes(s0) + count_lanes(s1) + count_lanes(s2) + count_lanes(s3);
+    if (cnt != 0 && (threadIdx.x & 63u) == 0) atomicAdd(&lds.sat[0], (unsigned long long)cnt);
     if (WIRE == INTSGD_WIRE_INT8) {
       const uint32_t packed = ((uint32_t)v.x & 0xFFu) | (((uint32_t)v.y & 0xFFu) << 8) |
                               (((uint32_t)v.z & 0xFFu) << 16) | (((uint32_t)v.w & 0xFFu) << 24);
-      store_plain((uint32_t*)q + q0, ql * 4u, packed);
+      store32<kPlain>(dst, ql * 4u, packed);
     } else {
-      store_plain((vi4*)q + q0, ql * 16u, v);
+      store128<kPlain>(dst, ql * 16u, as_u(v));
     }
   }
   __device__ __forceinline__ void end_tile(uint32_t, uint32_t) {}
@@ -453,13 +568,27 @@ struct CompressOp {
 
 template <int ROUND, int WIRE>
 __global__ __launch_bounds__(kThreads) void k_compress(const CompressArgs a) {
+  __shared__ ReduceLds lds;
+  zero_sat(lds);
   const uint32_t worker = blockIdx.y;
-  uint64_t* slot = &a.sat_partial[(uint64_t)worker * gridDim.x + blockIdx.x];
-  if (threadIdx.x == 0) *slot = 0ull;
-  __syncthreads();
-  CompressOp<ROUND, WIRE> op{a, worker, a.grads.p[worker], a.q_out.p[worker], 0.f, 0, 0};
+  CompressOp<ROUND, WIRE> op(a, lds, worker);
   drive_tiles(a.tm, op);
-  if ((threadIdx.x & 63u) == 0 && op.cnt != 0) atomicAdd(slot, (unsigned long long)op.cnt);
+  __syncthreads();
+  uint64_t* row = a.sat_partial + (uint64_t)worker * gridDim.x;
+  if (threadIdx.x == 0) row[blockIdx.x] = lds.sat[0];
+  if (arrive_last(&a.tickets[worker], gridDim.x, lds)) {
+    // last workgroup of this worker: sum its row
+    if (threadIdx.x == 0) lds.sat[1] = 0ull;
+    __syncthreads();
+    unsigned long long acc = 0ull;
+    for (uint32_t g = threadIdx.x; g < gridDim.x; g += kThreads) acc += row[g];
+    if (acc != 0ull) atomicAdd(&lds.sat[1], acc);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      a.sat_count[worker] = lds.sat[1];
+      a.tickets[worker] = 0u;
+    }
+  }
 }
 
 // ================================================================== a4
@@ -514,16 +643,18 @@ struct DecodeArgs {
   double eta;
   float* x;
   float* gtilde;         // decode_update only, may be null
-  double* norm_partial;  // F2 only
+  Finish fin;            // F2 only
 };
 
 template <bool WITH_NORM, bool WITH_GTILDE>
 struct DecodeOp {
   const DecodeArgs& a;
-  double (*lds_red)[kWaves];
+  ReduceLds& lds;
   double c, na, acc;
-  uint64_t q0;
+  __amdgpu_buffer_rsrc_t sum_s, x_s, gt_s;
 
+  __device__ __forceinline__ DecodeOp(const DecodeArgs& args, ReduceLds& l)
+      : a(args), lds(l), c(0.0), na(0.0), acc(0.0) {}
   __device__ __forceinline__ void begin_tile(uint32_t blk) {
     const float alpha = a.alpha[blk];
     na = (double)a.n * (double)alpha;
@@ -536,35 +667,36 @@ struct DecodeOp {
     a.x[j] = update_coord(a.x[j], S, c, acc);
     if (WITH_GTILDE) a.gtilde[j] = gtilde_of(S);
   }
-  __device__ __forceinline__ void begin_body(uint64_t first_quad) { q0 = first_quad; }
+  __device__ __forceinline__ void begin_body(uint64_t q0, uint32_t quads) {
+    sum_s = make_stream((const vi4*)a.sum + q0, quads * 16u);
+    x_s = make_stream((vf4*)a.x + q0, quads * 16u);
+    if (WITH_GTILDE) gt_s = make_stream((vf4*)a.gtilde + q0, quads * 16u);
+  }
   __device__ __forceinline__ void quad(uint32_t ql) {
-    vf4* xb = (vf4*)a.x + q0;
-    const vi4 S = load_stream<vi4>((const vi4*)a.sum + q0, ql * 16u);
-    const vf4 xv = load_plain<vf4>(xb, ql * 16u);
-    vf4 xn;
-    xn.x = update_coord(xv.x, S.x, c, acc);
-    xn.y = update_coord(xv.y, S.y, c, acc);
-    xn.z = update_coord(xv.z, S.z, c, acc);
-    xn.w = update_coord(xv.w, S.w, c, acc);
-    store_plain(xb, ql * 16u, xn);
+    const vi4 S = as_i(load128<kNonTemporal>(sum_s, ql * 16u));
+    const vf4 xv = as_f(load128<INTSGD_X_LOAD_POLICY>(x_s, ql * 16u));
+    store128<INTSGD_X_STORE_POLICY>(x_s, ql * 16u, as_u(update_quad(xv, S, c, acc)));
     if (WITH_GTILDE) {
       const vf4 gt = vf4{gtilde_of(S.x), gtilde_of(S.y), gtilde_of(S.z), gtilde_of(S.w)};
-      store_plain((vf4*)a.gtilde + q0, ql * 16u, gt);
+      store128<kPlain>(gt_s, ql * 16u, as_u(gt));
     }
   }
   __device__ __forceinline__ void end_tile(uint32_t t, uint32_t iter) {
     if (WITH_NORM) {
-      const double total = block_sum(acc, lds_red, iter & 1u);
-      if (threadIdx.x == 0) a.norm_partial[t] = total;
+      const double total = block_sum(acc, lds, iter & 1u);
+      if (threadIdx.x == 0) a.fin.norm_partial[t] = total;
     }
   }
 };
 
 template <bool WITH_NORM, bool WITH_GTILDE>
 __global__ __launch_bounds__(kThreads) void k_decode(const DecodeArgs a) {
-  __shared__ double lds_red[2][kWaves];
-  DecodeOp<WITH_NORM, WITH_GTILDE> op{a, lds_red, 0.0, 0.0, 0.0, 0};
+  __shared__ ReduceLds lds;
+  DecodeOp<WITH_NORM, WITH_GTILDE> op(a, lds);
   drive_tiles(a.tm, op);
+  if (WITH_NORM) {
+    if (arrive_last(a.fin.ticket, gridDim.x, lds)) final_sums<true, false>(a.fin, lds, gridDim.x);
+  }
 }
 
 // ================================================================== a7
@@ -572,99 +704,54 @@ struct NormArgs {
   TileMap tm;
   const float* x_new;
   const float* x_old;
-  double* norm_partial;
+  Finish fin;
 };
 
 struct NormOp {
   const NormArgs& a;
-  double (*lds_red)[kWaves];
+  ReduceLds& lds;
   double acc;
-  uint64_t q0;
+  __amdgpu_buffer_rsrc_t new_s, old_s;
 
+  __device__ __forceinline__ NormOp(const NormArgs& args, ReduceLds& l) : a(args), lds(l), acc(0.0) {}
   __device__ __forceinline__ void add(float xn, float xo) {
     const double delta = (double)xn - (double)xo;
     acc = __builtin_fma(delta, delta, acc);
   }
   __device__ __forceinline__ void begin_tile(uint32_t) { acc = 0.0; }
   __device__ __forceinline__ void scalar(uint64_t j) { add(a.x_new[j], a.x_old[j]); }
-  __device__ __forceinline__ void begin_body(uint64_t first_quad) { q0 = first_quad; }
+  __device__ __forceinline__ void begin_body(uint64_t q0, uint32_t quads) {
+    new_s = make_stream((const vf4*)a.x_new + q0, quads * 16u);
+    old_s = make_stream((const vf4*)a.x_old + q0, quads * 16u);
+  }
   __device__ __forceinline__ void quad(uint32_t ql) {
-    const vf4 n4 = load_stream<vf4>((const vf4*)a.x_new + q0, ql * 16u);
-    const vf4 o4 = load_stream<vf4>((const vf4*)a.x_old + q0, ql * 16u);
+    const vf4 n4 = as_f(load128<kNonTemporal>(new_s, ql * 16u));
+    const vf4 o4 = as_f(load128<kNonTemporal>(old_s, ql * 16u));
     add(n4.x, o4.x); add(n4.y, o4.y); add(n4.z, o4.z); add(n4.w, o4.w);
   }
   __device__ __forceinline__ void end_tile(uint32_t t, uint32_t iter) {
-    const double total = block_sum(acc, lds_red, iter & 1u);
-    if (threadIdx.x == 0) a.norm_partial[t] = total;
+    const double total = block_sum(acc, lds, iter & 1u);
+    if (threadIdx.x == 0) a.fin.norm_partial[t] = total;
   }
 };
 
 __global__ __launch_bounds__(kThreads) void k_update_norm(const NormArgs a) {
-  __shared__ double lds_red[2][kWaves];
-  NormOp op{a, lds_red, 0.0, 0};
+  __shared__ ReduceLds lds;
+  NormOp op(a, lds);
   drive_tiles(a.tm, op);
+  if (arrive_last(a.fin.ticket, gridDim.x, lds)) final_sums<true, false>(a.fin, lds, gridDim.x);
 }
 
-// ================================================================== fixed-order final sums
-struct FinalizeArgs {
-  const double* norm_partial;
-  const uint32_t* tile_prefix;
-  uint32_t num_tiles;
-  uint32_t norm_blocks;   // B if norms are wanted, else 0
-  double* norm_sq_out;
-  const uint64_t* sat_partial;
-  uint32_t grid;
-  uint32_t n;             // n if counts are wanted, else 0
-  uint64_t* sat_count;
-};
-
-__global__ __launch_bounds__(kThreads) void k_finalize(const FinalizeArgs a) {
-  __shared__ double lds_red[2][kWaves];
-  __shared__ unsigned long long lds_cnt;
-  if (blockIdx.x < a.norm_blocks) {
-    const uint32_t l = blockIdx.x;
-    const uint32_t t0 = a.tile_prefix ? a.tile_prefix[l] : 0u;
-    const uint32_t t1 = a.tile_prefix ? a.tile_prefix[l + 1] : a.num_tiles;
-    double acc = 0.0;
-    for (uint32_t t = t0 + threadIdx.x; t < t1; t += kThreads) acc += a.norm_partial[t];
-    const double total = block_sum(acc, lds_red, 0);
-    if (threadIdx.x == 0) a.norm_sq_out[l] = total;
-  } else {
-    const uint32_t i = blockIdx.x - a.norm_blocks;
-    if (threadIdx.x == 0) lds_cnt = 0ull;
-    __syncthreads();
-    unsigned long long acc = 0ull;
-    for (uint32_t g = threadIdx.x; g < a.grid; g += kThreads)
-      acc += a.sat_partial[(uint64_t)i * a.grid + g];
-    if (acc != 0ull) atomicAdd(&lds_cnt, acc);
-    __syncthreads();
-    if (threadIdx.x == 0) a.sat_count[i] = lds_cnt;
-  }
+// ================================================================== a8 on its own
+__global__ __launch_bounds__(256) void k_next_alpha(const double* norm_sq, AlphaRule rule, uint32_t B,
+                                                    uint32_t n, uint64_t d) {
+  const uint32_t l = blockIdx.x * 256u + threadIdx.x;
+  if (l < B) apply_alpha_rule(rule, B, n, d, l, norm_sq[l]);
 }
 
-// ================================================================== a8
-// Section 4.1 (Proposition 2) for one block, Algorithm 2 otherwise; fp64, same
-// operation order as written in the header.
-__global__ __launch_bounds__(kThreads) void k_next_alpha(const double* norm_sq, double* r, uint32_t B,
-                                                         const uint64_t* block_offsets, uint64_t d,
-                                                         uint32_t n, double beta, double eps,
-                                                         double eta, float* alpha_out) {
-  const uint32_t l = blockIdx.x * kThreads + threadIdx.x;
-  if (l >= B) return;
-  const double keep = beta * r[l];
-  const double fresh = (1.0 - beta) * norm_sq[l];
-  const double rl = keep + fresh;
-  r[l] = rl;
-  double alpha;
-  if (B == 1) {
-    const double den = 2.0 * (double)n * rl / (eta * eta) + eps * eps;
-    alpha = sqrt((double)d) / sqrt(den);
-  } else {
-    const double dl = (double)(block_offsets[l + 1] - block_offsets[l]);
-    const double den = 2.0 * (double)n * rl + eta * eta * (dl / (double)d) * eps * eps;
-    alpha = eta * sqrt(dl) / sqrt(den);
-  }
-  alpha_out[l] = (float)alpha;
+// Zeroes the control words at the head of a workspace.
+__global__ __launch_bounds__(256) void k_zero_control(uint32_t* words, uint32_t count) {
+  for (uint32_t i = threadIdx.x; i < count; i += 256u) words[i] = 0u;
 }
 
 inline hipError_t after_launch() { return hipGetLastError(); }
@@ -674,16 +761,17 @@ inline hipError_t after_launch() { return hipGetLastError(); }
 // ------------------------------------------------------------------ launchers
 hipError_t launch_compress(const TileMap& tm, const LaunchShape& ls, uint32_t n, int32_t wire,
                            const RoundSpec& rs, const WorkerPtrs& grads, const float* alpha,
-                           const WorkerOutPtrs& q_out, uint64_t* sat_partial) {
-  CompressArgs a{tm, rs, n, alpha, sat_partial, grads, q_out};
+                           const WorkerOutPtrs& q_out, uint32_t* tickets, uint64_t* sat_partial,
+                           uint64_t* sat_count) {
+  CompressArgs a{tm, rs, alpha, tickets, sat_partial, sat_count, grads, q_out};
   const dim3 grid(ls.grid, n), block(kThreads);
   const bool random = rs.rounding == INTSGD_ROUND_STOCHASTIC;
   if (wire == INTSGD_WIRE_INT8) {
-    if (random) hipLaunchKernelGGL((k_compress<1, 8>), grid, block, 0, ls.stream, a);
-    else hipLaunchKernelGGL((k_compress<0, 8>), grid, block, 0, ls.stream, a);
+    if (random) hipLaunchKernelGGL((k_compress<1, 8>), grid, block, ls.lds_reserve, ls.stream, a);
+    else hipLaunchKernelGGL((k_compress<0, 8>), grid, block, ls.lds_reserve, ls.stream, a);
   } else {
-    if (random) hipLaunchKernelGGL((k_compress<1, 32>), grid, block, 0, ls.stream, a);
-    else hipLaunchKernelGGL((k_compress<0, 32>), grid, block, 0, ls.stream, a);
+    if (random) hipLaunchKernelGGL((k_compress<1, 32>), grid, block, ls.lds_reserve, ls.stream, a);
+    else hipLaunchKernelGGL((k_compress<0, 32>), grid, block, ls.lds_reserve, ls.stream, a);
   }
   return after_launch();
 }
@@ -700,7 +788,7 @@ hipError_t launch_int_sum(uint64_t d, const LaunchShape& ls, uint32_t n, int32_t
 hipError_t launch_decode_update(const TileMap& tm, const LaunchShape& ls, uint32_t n,
                                 const int32_t* sum, const float* alpha, double eta, float* x,
                                 float* gtilde_out) {
-  DecodeArgs a{tm, n, sum, alpha, eta, x, gtilde_out, nullptr};
+  DecodeArgs a{tm, n, sum, alpha, eta, x, gtilde_out, Finish{}};
   const dim3 grid(ls.grid), block(kThreads);
   if (gtilde_out) hipLaunchKernelGGL((k_decode<false, true>), grid, block, 0, ls.stream, a);
   else hipLaunchKernelGGL((k_decode<false, false>), grid, block, 0, ls.stream, a);
@@ -708,62 +796,53 @@ hipError_t launch_decode_update(const TileMap& tm, const LaunchShape& ls, uint32
 }
 
 hipError_t launch_update_norm(const TileMap& tm, const LaunchShape& ls, const float* x_new,
-                              const float* x_old, double* norm_partial) {
-  NormArgs a{tm, x_new, x_old, norm_partial};
+                              const float* x_old, const Finish& fin) {
+  NormArgs a{tm, x_new, x_old, fin};
   hipLaunchKernelGGL(k_update_norm, dim3(ls.grid), dim3(kThreads), 0, ls.stream, a);
   return after_launch();
 }
 
 hipError_t launch_compress_sum(const TileMap& tm, const LaunchShape& ls, uint32_t n,
                                const RoundSpec& rs, const WorkerPtrs& grads, const float* alpha,
-                               int32_t* sum_out, uint64_t* sat_partial) {
-  CompressSumArgs a{tm, rs, n, alpha, sum_out, sat_partial, grads};
+                               int32_t* sum_out, const Finish& fin) {
+  AggregateArgs a{tm, rs, n, alpha, 0.0, nullptr, sum_out, fin, grads};
   const dim3 grid(ls.grid), block(kThreads);
   if (rs.rounding == INTSGD_ROUND_STOCHASTIC)
-    hipLaunchKernelGGL((k_compress_sum<1>), grid, block, 0, ls.stream, a);
+    hipLaunchKernelGGL((k_aggregate<1, false>), grid, block, ls.lds_reserve, ls.stream, a);
   else
-    hipLaunchKernelGGL((k_compress_sum<0>), grid, block, 0, ls.stream, a);
+    hipLaunchKernelGGL((k_aggregate<0, false>), grid, block, ls.lds_reserve, ls.stream, a);
   return after_launch();
 }
 
 hipError_t launch_decode_update_norm(const TileMap& tm, const LaunchShape& ls, uint32_t n,
                                      const int32_t* sum, const float* alpha, double eta, float* x,
-                                     double* norm_partial) {
-  DecodeArgs a{tm, n, sum, alpha, eta, x, nullptr, norm_partial};
+                                     const Finish& fin) {
+  DecodeArgs a{tm, n, sum, alpha, eta, x, nullptr, fin};
   hipLaunchKernelGGL((k_decode<true, false>), dim3(ls.grid), dim3(kThreads), 0, ls.stream, a);
   return after_launch();
 }
 
 hipError_t launch_step_fused(const TileMap& tm, const LaunchShape& ls, uint32_t n,
                              const RoundSpec& rs, const WorkerPtrs& grads, const float* alpha,
-                             double eta, float* x, double* norm_partial, uint64_t* sat_partial) {
-  StepArgs a{tm, rs, n, alpha, eta, x, norm_partial, sat_partial, grads};
+                             double eta, float* x, const Finish& fin) {
+  AggregateArgs a{tm, rs, n, alpha, eta, x, nullptr, fin, grads};
   const dim3 grid(ls.grid), block(kThreads);
   if (rs.rounding == INTSGD_ROUND_STOCHASTIC)
-    hipLaunchKernelGGL((k_step_fused<1>), grid, block, 0, ls.stream, a);
+    hipLaunchKernelGGL((k_aggregate<1, true>), grid, block, ls.lds_reserve, ls.stream, a);
   else
-    hipLaunchKernelGGL((k_step_fused<0>), grid, block, 0, ls.stream, a);
+    hipLaunchKernelGGL((k_aggregate<0, true>), grid, block, ls.lds_reserve, ls.stream, a);
   return after_launch();
 }
 
-hipError_t launch_finalize(hipStream_t stream, const double* norm_partial,
-                           const uint32_t* tile_prefix, uint32_t num_tiles, uint32_t B,
-                           double* norm_sq_out, const uint64_t* sat_partial, uint32_t grid,
-                           uint32_t n, uint64_t* sat_count) {
-  FinalizeArgs a{norm_partial, tile_prefix, num_tiles, norm_sq_out ? B : 0u, norm_sq_out,
-                 sat_partial, grid, sat_count ? n : 0u, sat_count};
-  const uint32_t blocks = a.norm_blocks + a.n;
-  if (blocks == 0) return hipSuccess;
-  hipLaunchKernelGGL(k_finalize, dim3(blocks), dim3(kThreads), 0, stream, a);
+hipError_t launch_next_alpha(hipStream_t stream, const double* norm_sq, const AlphaRule& rule,
+                             uint32_t B, uint32_t n, uint64_t d) {
+  const uint32_t blocks = (B + 255u) / 256u;
+  hipLaunchKernelGGL(k_next_alpha, dim3(blocks), dim3(256), 0, stream, norm_sq, rule, B, n, d);
   return after_launch();
 }
 
-hipError_t launch_next_alpha(hipStream_t stream, const double* norm_sq, double* r, uint32_t B,
-                             const uint64_t* block_offsets, uint64_t d, uint32_t n, double beta,
-                             double eps, double eta, float* alpha_out) {
-  const uint32_t blocks = (B + kThreads - 1) / kThreads;
-  hipLaunchKernelGGL(k_next_alpha, dim3(blocks), dim3(kThreads), 0, stream, norm_sq, r, B,
-                     block_offsets, d, n, beta, eps, eta, alpha_out);
+hipError_t launch_zero_control(hipStream_t stream, uint32_t* words, uint32_t count) {
+  hipLaunchKernelGGL(k_zero_control, dim3(1), dim3(256), 0, stream, words, count);
   return after_launch();
 }
 

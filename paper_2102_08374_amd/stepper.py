@@ -37,12 +37,16 @@ class Stepper:
                             self.alpha, stream)
 
     def step_fused(self, grads, x, k, stream=None, chain_alpha=True):
-        """F3 then a8.  grads: list of n device tensors; x updated in place."""
+        """The whole step a1-a8 in one launch (chain_alpha=False: stop after a7).
+        grads: list of n device tensors; x updated in place."""
         self.desc.step = k
-        B.intsgd_step_fused(self.desc, grads, self.alpha, self.eta, x, self.norm_sq,
-                            self.sat_count, self.workspace, stream)
         if chain_alpha:
-            self.next_alpha(stream)
+            B.intsgd_step_fused_next_alpha(self.desc, grads, self.alpha, self.eta, x, self.r,
+                                           self.beta, self.eps, self.norm_sq, self.sat_count,
+                                           self.workspace, stream)
+        else:
+            B.intsgd_step_fused(self.desc, grads, self.alpha, self.eta, x, self.norm_sq,
+                                self.sat_count, self.workspace, stream)
 
     def step_two_pass(self, grads, x, k, sum_buf, stream=None, chain_alpha=True):
         """F1 (compress + aggregate) then F2 (decode + update + norm) then a8."""

@@ -161,15 +161,19 @@ def fill_gradient(w: Workload, step: int, worker: int, out: torch.Tensor):
     return out
 
 
+def row_stride(d: int) -> int:
+    """Floats between the starts of two workers' gradients in one buffer: d rounded up
+    so that every row starts on a 256-byte boundary (each worker would own a separately
+    allocated, aligned gradient buffer)."""
+    return (d + 63) // 64 * 64
+
+
 def make_gradients(w: Workload, step: int, device, out: Optional[torch.Tensor] = None):
-    """-> (buffer [n, d], list of the n row views).  Rows are 16-byte aligned when d % 4 == 0;
-    otherwise each row gets its own allocation."""
-    if w.d % 4 == 0:
-        buf = out if out is not None else torch.empty((w.n, w.d), dtype=torch.float32, device=device)
-        rows = [buf[i] for i in range(w.n)]
-    else:
-        buf = None
-        rows = [torch.empty(w.d, dtype=torch.float32, device=device) for _ in range(w.n)]
+    """-> (buffer [n, row_stride(d)], list of the n row views of d floats)."""
+    stride = row_stride(w.d)
+    buf = out if out is not None else torch.empty((w.n, stride), dtype=torch.float32, device=device)
+    assert buf.shape == (w.n, stride)
+    rows = [buf[i, :w.d] for i in range(w.n)]
     for i, row in enumerate(rows):
         fill_gradient(w, step, i, row)
     return buf, rows

@@ -130,20 +130,49 @@ def test_pointer_alignment_eta_and_workspace_validation():
 
 
 def test_tuning_knobs_are_validated():
-    tile, grid = P.intsgd_get_tuning()
-    for bad_tile in (1000, 512, 131072, 4097):
-        assert lib.intsgd_set_tuning(bad_tile, 0) == EINVAL
-    assert lib.intsgd_set_tuning(0, 16385) == EINVAL
-    assert P.intsgd_get_tuning() == (tile, grid)
-    P.intsgd_set_tuning(2048, 100)
-    assert P.intsgd_get_tuning() == (2048, 100)
-    P.intsgd_set_tuning(tile, grid)
+    before = P.intsgd_get_tuning()
+    T = binding._CTuning
+    for bad in (T(1000, 0, 0), T(512, 0, 0), T(131072, 0, 0), T(4097, 0, 0), T(0, (1 << 20) + 1, 0),
+                T(0, 0, 1), T(0, 0, 9)):
+        assert lib.intsgd_set_tuning(C.byref(bad)) == EINVAL
+    assert lib.intsgd_set_tuning(None) == EINVAL
+    assert P.intsgd_get_tuning() == before
+    P.intsgd_set_tuning(4096, 100, 4)
+    assert P.intsgd_get_tuning() == (4096, 100, 4)
+    P.intsgd_set_tuning(tile_coords=1024)                # zero fields keep their value
+    assert P.intsgd_get_tuning() == (1024, 100, 4)
+    P.intsgd_set_tuning(*before)
     # the workspace size does not depend on the tuning
     desc = P.Desc(10**7, 8)
     a = P.intsgd_workspace_bytes(desc)
-    P.intsgd_set_tuning(1024, 16384)
+    P.intsgd_set_tuning(1024, 1 << 20, 8)
     assert P.intsgd_workspace_bytes(desc) == a
-    P.intsgd_set_tuning(tile, grid)
+    P.intsgd_set_tuning(*before)
+    assert P.intsgd_get_tuning() == before
+
+
+def test_workspace_init_validation():
+    assert lib.intsgd_workspace_init(None, 1 << 20, None) == EWORKSPACE
+    assert lib.intsgd_workspace_init(FAKE, 100, None) == EWORKSPACE
+    assert lib.intsgd_workspace_init(FAKE + 16, 1 << 20, None) == EWORKSPACE
+
+
+def test_single_launch_step_validation():
+    desc = P.Desc(1000, 4)
+    need = P.intsgd_workspace_bytes(desc)
+    f = lib.intsgd_step_fused_next_alpha
+    ok_args = lambda **kw: [kw.get("desc", desc.ref()), kw.get("g", ptrs(4)), kw.get("alpha", FAKE),
+                            kw.get("eta", 0.1), kw.get("x", FAKE), kw.get("r", FAKE),
+                            kw.get("beta", 0.9), kw.get("eps", 1e-8), kw.get("ns", FAKE),
+                            kw.get("sat", FAKE), kw.get("ws", FAKE), kw.get("wb", need), None]
+    assert f(*ok_args(r=None)) == EINVAL
+    assert f(*ok_args(alpha=None)) == EINVAL
+    assert f(*ok_args(beta=1.0)) == EINVAL
+    assert f(*ok_args(eps=-1.0)) == EINVAL
+    assert f(*ok_args(eta=0.0)) == EINVAL
+    assert f(*ok_args(x=FAKE_ODD)) == EALIGN
+    assert f(*ok_args(wb=need - 1)) == EWORKSPACE
+    assert f(*ok_args(desc=None)) == EINVAL
 
 
 def test_status_strings():

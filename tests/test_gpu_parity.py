@@ -21,11 +21,14 @@ NORM_RTOL = 1e-5
 ALPHA_RTOL = 1e-5
 
 
+DEFAULT_TUNING = P.intsgd_get_tuning()
+
+
 @pytest.fixture(autouse=True)
 def _default_tuning():
-    P.intsgd_set_tuning(4096, 8192)
+    P.intsgd_set_tuning(*DEFAULT_TUNING)
     yield
-    P.intsgd_set_tuning(4096, 8192)
+    P.intsgd_set_tuning(*DEFAULT_TUNING)
 
 
 def dev(a):
@@ -65,7 +68,7 @@ def make_case(d, n, offsets, seed, alpha_scale=1.0):
 @pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "d%d-n%d" % (s[0], s[1]))
 def test_every_entry_point_matches_oracle(shape, wire, clip, rounding):
     d, n, offsets, tile = shape
-    P.intsgd_set_tuning(tile, 8192)
+    P.intsgd_set_tuning(tile_coords=tile)
     L = P.default_clip(n) if clip is None else clip
     seed, step, eta = 0x1234ABCD5678EF01, 11, 0.1
     alpha, g, x = make_case(d, n, offsets, seed=d + n + rounding)
@@ -151,8 +154,9 @@ def test_every_entry_point_matches_oracle(shape, wire, clip, rounding):
         assert np.array_equal(host(d_g[i]).view(np.uint32), g[i].view(np.uint32))
 
 
-@pytest.mark.parametrize("tile,grid", [(1024, 1), (1024, 7), (4096, 8192), (16384, 64), (65536, 3)])
-def test_results_do_not_depend_on_tuning(tile, grid):
+@pytest.mark.parametrize("tile,grid,wgs", [(1024, 1, 2), (1024, 7, 8), (4096, 8192, 3), (16384, 64, 2),
+                                           (65536, 3, 4), (2048, 1 << 20, 2)])
+def test_results_do_not_depend_on_tuning(tile, grid, wgs):
     """Tile size and grid only change the summation order of the norm."""
     d, n, offsets = 300007, 6, [0, 17, 100000, 100003, 300007]
     alpha, g, x = make_case(d, n, offsets, seed=5)
@@ -160,7 +164,7 @@ def test_results_do_not_depend_on_tuning(tile, grid):
     ws = P.new_workspace(desc, DEV)
     off_np = np.array(offsets, np.uint64)
     out = oracle.step(list(g), alpha, x, rounding=1, L=1000, eta=0.3, seed=9, step=2, offsets=off_np)
-    P.intsgd_set_tuning(tile, grid)
+    P.intsgd_set_tuning(tile, grid, wgs)
     d_x = dev(x)
     d_ns = torch.zeros(len(offsets) - 1, dtype=torch.float64, device=DEV)
     d_cnt = torch.zeros(n, dtype=torch.int64, device=DEV)
@@ -335,7 +339,7 @@ def sampled_check(w: W.Workload, steps, slices_per_step=48, slice_len=8192):
     st = Stepper(desc, eta=w.eta, beta=w.beta, eps=w.eps, device=DEV)
     st.start(w.first_normsq)
     x = W.make_params(w, DEV)
-    buf = torch.empty((w.n, w.d), dtype=torch.float32, device=DEV)
+    buf = torch.empty((w.n, W.row_stride(w.d)), dtype=torch.float32, device=DEV)
     rng = np.random.default_rng(w.config_id)
     tile = P.intsgd_get_tuning()[0]
     for k in range(1, steps + 1):
