@@ -2,11 +2,11 @@
 """Benchmark of the IntSGD compression hot path on one MI355X.
 
 A step is one pass of the whole path over one batch of synthetic gradients:
-scale + round + clip + aggregate + decode + update + norm + next alpha, which the
-library runs as ONE kernel launch (the sweep's last workgroup does the fixed-order
-final sums and the alpha rule).  Gradients, parameters and all state are resident
-in HBM before the timed region; nothing is copied to the host inside it.  Prints
-ONE JSON line.
+scale + round + clip + aggregate + decode + update + norm (one fused sweep kernel)
+and the fixed-order final sums + next alpha (one small kernel behind it), through
+a single library call.  Gradients, parameters and all state are resident in HBM
+before the timed region; nothing is copied to the host inside it.  Prints ONE JSON
+line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--mode fused]
 """
@@ -62,6 +62,40 @@ def cpu_baseline(w, rows, alpha_host, x_host, max_wc=420_000_000):
                 ln, w.d, w.n, dt)}
 
 
+class HipEvents:
+    """Raw HIP events from the runtime this process already has loaded (the library's
+    profiling taps take hipEvent_t handles)."""
+
+    def __init__(self):
+        import ctypes as C
+        path = None
+        with open("/proc/self/maps") as fh:
+            for line in fh:
+                if "libamdhip64" in line:
+                    path = line.split()[-1]
+                    break
+        assert path, "HIP runtime not loaded"
+        self.C = C
+        self.hip = C.CDLL(path)
+        self.hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [C.c_void_p]
+
+    def create(self):
+        ev = self.C.c_void_p()
+        assert self.hip.hipEventCreate(self.C.byref(ev)) == 0
+        return ev.value
+
+    def elapsed_ms(self, a, b):
+        ms = self.C.c_float()
+        rc = self.hip.hipEventElapsedTime(self.C.byref(ms), a, b)
+        assert rc == 0, "hipEventElapsedTime -> %d" % rc
+        return float(ms.value)
+
+    def destroy(self, ev):
+        self.hip.hipEventDestroy(ev)
+
+
 def load_traffic(name, mode):
     """HBM bytes per launch of the dominant kernel from committed rocprofv3 counter
     summaries (profiles/traffic.json), or None."""
@@ -111,9 +145,9 @@ def main():
     def one_step(k):
         rows = sets[(k - 1) % pool][1]
         if args.mode == "fused":
-            st.step_fused(rows, x, k)                    # a1-a8, one launch
+            st.step_fused(rows, x, k)                    # a1-a8, one call
         else:
-            st.step_two_pass(rows, x, k, sum_buf)        # F1, F2, a8: three launches
+            st.step_two_pass(rows, x, k, sum_buf)        # F1, F2, a8
 
     st.start(w.first_normsq)
     alpha0 = st.alpha.cpu().numpy().copy()
@@ -123,23 +157,24 @@ def main():
         one_step(k)
     torch.cuda.synchronize()
 
-    # timed region: exactly K steps; per-step events bracket the step's kernel on the
-    # stream it is launched on
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-          for _ in range(args.steps)]
+    # timed region: exactly K steps.  In every step the library records a pair of HIP
+    # events right around the sweep kernel, on the stream it launches it on.
+    hip = HipEvents()
+    ev = [(hip.create(), hip.create()) for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        k = args.warmup + 1 + i
-        ev[i][0].record()
-        one_step(k)
-        ev[i][1].record()
+        P.intsgd_tap_next_launch(ev[i][0], ev[i][1])
+        one_step(args.warmup + 1 + i)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
-    kernel_ms = sorted(a.elapsed_time(b) for a, b in ev)
+    kernel_ms = sorted(hip.elapsed_ms(a, b) for a, b in ev)
+    for a, b in ev:
+        hip.destroy(a)
+        hip.destroy(b)
     avg_kernel_ms = sum(kernel_ms) / len(kernel_ms)
-    per_coord = (4 * w.n + 8) if args.mode == "fused" else (4 * w.n + 16)
+    per_coord = (4 * w.n + 8) if args.mode == "fused" else (4 * w.n + 4)
     algo_bytes = per_coord * w.d
     achieved = algo_bytes / (avg_kernel_ms * 1e-3) / 1e9
     sat = int(st.sat_count.cpu().numpy().view("uint64").sum())
@@ -170,8 +205,8 @@ def main():
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
             "traffic": load_traffic(w.name, args.mode),
-            "kernel": "k_aggregate<ROUND, FUSED=true> (the whole step)" if args.mode == "fused"
-                      else "k_aggregate<ROUND, false> + k_decode<true, false> + k_next_alpha",
+            "kernel": "k_aggregate<ROUND, FUSED=true>: a1-a7 in one sweep" if args.mode == "fused"
+                      else "k_aggregate<ROUND, FUSED=false>: a1-a4 (first of the two sweeps)",
             "algorithmic_bytes_per_launch": algo_bytes,
             "kernel_ms_avg": avg_kernel_ms, "kernel_ms_min": kernel_ms[0],
             "kernel_ms_median": kernel_ms[len(kernel_ms) // 2],

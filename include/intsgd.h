@@ -30,10 +30,9 @@
  *     that is built the first time a descriptor with num_blocks > 1 is used (or
  *     by intsgd_prepare) and freed by intsgd_release().  Descriptors with
  *     num_blocks == 1 need none.
- *   - A workspace must be passed through intsgd_workspace_init once after it is
- *     allocated (and again if anything else wrote to it); every call then leaves
- *     it ready for the next one.  Calls on different streams that share a
- *     workspace race; give each concurrent call its own workspace.
+ *   - A workspace needs no initialisation and holds nothing between calls.  Calls
+ *     on different streams that share a workspace race; give each concurrent call
+ *     its own workspace.
  *   - For full bandwidth give every vector a 128-byte aligned start (only 16 is
  *     required).
  */
@@ -101,10 +100,11 @@ typedef struct intsgd_desc {
  * workspace needs for this descriptor; 0 if the descriptor is invalid. */
 size_t intsgd_workspace_bytes(const intsgd_desc* desc);
 
-/* Enqueues the one-time initialisation of a workspace (zeroes the control words the
- * kernels use to elect the workgroup that finishes their reductions; each call that
- * uses the workspace resets them itself).  workspace_bytes >= 1024. */
-intsgd_status intsgd_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream);
+/* Profiling aid.  The next call of THIS thread that launches a streaming kernel
+ * records `start_event` right before and `stop_event` right after that kernel (not
+ * around the small final-sum kernel that follows it) on the call's stream, then
+ * forgets both.  Pass hipEvent_t handles as void*; NULL clears a pending tap. */
+intsgd_status intsgd_tap_next_launch(void* start_event, void* stop_event);
 
 /* Validates the descriptor and builds the library's tile table for its partition
  * now (the only call that may allocate device memory), so that later calls on
@@ -200,9 +200,9 @@ intsgd_status intsgd_step_fused(const intsgd_desc* desc, const float* const* gra
                                 void* hip_stream);
 
 /*
- * The whole step in ONE launch: F3 followed by a8 (Section 4.1 / Algorithm 2) applied
- * by the kernel's last workgroup.  alpha: DEVICE float[B], read as alpha_k during the
- * sweep and overwritten with alpha_{k+1} at the end; r: DEVICE double[B] in/out;
+ * The whole step in one call: F3, whose small final-sum kernel also applies a8
+ * (Section 4.1 / Algorithm 2).  alpha: DEVICE float[B], read as alpha_k during the
+ * sweep and overwritten with alpha_{k+1} afterwards; r: DEVICE double[B] in/out;
  * norm_sq_out, sat_count as in intsgd_step_fused.  eta is eta_k for both the update
  * and the rule.  Same results as intsgd_step_fused followed by intsgd_next_alpha.
  */

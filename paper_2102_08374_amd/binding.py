@@ -16,7 +16,7 @@ __all__ = [
     "intsgd_release", "intsgd_compress", "intsgd_int_sum", "intsgd_decode_update",
     "intsgd_update_norm", "intsgd_next_alpha", "intsgd_next_alpha_host", "intsgd_compress_sum",
     "intsgd_decode_update_norm", "intsgd_step_fused", "intsgd_step_fused_next_alpha",
-    "intsgd_workspace_init", "intsgd_set_tuning", "intsgd_get_tuning", "intsgd_status_string",
+    "intsgd_tap_next_launch", "intsgd_set_tuning", "intsgd_get_tuning", "intsgd_status_string",
     "new_workspace", "EXPORTED_SYMBOLS",
 ]
 
@@ -27,7 +27,7 @@ WIRE_INT32 = 32
 MAX_WORKERS = 128
 
 EXPORTED_SYMBOLS = [
-    "intsgd_workspace_bytes", "intsgd_workspace_init", "intsgd_prepare", "intsgd_release",
+    "intsgd_workspace_bytes", "intsgd_tap_next_launch", "intsgd_prepare", "intsgd_release",
     "intsgd_compress", "intsgd_step_fused_next_alpha",
     "intsgd_int_sum", "intsgd_decode_update", "intsgd_update_norm", "intsgd_next_alpha",
     "intsgd_next_alpha_host", "intsgd_compress_sum", "intsgd_decode_update_norm",
@@ -84,7 +84,7 @@ _lib.intsgd_decode_update_norm.argtypes = [_DP, _P, _P, C.c_double, _P, _P, _P, 
 _lib.intsgd_step_fused.argtypes = [_DP, _PP, _P, C.c_double, _P, _P, _P, _P, C.c_size_t, _P]
 _lib.intsgd_step_fused_next_alpha.argtypes = [_DP, _PP, _P, C.c_double, _P, _P, C.c_double,
                                               C.c_double, _P, _P, _P, C.c_size_t, _P]
-_lib.intsgd_workspace_init.argtypes = [_P, C.c_size_t, _P]
+_lib.intsgd_tap_next_launch.argtypes = [_P, _P]
 _lib.intsgd_set_tuning.argtypes = [C.POINTER(_CTuning)]
 _lib.intsgd_get_tuning.argtypes = [C.POINTER(_CTuning)]
 _lib.intsgd_get_tuning.restype = None
@@ -95,7 +95,7 @@ _lib.intsgd_last_hip_error.restype = C.c_char_p
 for _name in ("intsgd_prepare", "intsgd_compress", "intsgd_int_sum", "intsgd_decode_update",
               "intsgd_update_norm", "intsgd_next_alpha", "intsgd_next_alpha_host",
               "intsgd_compress_sum", "intsgd_decode_update_norm", "intsgd_step_fused",
-              "intsgd_step_fused_next_alpha", "intsgd_workspace_init", "intsgd_set_tuning"):
+              "intsgd_step_fused_next_alpha", "intsgd_tap_next_launch", "intsgd_set_tuning"):
     getattr(_lib, _name).restype = C.c_int
 
 
@@ -208,19 +208,17 @@ def intsgd_workspace_bytes(desc: Desc) -> int:
     return int(_lib.intsgd_workspace_bytes(desc.ref()))
 
 
-def intsgd_workspace_init(workspace, stream=None):
-    w, wb = _ws(workspace)
-    _check(_lib.intsgd_workspace_init(w, wb, _stream(stream)), "intsgd_workspace_init")
+def intsgd_tap_next_launch(start_event, stop_event):
+    """Raw hipEvent_t handles (ints) or None; see include/intsgd.h."""
+    _check(_lib.intsgd_tap_next_launch(C.c_void_p(start_event or 0), C.c_void_p(stop_event or 0)),
+           "intsgd_tap_next_launch")
 
 
 def new_workspace(desc: Desc, device="cuda") -> torch.Tensor:
-    """Allocates and initialises a workspace for `desc`."""
     nbytes = intsgd_workspace_bytes(desc)
     if nbytes == 0:
         raise IntSGDError(-1, "intsgd_workspace_bytes")
-    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
-    intsgd_workspace_init(ws)
-    return ws
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
 
 
 def intsgd_prepare(desc: Desc):

@@ -23,7 +23,6 @@ constexpr uint32_t kMaxTile = 65536;
 constexpr uint32_t kMaxGrid = 1u << 20;
 constexpr uint64_t kMaxD = 1ull << 40;
 constexpr size_t kAlign = 256;
-constexpr size_t kControlBytes = 1024;          // tickets: one word per worker, padded
 constexpr uint32_t kLdsPerCu = 160u * 1024u;    // gfx950
 
 // Measured on MI355X (d = 25.6 M, n = 16): 8 KB per stream and workgroup, two resident
@@ -31,6 +30,14 @@ constexpr uint32_t kLdsPerCu = 160u * 1024u;    // gfx950
 intsgd_tuning g_tuning = {2048, kMaxGrid, 2};
 
 thread_local std::string t_hip_error;
+thread_local hipEvent_t t_tap_start = nullptr, t_tap_stop = nullptr;
+
+// Moves this thread's pending profiling taps (if any) into a launch.
+void take_taps(LaunchShape* ls) {
+  ls->tap_start = t_tap_start;
+  ls->tap_stop = t_tap_stop;
+  t_tap_start = t_tap_stop = nullptr;
+}
 
 intsgd_status hip_fail(hipError_t e) {
   t_hip_error = std::string(hipGetErrorName(e)) + ": " + hipGetErrorString(e);
@@ -86,7 +93,7 @@ intsgd_status validate_vec(const void* p) {
 
 uint64_t tiles_of(uint64_t len, uint32_t tile) { return (len + tile - 1) / tile; }
 
-// Workspace carving: [control words][norm partial per tile][clip flag per workgroup]
+// Workspace carving: [norm partial per tile][clip flag per workgroup]
 // [clip counts per workgroup and worker]; sized for the smallest tile so that it is
 // valid under any tuning (the grid never exceeds the number of tiles).
 struct WorkspaceLayout {
@@ -96,7 +103,7 @@ struct WorkspaceLayout {
 WorkspaceLayout workspace_layout(const intsgd_desc* desc) {
   WorkspaceLayout w;
   const uint64_t max_tiles = tiles_of(desc->d, kMinTile) + desc->num_blocks;
-  w.norm_off = kControlBytes;
+  w.norm_off = 0;
   w.any_off = w.norm_off + round_up((size_t)max_tiles * sizeof(double), kAlign);
   w.rows_off = w.any_off + round_up((size_t)max_tiles * sizeof(uint32_t), kAlign);
   w.total = w.rows_off + round_up((size_t)max_tiles * desc->n * sizeof(uint64_t), kAlign);
@@ -110,7 +117,6 @@ intsgd_status validate_workspace(const intsgd_desc* desc, void* ws, size_t bytes
   return INTSGD_OK;
 }
 
-uint32_t* ws_tickets(void* ws) { return static_cast<uint32_t*>(ws); }
 template <class T>
 T* ws_at(void* ws, size_t off) {
   return reinterpret_cast<T*>(static_cast<char*>(ws) + off);
@@ -240,6 +246,7 @@ intsgd_status make_tiling(const intsgd_desc* desc, void* stream, Tiling* t) {
   t->ls.grid = t->tm.num_tiles < g_tuning.max_workgroups ? t->tm.num_tiles : g_tuning.max_workgroups;
   t->ls.lds_reserve = lds_reserve_for(g_tuning.workgroups_per_cu);
   t->ls.stream = static_cast<hipStream_t>(stream);
+  take_taps(&t->ls);
   return INTSGD_OK;
 }
 
@@ -254,12 +261,12 @@ Finish make_finish(const intsgd_desc* desc, const Tiling& t, void* ws, double* n
                    uint64_t* sat_count) {
   const WorkspaceLayout w = workspace_layout(desc);
   Finish f{};
-  f.ticket = ws_tickets(ws);
   f.norm_partial = ws_at<double>(ws, w.norm_off);
   f.tile_prefix = t.tile_prefix;
   f.num_tiles = t.tm.num_tiles;
   f.B = desc->num_blocks;
   f.norm_sq_out = norm_sq_out;
+  f.workgroups = t.ls.grid;
   f.sat_any = ws_at<uint32_t>(ws, w.any_off);
   f.sat_rows = ws_at<uint64_t>(ws, w.rows_off);
   f.n = desc->n;
@@ -315,11 +322,10 @@ size_t intsgd_workspace_bytes(const intsgd_desc* desc) {
   return workspace_layout(desc).total;
 }
 
-intsgd_status intsgd_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream) {
-  if (workspace == nullptr || workspace_bytes < kControlBytes) return INTSGD_EWORKSPACE;
-  if ((reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0) return INTSGD_EWORKSPACE;
-  return done(launch_zero_control(static_cast<hipStream_t>(hip_stream), ws_tickets(workspace),
-                                  (uint32_t)(kControlBytes / sizeof(uint32_t))));
+intsgd_status intsgd_tap_next_launch(void* start_event, void* stop_event) {
+  t_tap_start = static_cast<hipEvent_t>(start_event);
+  t_tap_stop = static_cast<hipEvent_t>(stop_event);
+  return INTSGD_OK;
 }
 
 intsgd_status intsgd_prepare(const intsgd_desc* desc) {
@@ -352,8 +358,7 @@ intsgd_status intsgd_compress(const intsgd_desc* desc, const float* const* grads
   for (uint32_t i = 0; i < desc->n; ++i) q.p[i] = q_out[i];
   const WorkspaceLayout w = workspace_layout(desc);
   return done(launch_compress(t.tm, t.ls, desc->n, desc->wire, round_spec(desc), g, alpha, q,
-                              ws_tickets(workspace), ws_at<uint64_t>(workspace, w.rows_off),
-                              sat_count));
+                              ws_at<uint64_t>(workspace, w.rows_off), sat_count));
 }
 
 intsgd_status intsgd_int_sum(const intsgd_desc* desc, const void* const* q, int32_t* sum_out,
@@ -366,7 +371,8 @@ intsgd_status intsgd_int_sum(const intsgd_desc* desc, const void* const* q, int3
   // about four quads per thread and pass of the grid-stride loop
   const uint64_t want = tiles_of((desc->d >> 2) + 1, INTSGD_THREADS_PER_WORKGROUP * 4);
   LaunchShape ls{(uint32_t)(want < g_tuning.max_workgroups ? want : g_tuning.max_workgroups), 0,
-                 static_cast<hipStream_t>(hip_stream)};
+                 static_cast<hipStream_t>(hip_stream), nullptr, nullptr};
+  take_taps(&ls);
   return done(launch_int_sum(desc->d, ls, desc->n, desc->wire, qp, sum_out));
 }
 

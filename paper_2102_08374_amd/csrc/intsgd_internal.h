@@ -49,6 +49,7 @@ struct LaunchShape {
   uint32_t grid;         // workgroups along x
   uint32_t lds_reserve;  // extra dynamic LDS per workgroup (caps workgroups per CU), heavy kernels
   hipStream_t stream;
+  hipEvent_t tap_start, tap_stop;  // optional profiling taps around the streaming kernel
 };
 
 // The alpha rule of step a8 on device arrays; r == nullptr means "do not apply".
@@ -59,14 +60,14 @@ struct AlphaRule {
   double beta, eps, eta;
 };
 
-// What the last workgroup of a kernel needs to finish the reductions.
+// What the final-sum kernel behind a sweep needs.
 struct Finish {
-  uint32_t* ticket;               // control word: zero at entry, zero again at exit
   double* norm_partial;           // one slot per tile
   const uint32_t* tile_prefix;    // device, B+1: tile range of each block; unused when B == 1
   uint32_t num_tiles;
   uint32_t B;
   double* norm_sq_out;            // B
+  uint32_t workgroups;            // grid of the sweep
   uint32_t* sat_any;              // one flag per workgroup
   uint64_t* sat_rows;             // [workgroup][n], written only where the flag is set
   uint32_t n;                     // workers (clip counts)
@@ -79,7 +80,7 @@ struct Finish {
 // Every launcher only enqueues; the return value is hipGetLastError() after the launch.
 hipError_t launch_compress(const TileMap& tm, const LaunchShape& ls, uint32_t n, int32_t wire,
                            const RoundSpec& rs, const WorkerPtrs& grads, const float* alpha,
-                           const WorkerOutPtrs& q_out, uint32_t* tickets, uint64_t* sat_partial,
+                           const WorkerOutPtrs& q_out, uint64_t* sat_partial,
                            uint64_t* sat_count);
 hipError_t launch_int_sum(uint64_t d, const LaunchShape& ls, uint32_t n, int32_t wire,
                           const WorkerPtrs& q, int32_t* sum_out);
@@ -99,7 +100,6 @@ hipError_t launch_step_fused(const TileMap& tm, const LaunchShape& ls, uint32_t 
                              double eta, float* x, const Finish& fin);
 hipError_t launch_next_alpha(hipStream_t stream, const double* norm_sq, const AlphaRule& rule,
                              uint32_t B, uint32_t n, uint64_t d);
-hipError_t launch_zero_control(hipStream_t stream, uint32_t* words, uint32_t count);
 
 }  // namespace intsgd
 

@@ -37,7 +37,7 @@ class Stepper:
                             self.alpha, stream)
 
     def step_fused(self, grads, x, k, stream=None, chain_alpha=True):
-        """The whole step a1-a8 in one launch (chain_alpha=False: stop after a7).
+        """The whole step a1-a8 in one call (chain_alpha=False: stop after a7).
         grads: list of n device tensors; x updated in place."""
         self.desc.step = k
         if chain_alpha:

@@ -151,13 +151,7 @@ def test_tuning_knobs_are_validated():
     assert P.intsgd_get_tuning() == before
 
 
-def test_workspace_init_validation():
-    assert lib.intsgd_workspace_init(None, 1 << 20, None) == EWORKSPACE
-    assert lib.intsgd_workspace_init(FAKE, 100, None) == EWORKSPACE
-    assert lib.intsgd_workspace_init(FAKE + 16, 1 << 20, None) == EWORKSPACE
-
-
-def test_single_launch_step_validation():
+def test_whole_step_call_validation():
     desc = P.Desc(1000, 4)
     need = P.intsgd_workspace_bytes(desc)
     f = lib.intsgd_step_fused_next_alpha
