@@ -93,18 +93,21 @@ intsgd_status validate_vec(const void* p) {
 
 uint64_t tiles_of(uint64_t len, uint32_t tile) { return (len + tile - 1) / tile; }
 
-// Workspace carving: [norm partial per tile][clip flag per workgroup]
-// [clip counts per workgroup and worker]; sized for the smallest tile so that it is
-// valid under any tuning (the grid never exceeds the number of tiles).
+// Workspace carving: [norm partial per tile][first-level norm sums][clip hint]
+// [clip flag per workgroup][clip counts per workgroup and worker]; sized for the
+// smallest tile so that it is valid under any tuning (the grid never exceeds the
+// number of tiles).
 struct WorkspaceLayout {
-  size_t norm_off, any_off, rows_off, total;
+  size_t norm_off, mid_off, hint_off, any_off, rows_off, total;
 };
 
 WorkspaceLayout workspace_layout(const intsgd_desc* desc) {
   WorkspaceLayout w;
   const uint64_t max_tiles = tiles_of(desc->d, kMinTile) + desc->num_blocks;
   w.norm_off = 0;
-  w.any_off = w.norm_off + round_up((size_t)max_tiles * sizeof(double), kAlign);
+  w.mid_off = w.norm_off + round_up((size_t)max_tiles * sizeof(double), kAlign);
+  w.hint_off = w.mid_off + round_up((size_t)(max_tiles / 4096 + 2) * sizeof(double), kAlign);
+  w.any_off = w.hint_off + kAlign;
   w.rows_off = w.any_off + round_up((size_t)max_tiles * sizeof(uint32_t), kAlign);
   w.total = w.rows_off + round_up((size_t)max_tiles * desc->n * sizeof(uint64_t), kAlign);
   return w;
@@ -262,6 +265,8 @@ Finish make_finish(const intsgd_desc* desc, const Tiling& t, void* ws, double* n
   const WorkspaceLayout w = workspace_layout(desc);
   Finish f{};
   f.norm_partial = ws_at<double>(ws, w.norm_off);
+  f.norm_mid = ws_at<double>(ws, w.mid_off);
+  f.sat_hint = ws_at<uint32_t>(ws, w.hint_off);
   f.tile_prefix = t.tile_prefix;
   f.num_tiles = t.tm.num_tiles;
   f.B = desc->num_blocks;

@@ -63,11 +63,13 @@ struct AlphaRule {
 // What the final-sum kernel behind a sweep needs.
 struct Finish {
   double* norm_partial;           // one slot per tile
+  double* norm_mid;               // first-level sums when the tile list is very long
   const uint32_t* tile_prefix;    // device, B+1: tile range of each block; unused when B == 1
   uint32_t num_tiles;
   uint32_t B;
   double* norm_sq_out;            // B
   uint32_t workgroups;            // grid of the sweep
+  uint32_t* sat_hint;             // non-zero: some workgroup clipped (or never used yet)
   uint32_t* sat_any;              // one flag per workgroup
   uint64_t* sat_rows;             // [workgroup][n], written only where the flag is set
   uint32_t n;                     // workers (clip counts)

@@ -360,64 +360,89 @@ __device__ __forceinline__ void apply_alpha_rule(const AlphaRule& rule, uint32_t
   rule.alpha_out[l] = (float)alpha;
 }
 
-// ------------------------------------------------------------------ end-of-kernel reductions
-// Clip counts of this workgroup -> workspace row (only when some are non-zero).
+// ------------------------------------------------------------------ reductions behind a sweep
+// Clip counts of this workgroup -> its flag and, only when some are non-zero, its row
+// plus the launch-wide hint that tells the final-sum kernel to look at the rows at all.
 __device__ __forceinline__ void publish_sat(const Finish& f, const ReduceLds& lds, uint32_t wg) {
   bool any = false;
   for (uint32_t i = 0; i < f.n; ++i) any |= lds.sat[i] != 0ull;
   f.sat_any[wg] = any ? 1u : 0u;
-  if (any)
+  if (any) {
     for (uint32_t i = 0; i < f.n; ++i) f.sat_rows[(uint64_t)wg * f.n + i] = lds.sat[i];
+    *f.sat_hint = 1u;       // every writer stores the same value
+  }
 }
 
-// Fixed-order sums of the norm partials (per block), the optional alpha rule, and the
-// clip counts; run by the single workgroup of k_finish.
+// Sum of partial[t0, t1) by the whole workgroup in a fixed order (valid in thread 0).
+// Eight independent loads in flight per lane: these kernels are pure latency.
+__device__ __forceinline__ double ordered_sum(const double* partial, uint32_t t0, uint32_t t1,
+                                              ReduceLds& lds) {
+  double acc = 0.0;
+  uint32_t t = t0 + threadIdx.x;
+  for (; t + 7u * kThreads < t1; t += 8u * kThreads) {
+    double v[8];
+#pragma unroll
+    for (uint32_t u = 0; u < 8; ++u) v[u] = partial[t + u * kThreads];
+#pragma unroll
+    for (uint32_t u = 0; u < 8; ++u) acc += v[u];
+  }
+  for (; t < t1; t += kThreads) acc += partial[t];
+  return block_sum(acc, lds, 0);
+}
+
+// First level for very long partial lists (one block only): workgroup c sums chunk c.
+__global__ __launch_bounds__(kThreads) void k_finish_chunks(const double* partial, uint32_t count,
+                                                            uint32_t chunk, double* mid) {
+  __shared__ ReduceLds lds;
+  const uint32_t t0 = blockIdx.x * chunk;
+  const uint32_t t1 = (count - t0 < chunk) ? count : t0 + chunk;
+  const double total = ordered_sum(partial, t0, t1, lds);
+  if (threadIdx.x == 0) mid[blockIdx.x] = total;
+}
+
+// Workgroup l sums the norm partials of block l in a fixed order and applies the
+// optional alpha rule to it; workgroup 0 also totals the clip counts.
 template <bool WITH_NORM, bool WITH_SAT>
-__device__ __forceinline__ void final_sums(const Finish& f, ReduceLds& lds) {
+__global__ __launch_bounds__(kThreads) void k_finish(const Finish f) {
+  __shared__ ReduceLds lds;
   const uint32_t tid = threadIdx.x;
+  const uint32_t l = blockIdx.x;
   if (WITH_NORM) {
-    if (f.B == 1) {
-      double acc = 0.0;
-      for (uint32_t t = tid; t < f.num_tiles; t += kThreads) acc += f.norm_partial[t];
-      const double total = block_sum(acc, lds, 0);
-      if (tid == 0) {
-        f.norm_sq_out[0] = total;
-        if (f.rule.r != nullptr) apply_alpha_rule(f.rule, 1, f.n_workers, f.d, 0, total);
-      }
-    } else {
-      const uint32_t lane = tid & 63u;
-      for (uint32_t l = tid >> 6; l < f.B; l += kWaves) {     // one wavefront per block
-        const uint32_t t0 = f.tile_prefix[l], t1 = f.tile_prefix[l + 1];
-        double acc = 0.0;
-        for (uint32_t t = t0 + lane; t < t1; t += 64u) acc += f.norm_partial[t];
-        const double total = wave_sum(acc);
-        if (lane == 0) {
-          f.norm_sq_out[l] = total;
-          if (f.rule.r != nullptr) apply_alpha_rule(f.rule, f.B, f.n_workers, f.d, l, total);
-        }
-      }
+    const uint32_t t0 = (f.B == 1) ? 0u : f.tile_prefix[l];
+    const uint32_t t1 = (f.B == 1) ? f.num_tiles : f.tile_prefix[l + 1];
+    const double total = ordered_sum(f.norm_partial, t0, t1, lds);
+    if (tid == 0) {
+      f.norm_sq_out[l] = total;
+      if (f.rule.r != nullptr) apply_alpha_rule(f.rule, f.B, f.n_workers, f.d, l, total);
     }
   }
-  if (WITH_SAT) {
+  if (WITH_SAT && l == 0) {
     __syncthreads();
     if (tid < INTSGD_MAX_WORKERS) lds.sat[tid] = 0ull;
     __syncthreads();
-    for (uint32_t g = tid; g < f.workgroups; g += kThreads) {
-      if (f.sat_any[g] != 0u)
+    if (*f.sat_hint != 0u) {              // something clipped (or first use): read the rows
+      auto add_row = [&](uint32_t g) {
         for (uint32_t i = 0; i < f.n; ++i) {
           const unsigned long long c = f.sat_rows[(uint64_t)g * f.n + i];
           if (c != 0ull) atomicAdd(&lds.sat[i], c);
         }
+      };
+      uint32_t g = tid;
+      for (; g + 7u * kThreads < f.workgroups; g += 8u * kThreads) {
+        uint32_t flag[8];
+#pragma unroll
+        for (uint32_t u = 0; u < 8; ++u) flag[u] = f.sat_any[g + u * kThreads];
+#pragma unroll
+        for (uint32_t u = 0; u < 8; ++u)
+          if (flag[u] != 0u) add_row(g + u * kThreads);
+      }
+      for (; g < f.workgroups; g += kThreads)
+        if (f.sat_any[g] != 0u) add_row(g);
     }
     __syncthreads();
     if (tid < f.n) f.sat_count[tid] = lds.sat[tid];
+    if (tid == 0) *f.sat_hint = 0u;
   }
-}
-
-template <bool WITH_NORM, bool WITH_SAT>
-__global__ __launch_bounds__(kThreads) void k_finish(const Finish f) {
-  __shared__ ReduceLds lds;
-  final_sums<WITH_NORM, WITH_SAT>(f, lds);
 }
 
 // Clip counts of the per-worker compress kernel: workgroup i sums row i.
@@ -745,8 +770,21 @@ struct Tapped {
   }
 };
 
-hipError_t finish(hipStream_t stream, const Finish& fin, bool with_norm, bool with_sat) {
-  const dim3 grid(1), block(kThreads);
+constexpr uint32_t kChunk = 8192;            // partials per first-level workgroup
+constexpr uint32_t kTwoLevelFrom = 2 * kChunk;
+
+hipError_t finish(hipStream_t stream, const Finish& fin_in, bool with_norm, bool with_sat) {
+  Finish fin = fin_in;
+  if (with_norm && fin.B == 1 && fin.num_tiles > kTwoLevelFrom) {
+    const uint32_t chunks = (fin.num_tiles + kChunk - 1) / kChunk;
+    hipLaunchKernelGGL(k_finish_chunks, dim3(chunks), dim3(kThreads), 0, stream, fin.norm_partial,
+                       fin.num_tiles, kChunk, fin.norm_mid);
+    const hipError_t e = after_launch();
+    if (e != hipSuccess) return e;
+    fin.norm_partial = fin.norm_mid;
+    fin.num_tiles = chunks;
+  }
+  const dim3 grid(with_norm ? fin.B : 1u), block(kThreads);
   if (with_norm && with_sat) hipLaunchKernelGGL((k_finish<true, true>), grid, block, 0, stream, fin);
   else if (with_norm) hipLaunchKernelGGL((k_finish<true, false>), grid, block, 0, stream, fin);
   else hipLaunchKernelGGL((k_finish<false, true>), grid, block, 0, stream, fin);
