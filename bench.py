@@ -200,7 +200,8 @@ def main():
             "workload": w.name, "d": w.d, "n_workers": w.n, "blocks": w.num_blocks,
             "rounding": "stochastic" if w.rounding else "nearest-even", "wire": "int%d" % w.wire,
             "clip": w.clip, "grad_dist": w.grad_kind, "mode": args.mode, "gradient_sets": pool,
-            "tile_coords": tile, "max_workgroups": grid, "workgroups_per_cu": wgs_per_cu,
+            "tuning_overrides": {"tile_coords": tile, "max_workgroups": grid,
+                                 "workgroups_per_cu": wgs_per_cu},
             "alpha_last": alpha_last,
             "clipped_last_step": sat,
         },

@@ -212,9 +212,10 @@ intsgd_status intsgd_step_fused_next_alpha(const intsgd_desc* desc, const float*
                                            uint64_t* sat_count, void* workspace,
                                            size_t workspace_bytes, void* hip_stream);
 
-/* Tuning knobs (process-wide; not part of the numerical contract: results do not
+/* Tuning overrides (process-wide; not part of the numerical contract: results do not
  * depend on them except for the summation order of the norm).  A field that is 0
- * keeps the current value.
+ * means "automatic": the library picks per call (by rounding mode) what measured best
+ * on MI355X.  intsgd_set_tuning replaces all three fields.
  *   tile_coords        coordinates per work tile, a multiple of 1024 in [1024, 65536]
  *   max_workgroups     cap of the launch grid, in [1, 1048576]; tiles beyond it are
  *                      taken by striding

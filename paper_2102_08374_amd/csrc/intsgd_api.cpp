@@ -25,9 +25,21 @@ constexpr uint64_t kMaxD = 1ull << 40;
 constexpr size_t kAlign = 256;
 constexpr uint32_t kLdsPerCu = 160u * 1024u;    // gfx950
 
-// Measured on MI355X (d = 25.6 M, n = 16): 8 KB per stream and workgroup, two resident
-// workgroups of 512 threads per CU, one workgroup per tile.
-intsgd_tuning g_tuning = {2048, kMaxGrid, 2};
+// Process-wide overrides; a zero field means "automatic".
+intsgd_tuning g_tuning = {0, 0, 0};
+
+// Automatic choices, measured on MI355X.  Nearest-even rounding is bound by HBM and
+// likes few, large bursts in flight: 8 KB per stream and workgroup, two resident
+// workgroups of 512 threads per CU.  Randomized rounding is co-bound by the integer
+// ALU (Philox) and needs more wavefronts to keep it busy: 16 KB tiles, four per CU.
+intsgd_tuning effective_tuning(const intsgd_desc* desc) {
+  const bool random = desc->rounding == INTSGD_ROUND_STOCHASTIC;
+  intsgd_tuning t = g_tuning;
+  if (t.tile_coords == 0) t.tile_coords = random ? 4096 : 2048;
+  if (t.max_workgroups == 0) t.max_workgroups = kMaxGrid;
+  if (t.workgroups_per_cu == 0) t.workgroups_per_cu = random ? 4 : 2;
+  return t;
+}
 
 thread_local std::string t_hip_error;
 thread_local hipEvent_t t_tap_start = nullptr, t_tap_stop = nullptr;
@@ -229,7 +241,8 @@ uint32_t lds_reserve_for(uint32_t k) {
 }
 
 intsgd_status make_tiling(const intsgd_desc* desc, void* stream, Tiling* t) {
-  const uint32_t tile = g_tuning.tile_coords;
+  const intsgd_tuning tune = effective_tuning(desc);
+  const uint32_t tile = tune.tile_coords;
   t->tm.d = desc->d;
   t->tm.tile = tile;
   if (desc->num_blocks == 1) {
@@ -246,8 +259,8 @@ intsgd_status make_tiling(const intsgd_desc* desc, void* stream, Tiling* t) {
     t->tile_prefix = plan->tile_prefix;
     t->offsets_dev = plan->offsets_dev;
   }
-  t->ls.grid = t->tm.num_tiles < g_tuning.max_workgroups ? t->tm.num_tiles : g_tuning.max_workgroups;
-  t->ls.lds_reserve = lds_reserve_for(g_tuning.workgroups_per_cu);
+  t->ls.grid = t->tm.num_tiles < tune.max_workgroups ? t->tm.num_tiles : tune.max_workgroups;
+  t->ls.lds_reserve = lds_reserve_for(tune.workgroups_per_cu);
   t->ls.stream = static_cast<hipStream_t>(stream);
   take_taps(&t->ls);
   return INTSGD_OK;
@@ -337,7 +350,7 @@ intsgd_status intsgd_prepare(const intsgd_desc* desc) {
   INTSGD_TRY(validate_desc(desc));
   if (desc->num_blocks == 1) return INTSGD_OK;
   const DevicePlan* plan = nullptr;
-  return get_plan(desc, g_tuning.tile_coords, &plan);
+  return get_plan(desc, effective_tuning(desc).tile_coords, &plan);
 }
 
 void intsgd_release(void) {
@@ -375,7 +388,8 @@ intsgd_status intsgd_int_sum(const intsgd_desc* desc, const void* const* q, int3
   fill_ptrs(&qp, q, desc->n);
   // about four quads per thread and pass of the grid-stride loop
   const uint64_t want = tiles_of((desc->d >> 2) + 1, INTSGD_THREADS_PER_WORKGROUP * 4);
-  LaunchShape ls{(uint32_t)(want < g_tuning.max_workgroups ? want : g_tuning.max_workgroups), 0,
+  const uint32_t cap = effective_tuning(desc).max_workgroups;
+  LaunchShape ls{(uint32_t)(want < cap ? want : cap), 0,
                  static_cast<hipStream_t>(hip_stream), nullptr, nullptr};
   take_taps(&ls);
   return done(launch_int_sum(desc->d, ls, desc->n, desc->wire, qp, sum_out));
@@ -418,7 +432,7 @@ intsgd_status intsgd_next_alpha(const intsgd_desc* desc, const double* norm_sq, 
   const uint64_t* offsets_dev = nullptr;
   if (desc->num_blocks > 1) {
     const DevicePlan* plan = nullptr;
-    INTSGD_TRY(get_plan(desc, g_tuning.tile_coords, &plan));
+    INTSGD_TRY(get_plan(desc, effective_tuning(desc).tile_coords, &plan));
     offsets_dev = plan->offsets_dev;
   }
   const AlphaRule rule{r, alpha_out, offsets_dev, beta, eps, eta};
@@ -512,9 +526,7 @@ intsgd_status intsgd_set_tuning(const intsgd_tuning* tuning) {
   if (grid > kMaxGrid) return INTSGD_EINVAL;
   if (wgs != 0 && (wgs < 2 || wgs > 8)) return INTSGD_EINVAL;
   std::lock_guard<std::mutex> lock(g_mutex);
-  if (tile != 0) g_tuning.tile_coords = tile;
-  if (grid != 0) g_tuning.max_workgroups = grid;
-  if (wgs != 0) g_tuning.workgroups_per_cu = wgs;
+  g_tuning = *tuning;
   return INTSGD_OK;
 }
 

@@ -112,8 +112,13 @@ __device__ __forceinline__ int32_t cvt_i32_saturating(float r) {
   return q;
 }
 
+// Clamp to [-L, L] (L >= 1, wave-uniform) as one median-of-three; the compiler cannot
+// form it from min/max because it cannot prove -L <= L.  Only one operand may be an
+// SGPR on this ISA, hence L in a VGPR.
 __device__ __forceinline__ int32_t clamp_sym(int32_t q, int32_t L) {
-  return min(max(q, -L), L);
+  int32_t r;
+  asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(q), "s"(-L), "v"(L));
+  return r;
 }
 
 // Section 5.1 deterministic rounding (nearest, ties to even) of t = alpha*g, clipped

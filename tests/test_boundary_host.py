@@ -137,10 +137,11 @@ def test_tuning_knobs_are_validated():
         assert lib.intsgd_set_tuning(C.byref(bad)) == EINVAL
     assert lib.intsgd_set_tuning(None) == EINVAL
     assert P.intsgd_get_tuning() == before
+    assert before == (0, 0, 0)                           # everything automatic by default
     P.intsgd_set_tuning(4096, 100, 4)
     assert P.intsgd_get_tuning() == (4096, 100, 4)
-    P.intsgd_set_tuning(tile_coords=1024)                # zero fields keep their value
-    assert P.intsgd_get_tuning() == (1024, 100, 4)
+    P.intsgd_set_tuning(tile_coords=1024)                # zero fields go back to automatic
+    assert P.intsgd_get_tuning() == (1024, 0, 0)
     P.intsgd_set_tuning(*before)
     # the workspace size does not depend on the tuning
     desc = P.Desc(10**7, 8)

@@ -341,7 +341,7 @@ def sampled_check(w: W.Workload, steps, slices_per_step=48, slice_len=8192):
     x = W.make_params(w, DEV)
     buf = torch.empty((w.n, W.row_stride(w.d)), dtype=torch.float32, device=DEV)
     rng = np.random.default_rng(w.config_id)
-    tile = P.intsgd_get_tuning()[0]
+    tile = P.intsgd_get_tuning()[0] or (4096 if w.rounding else 2048)
     for k in range(1, steps + 1):
         _, rows = W.make_gradients(w, k, DEV, out=buf)
         a_gpu = host(st.alpha).copy()
