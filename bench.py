@@ -42,9 +42,10 @@ def parse():
     return ap.parse_args()
 
 
-def cpu_baseline(w, rows, alpha_host, x_host, max_wc=420_000_000):
-    """The oracle as it stands, single-threaded, on a bounded leading slice of the same
-    workload (the whole vector when it is small enough); reported in the metric's unit."""
+def cpu_baseline(w, rows, alpha_host, x_host, max_wc=420_000_000, steps=4):
+    """The oracle as it stands, single-threaded, on a bounded sample of the same workload:
+    `steps` consecutive steps on the leading slice of at most max_wc worker-coordinates
+    (the whole vector when it is small enough); reported in the metric's unit."""
     import numpy as np
 
     import oracle
@@ -53,15 +54,21 @@ def cpu_baseline(w, rows, alpha_host, x_host, max_wc=420_000_000):
     if w.block_offsets is not None:
         off = np.array(w.block_offsets, np.uint64)
     g = [r[:ln].cpu().numpy() for r in rows]
+    x = x_host[:ln]
+    alpha = alpha_host
+    r = np.zeros(w.num_blocks)
     t0 = time.perf_counter()
-    out = oracle.step(g, alpha_host, x_host[:ln], rounding=w.rounding, L=w.clip, eta=w.eta,
-                      seed=w.philox_seed, step=1, offsets=off)
-    oracle.next_alpha(out["normsq"], np.zeros(w.num_blocks), d=w.d, n=w.n, beta=w.beta, eps=w.eps,
-                      eta=w.eta, offsets=off)
+    for k in range(1, steps + 1):
+        out = oracle.step(g, alpha, x, rounding=w.rounding, L=w.clip, eta=w.eta,
+                          seed=w.philox_seed, step=k, offsets=off)
+        x = out["x_new"]
+        r, _, alpha, _ = oracle.next_alpha(out["normsq"], r, d=w.d, n=w.n, beta=w.beta, eps=w.eps,
+                                           eta=w.eta, offsets=off)
     dt = time.perf_counter() - t0
-    return {"value": 4.0 * w.n * ln / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": "one step on the first %d of %d coordinates x %d workers (%.1f s)" % (
-                ln, w.d, w.n, dt)}
+    return {"value": 4.0 * w.n * ln * steps / dt / 1e9, "unit": "GB/s", "cores": 1,
+            "kind": "oracle",
+            "sample": "%d steps on the first %d of %d coordinates x %d workers (%.1f s)" % (
+                steps, ln, w.d, w.n, dt)}
 
 
 class HipEvents:

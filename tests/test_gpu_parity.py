@@ -380,3 +380,50 @@ def test_config5_full_size_sampled():
     assert free > 70e9, "needs the 288 GB MI355X"
     sampled_check(W.config(5), steps=1, slices_per_step=64)
     torch.cuda.empty_cache()
+
+
+def test_whole_step_call_equals_step_then_rule():
+    """intsgd_step_fused_next_alpha == intsgd_step_fused followed by intsgd_next_alpha,
+    bit for bit, for one block and for several."""
+    for offsets in (None, [0, 1000, 1001, 50000, 120003]):
+        d, n = 120003, 5
+        B = 1 if offsets is None else len(offsets) - 1
+        alpha, g, x = make_case(d, n, offsets, seed=77)
+        desc = P.Desc(d, n, rounding=P.ROUND_STOCHASTIC, clip=500, seed=3, step=8, block_offsets=offsets)
+        ws = P.new_workspace(desc, DEV)
+        rows = rows_on_device(g)
+        r0 = np.random.default_rng(1).uniform(1e-6, 1e-3, B)
+        out = []
+        for chained in (False, True):
+            d_x, d_a, d_r = dev(x), dev(alpha), dev(r0.copy())
+            d_ns = torch.zeros(B, dtype=torch.float64, device=DEV)
+            d_cnt = torch.zeros(n, dtype=torch.int64, device=DEV)
+            if chained:
+                P.intsgd_step_fused_next_alpha(desc, rows, d_a, 0.1, d_x, d_r, 0.9, 1e-8, d_ns, d_cnt, ws)
+            else:
+                P.intsgd_step_fused(desc, rows, d_a, 0.1, d_x, d_ns, d_cnt, ws)
+                P.intsgd_next_alpha(desc, d_ns, d_r, 0.9, 1e-8, 0.1, d_a)
+            out.append([host(t).copy() for t in (d_x, d_a, d_r, d_ns, d_cnt)])
+        for a, b in zip(*out):
+            assert np.array_equal(a.view(np.uint8), b.view(np.uint8))
+
+
+def test_profiling_taps_bracket_the_sweep():
+    import bench
+    hip = bench.HipEvents()
+    w = W.config(2).scaled(4_000_000)
+    desc = P.Desc(w.d, w.n, clip=w.clip)
+    st = Stepper(desc, eta=w.eta, device=DEV)
+    st.start(w.first_normsq)
+    x = W.make_params(w, DEV)
+    _, rows = W.make_gradients(w, 1, DEV)
+    st.step_fused(rows, x, 1)
+    a, b = hip.create(), hip.create()
+    P.intsgd_tap_next_launch(a, b)
+    st.step_fused(rows, x, 2)
+    st.step_fused(rows, x, 3)            # the tap is one-shot: this call must not touch the events
+    torch.cuda.synchronize()
+    ms = hip.elapsed_ms(a, b)
+    assert 0.0 < ms < 50.0
+    hip.destroy(a)
+    hip.destroy(b)
