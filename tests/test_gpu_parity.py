@@ -427,3 +427,41 @@ def test_profiling_taps_bracket_the_sweep():
     assert 0.0 < ms < 50.0
     hip.destroy(a)
     hip.destroy(b)
+
+
+def test_coordinates_beyond_32_bit_quad_index():
+    """d = 2^34 + 4099 (68.7 GB per vector, n = 1): tile starts, quad indices and the Philox
+    counter's high word all exceed 32 bits; the oracle recomputes windows at both ends."""
+    free, _ = torch.cuda.mem_get_info()
+    assert free > 160e9, "needs the 288 GB MI355X"
+    d, n = (1 << 34) + 4099, 1
+    desc = P.Desc(d, n, rounding=P.ROUND_STOCHASTIC, clip=P.default_clip(1), seed=(5 << 32) | 7, step=3)
+    ws = P.new_workspace(desc, DEV)
+    g = torch.empty(d, dtype=torch.float32, device=DEV)
+    x = torch.empty(d, dtype=torch.float32, device=DEV)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(1234)
+    for a in range(0, d, 1 << 28):
+        g[a:a + (1 << 28)].normal_(0.0, 1e-3, generator=gen)
+        x[a:a + (1 << 28)].normal_(0.0, 1.0, generator=gen)
+    alpha = np.array([912.5], F32)
+    ln = 8192
+    starts = [0, (1 << 32) - 4096, (1 << 33) + 1021, (1 << 34) - ln // 2, d - ln]
+    x_old = [host(x[s:s + ln]).copy() for s in starts]
+    d_ns = torch.zeros(1, dtype=torch.float64, device=DEV)
+    d_cnt = torch.zeros(1, dtype=torch.int64, device=DEV)
+    P.intsgd_step_fused(desc, [g], dev(alpha), 0.1, x, d_ns, d_cnt, ws)
+    torch.cuda.synchronize()
+    assert u64(d_cnt)[0] == 0
+    for s, xo in zip(starts, x_old):
+        out = oracle.step([host(g[s:s + ln])], alpha, xo, rounding=1, L=P.default_clip(1), eta=0.1,
+                          seed=(5 << 32) | 7, step=3, j0=s)
+        assert_within_ulp(host(x[s:s + ln]), out["x_new"], 1, "x[%d:+%d]" % (s, ln))
+        changed = int((out["x_new"] != xo).sum())
+        assert changed > ln // 4          # the update really happened there
+    # the norm against the rule of thumb E||dx||^2 = (eta/alpha)^2 d E[S^2], S = Int(alpha g)
+    t = float(alpha[0]) * 1e-3
+    expect = (0.1 / float(alpha[0])) ** 2 * d * (t * t + 1.0 / 6.0)
+    assert abs(host(d_ns)[0] / expect - 1.0) < 0.05
+    del g, x
+    torch.cuda.empty_cache()
