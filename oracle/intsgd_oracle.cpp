@@ -168,6 +168,30 @@ void oracle_decode_update(const int32_t* sum, uint64_t j0, uint64_t len, const f
   }
 }
 
+// Momentum / weight-decay form of the update line (the optimizer of Section 5's
+// experiments: SGD with momentum 0.9 and weight decay 1e-4; the paper's code is
+// PyTorch, whose SGD rule this is).  Per coordinate, in fp64 with each operation
+// rounded on its own, the two state vectors stored in fp32:
+//   g~ = S * (1 / (n alpha));  dd = g~ + wd x;  m' = fl32(mu m + dd);  x' = fl32(x - eta m').
+void oracle_decode_update_momentum(const int32_t* sum, uint64_t j0, uint64_t len,
+                                   const float* alpha, const uint64_t* offsets, uint32_t B,
+                                   uint32_t n, double eta, double mu, double wd, const float* x,
+                                   const float* m, float* x_new, float* m_new) {
+  for (uint64_t t_ = 0; t_ < len; ++t_) {
+    const uint64_t j = j0 + t_;
+    const double a = (double)alpha[block_of(j, offsets, B)];
+    const double cg = 1.0 / ((double)n * a);
+    const double gt = cg * (double)sum[t_];
+    const double decay = wd * (double)x[t_];
+    const double dd = gt + decay;
+    const double carried = mu * (double)m[t_];
+    const float mn = (float)(carried + dd);
+    const double stepv = eta * (double)mn;
+    m_new[t_] = mn;
+    x_new[t_] = (float)((double)x[t_] - stepv);
+  }
+}
+
 // ||(x^{k+1})_l - (x^k)_l||^2 per block over the slice, ADDED into normsq[B]
 // (the caller zeroes it), so slices can be accumulated.
 void oracle_update_norm(const float* x_new, const float* x_old, uint64_t j0, uint64_t len,
@@ -229,6 +253,29 @@ uint64_t oracle_step(const float* const* grads, uint32_t n, uint64_t j0, uint64_
   if (!s) { local_sum.resize(len); s = local_sum.data(); }
   const uint64_t overflow = oracle_int_sum(qp.data(), n, len, s);
   oracle_decode_update(s, j0, len, alpha, offsets, B, n, eta, x, x_new, nullptr);
+  oracle_update_norm(x_new, x, j0, len, offsets, B, normsq);
+  return overflow;
+}
+
+// oracle_step with the momentum / weight-decay update in place of the plain one.
+uint64_t oracle_step_momentum(const float* const* grads, uint32_t n, uint64_t j0, uint64_t len,
+                              const float* alpha, const uint64_t* offsets, uint32_t B,
+                              int rounding, int32_t L, uint64_t seed, uint32_t step, double eta,
+                              double mu, double wd, const float* x, const float* m, float* x_new,
+                              float* m_new, int32_t* sum_out, uint64_t* sat_count,
+                              double* normsq) {
+  std::vector<std::vector<int32_t>> q(n, std::vector<int32_t>(len));
+  std::vector<const int32_t*> qp(n);
+  for (uint32_t i = 0; i < n; ++i) {
+    sat_count[i] = oracle_compress(grads[i], j0, len, alpha, offsets, B, rounding, L, seed,
+                                   step, i, q[i].data());
+    qp[i] = q[i].data();
+  }
+  std::vector<int32_t> local_sum;
+  int32_t* s = sum_out;
+  if (!s) { local_sum.resize(len); s = local_sum.data(); }
+  const uint64_t overflow = oracle_int_sum(qp.data(), n, len, s);
+  oracle_decode_update_momentum(s, j0, len, alpha, offsets, B, n, eta, mu, wd, x, m, x_new, m_new);
   oracle_update_norm(x_new, x, j0, len, offsets, B, normsq);
   return overflow;
 }

@@ -13,7 +13,8 @@ from . import build as _build
 
 __all__ = [
     "philox4x32_10", "random_word", "int_random", "int_nearest", "saturate", "compress",
-    "int_sum", "decode_update", "update_norm", "next_alpha", "step",
+    "int_sum", "decode_update", "update_norm", "next_alpha", "step", "decode_update_momentum",
+    "step_momentum",
     "ROUND_NEAREST_EVEN", "ROUND_STOCHASTIC",
 ]
 
@@ -46,6 +47,15 @@ _lib.oracle_int_sum.restype = C.c_uint64
 _lib.oracle_decode_update.argtypes = [_i32p, C.c_uint64, C.c_uint64, _f32p, _u64p, C.c_uint32,
                                       C.c_uint32, C.c_double, _f32p, _f32p, _f32p]
 _lib.oracle_decode_update.restype = None
+_lib.oracle_decode_update_momentum.argtypes = [_i32p, C.c_uint64, C.c_uint64, _f32p, _u64p,
+                                               C.c_uint32, C.c_uint32, C.c_double, C.c_double,
+                                               C.c_double, _f32p, _f32p, _f32p, _f32p]
+_lib.oracle_decode_update_momentum.restype = None
+_lib.oracle_step_momentum.argtypes = [C.POINTER(_f32p), C.c_uint32, C.c_uint64, C.c_uint64, _f32p,
+                                      _u64p, C.c_uint32, C.c_int, C.c_int32, C.c_uint64, C.c_uint32,
+                                      C.c_double, C.c_double, C.c_double, _f32p, _f32p, _f32p, _f32p,
+                                      _i32p, _u64p, _f64p]
+_lib.oracle_step_momentum.restype = C.c_uint64
 _lib.oracle_update_norm.argtypes = [_f32p, _f32p, C.c_uint64, C.c_uint64, _u64p, C.c_uint32,
                                     _f64p]
 _lib.oracle_update_norm.restype = None
@@ -195,3 +205,45 @@ def step(grads, alpha, x, *, rounding, L, eta, seed=0, step=0, j0=0, offsets=Non
                            int(step), float(eta), _ptr(x, C.c_float), _ptr(xn, C.c_float),
                            _ptr(S, C.c_int32), _ptr(sat, C.c_uint64), _ptr(ns, C.c_double))
     return dict(x_new=xn, S=S, sat_count=sat, normsq=ns, overflow=int(ovf))
+
+
+def decode_update_momentum(S, alpha, x, m, *, n, eta, mu, wd, j0=0, offsets=None):
+    """Momentum / weight-decay update -> (x_new, m_new)."""
+    S = _arr(S, np.int32)
+    x = _arr(x, np.float32)
+    m = _arr(m, np.float32)
+    assert S.size == x.size == m.size
+    a, ap = _alpha(alpha)
+    off, offp = _offsets(offsets, a.size)
+    xn = np.empty_like(x)
+    mn = np.empty_like(m)
+    _lib.oracle_decode_update_momentum(_ptr(S, C.c_int32), int(j0), S.size, ap, offp, a.size,
+                                       int(n), float(eta), float(mu), float(wd),
+                                       _ptr(x, C.c_float), _ptr(m, C.c_float), _ptr(xn, C.c_float),
+                                       _ptr(mn, C.c_float))
+    return xn, mn
+
+
+def step_momentum(grads, alpha, x, m, *, rounding, L, eta, mu, wd, seed=0, step=0, j0=0,
+                  offsets=None, normsq=None):
+    """One whole step with the momentum / weight-decay update on a slice."""
+    gs = [_arr(g, np.float32) for g in grads]
+    n, ln = len(gs), gs[0].size
+    x = _arr(x, np.float32)
+    m = _arr(m, np.float32)
+    assert x.size == ln and m.size == ln
+    a, ap = _alpha(alpha)
+    B = a.size
+    off, offp = _offsets(offsets, B)
+    ptrs = (_f32p * n)(*[_ptr(g, C.c_float) for g in gs])
+    xn = np.empty_like(x)
+    mn = np.empty_like(m)
+    S = np.empty(ln, np.int32)
+    sat = np.zeros(n, np.uint64)
+    ns = np.zeros(B, np.float64) if normsq is None else normsq
+    ovf = _lib.oracle_step_momentum(ptrs, n, int(j0), ln, ap, offp, B, int(rounding), int(L),
+                                    int(seed), int(step), float(eta), float(mu), float(wd),
+                                    _ptr(x, C.c_float), _ptr(m, C.c_float), _ptr(xn, C.c_float),
+                                    _ptr(mn, C.c_float), _ptr(S, C.c_int32), _ptr(sat, C.c_uint64),
+                                    _ptr(ns, C.c_double))
+    return dict(x_new=xn, m_new=mn, S=S, sat_count=sat, normsq=ns, overflow=int(ovf))

@@ -395,3 +395,85 @@ def test_steady_state_alpha_fixed_point():
     p = t - np.floor(t)
     q = float((p * (1 - p)).mean())
     assert math.isclose((a * sigma) ** 2, 0.5 - q, rel_tol=0.08)
+
+
+# ----------------------------------------------------------------------------- momentum form
+def test_momentum_update_in_rationals_and_special_cases():
+    """Momentum / weight-decay update (the optimizer of Section 5's experiments): each stored
+    value is the correctly rounded rational result of its own line; mu = wd = 0 stores the
+    decoded gradient in m and takes the plain SGD step with it."""
+    rng = np.random.default_rng(31)
+    n, d = 3, 16
+    alpha = F32(713.25)
+    S = rng.integers(-40, 40, d).astype(np.int32)
+    x = rng.normal(0, 1, d).astype(F32)
+    m = rng.normal(0, 0.01, d).astype(F32)
+    eta, mu, wd = 0.1, 0.9, 1e-4
+    xn, mn = oracle.decode_update_momentum(S, alpha, x, m, n=n, eta=eta, mu=mu, wd=wd)
+    a = Fraction(float(alpha))
+    half = Fraction(501, 1000)
+    for j in range(d):
+        gt = Fraction(int(S[j])) / (n * a)
+        M = Fraction(mu) * Fraction(float(m[j])) + gt + Fraction(wd) * Fraction(float(x[j]))
+        assert abs(Fraction(float(mn[j])) - M) <= Fraction(pyref.ulp32(M)) * half
+        X = Fraction(float(x[j])) - Fraction(eta) * Fraction(float(mn[j]))    # uses the STORED m'
+        assert abs(Fraction(float(xn[j])) - X) <= Fraction(pyref.ulp32(X)) * half
+    xn0, mn0 = oracle.decode_update_momentum(S, alpha, x, m, n=n, eta=eta, mu=0.0, wd=0.0)
+    _, gt32 = oracle.decode_update(S, alpha, x, n=n, eta=eta, want_gtilde=True)
+    assert np.all(np.abs(mn0.astype(np.float64) - gt32.astype(np.float64))
+                  <= np.spacing(np.abs(gt32)).astype(np.float64))
+    want = (x.astype(np.float64) - eta * mn0.astype(np.float64)).astype(F32)
+    assert np.array_equal(xn0, want)
+
+
+def test_momentum_matches_torch_sgd():
+    """Several steps against torch.optim.SGD(momentum, weight_decay) run in float64 on the
+    decoded gradients: same recursion, so agreement to fp32 rounding of the stored state."""
+    import torch
+    rng = np.random.default_rng(37)
+    n, d, alpha = 4, 500, F32(256.0)           # power of two: decoded gradient exact in fp32
+    eta, mu, wd = 0.05, 0.9, 1e-4
+    x = rng.normal(0, 1, d).astype(F32)
+    m = np.zeros(d, F32)
+    p = torch.tensor(x.astype(np.float64), requires_grad=True)
+    opt = torch.optim.SGD([p], lr=eta, momentum=mu, weight_decay=wd)
+    for k in range(12):
+        S = rng.integers(-30, 30, d).astype(np.int32)
+        x, m = oracle.decode_update_momentum(S, alpha, x, m, n=n, eta=eta, mu=mu, wd=wd)
+        p.grad = torch.tensor(S.astype(np.float64) / (n * float(alpha)))
+        opt.step()
+        ref = p.detach().numpy()
+        assert np.all(np.abs(x - ref) <= (k + 1) * 4 * np.spacing(np.abs(ref).astype(F32)) + 1e-7)
+    buf = opt.state[p]["momentum_buffer"].numpy()
+    assert np.allclose(m, buf, rtol=1e-4, atol=1e-6)
+
+
+def test_momentum_geometric_closed_form():
+    """Constant decoded gradient, no decay: m_K = g (1 - mu^K)/(1 - mu)."""
+    n, alpha, eta, mu = 2, F32(64.0), 0.1, 0.5
+    S = np.array([8, -24, 0, 128], np.int32)
+    g = S / (n * 64.0)
+    x = np.zeros(4, F32)
+    m = np.zeros(4, F32)
+    K = 10
+    for _ in range(K):
+        x, m = oracle.decode_update_momentum(S, alpha, x, m, n=n, eta=eta, mu=mu, wd=0.0)
+    assert np.allclose(m, g * (1 - mu**K) / (1 - mu), rtol=1e-6)
+    total = sum(g * (1 - mu**k) / (1 - mu) for k in range(1, K + 1))
+    assert np.allclose(x, -eta * total, rtol=1e-5)
+
+
+def test_step_momentum_composes():
+    rng = np.random.default_rng(41)
+    n, d = 3, 64
+    g = rng.normal(0, 0.01, (n, d)).astype(F32)
+    x = rng.normal(0, 1, d).astype(F32)
+    m = rng.normal(0, 0.01, d).astype(F32)
+    kw = dict(rounding=1, L=1000, eta=0.1, seed=5, step=2)
+    plain = oracle.step(list(g), F32(300.0), x, **kw)
+    mom = oracle.step_momentum(list(g), F32(300.0), x, m, mu=0.9, wd=1e-4, **kw)
+    assert np.array_equal(plain["S"], mom["S"]) and np.array_equal(plain["sat_count"], mom["sat_count"])
+    xn, mn = oracle.decode_update_momentum(mom["S"], F32(300.0), x, m, n=n, eta=0.1, mu=0.9, wd=1e-4)
+    assert np.array_equal(xn, mom["x_new"]) and np.array_equal(mn, mom["m_new"])
+    nrm = float(((xn.astype(np.float64) - x.astype(np.float64)) ** 2).sum())
+    assert math.isclose(mom["normsq"][0], nrm, rel_tol=1e-13)
