@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--no-taps", action="store_true",
                     help="do not record per-kernel events (roofline numbers are then null)")
     ap.add_argument("--global-alpha", action="store_true", help="config 4 with one alpha")
+    ap.add_argument("--momentum", action="store_true",
+                    help="momentum 0.9 / weight decay 1e-4 form of the update (fused mode)")
     return ap.parse_args()
 
 
@@ -149,11 +151,14 @@ def main():
         buf, rows = W.make_gradients(w, s + 1, dev)
         sets.append((buf, rows))
     sum_buf = torch.empty(w.d, dtype=torch.int32, device=dev) if args.mode == "two_pass" else None
+    mom = torch.zeros_like(x) if args.momentum else None
     torch.cuda.synchronize()
 
     def one_step(k):
         rows = sets[(k - 1) % pool][1]
-        if args.mode == "fused":
+        if args.momentum:
+            st.step_momentum(rows, x, mom, k, 0.9, 1e-4)  # a1-a8 with the momentum update
+        elif args.mode == "fused":
             st.step_fused(rows, x, k)                    # a1-a8, one call
         else:
             st.step_two_pass(rows, x, k, sum_buf)        # F1, F2, a8
@@ -185,6 +190,8 @@ def main():
         hip.destroy(b)
     avg_kernel_ms = sum(kernel_ms) / len(kernel_ms)
     per_coord = (4 * w.n + 8) if args.mode == "fused" else (4 * w.n + 4)
+    if args.momentum:
+        per_coord = 4 * w.n + 16
     algo_bytes = per_coord * w.d
     achieved = algo_bytes / (avg_kernel_ms * 1e-3) / 1e9
     sat = int(st.sat_count.cpu().numpy().view("uint64").sum())
@@ -206,7 +213,8 @@ def main():
         "config": {
             "workload": w.name, "d": w.d, "n_workers": w.n, "blocks": w.num_blocks,
             "rounding": "stochastic" if w.rounding else "nearest-even", "wire": "int%d" % w.wire,
-            "clip": w.clip, "grad_dist": w.grad_kind, "mode": args.mode, "gradient_sets": pool,
+            "clip": w.clip, "grad_dist": w.grad_kind,
+            "mode": args.mode + ("+momentum" if args.momentum else ""), "gradient_sets": pool,
             "tuning_overrides": {"tile_coords": tile, "max_workgroups": grid,
                                  "workgroups_per_cu": wgs_per_cu},
             "alpha_last": alpha_last,
@@ -215,7 +223,7 @@ def main():
         "roofline": {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": load_traffic(w.name, args.mode),
+            "traffic": None if args.momentum else load_traffic(w.name, args.mode),
             "kernel": "k_aggregate<ROUND, FUSED=true>: a1-a7 in one sweep" if args.mode == "fused"
                       else "k_aggregate<ROUND, FUSED=false>: a1-a4 (first of the two sweeps)",
             "algorithmic_bytes_per_launch": algo_bytes,
@@ -223,7 +231,7 @@ def main():
             "kernel_ms_median": kernel_ms[len(kernel_ms) // 2],
         },
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.momentum:
         result["cpu_baseline"] = cpu_baseline(w, sets[0][1], alpha0, x0)
     print(json.dumps(result))
 

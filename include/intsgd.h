@@ -212,6 +212,30 @@ intsgd_status intsgd_step_fused_next_alpha(const intsgd_desc* desc, const float*
                                            uint64_t* sat_count, void* workspace,
                                            size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Momentum / weight-decay form of the update (the optimizer of the paper's experiments,
+ * Appendix C.1: SGD with momentum 0.9 and weight decay 1e-4; PyTorch's SGD rule).  Per
+ * coordinate in fp64, every operation rounded on its own, both state vectors in fp32:
+ *   g~ = S (1/(n alpha));  dd = g~ + weight_decay x;  m <- fl32(mu m + dd);  x <- fl32(x - eta m).
+ * m: DEVICE float[d] in/out (16-byte aligned); 0 <= mu < 1; weight_decay >= 0.
+ * norm_sq_out is ||x_new - x_old||^2 per block as everywhere else (it now contains the
+ * momentum term).
+ *
+ * intsgd_decode_update_momentum: F2 with this update (a5-a7 on a given aggregate).
+ * intsgd_step_momentum: F3 with this update in one sweep; if r is not NULL, a8 is applied
+ * as in intsgd_step_fused_next_alpha (alpha in/out), otherwise alpha is only read.
+ */
+intsgd_status intsgd_decode_update_momentum(const intsgd_desc* desc, const int32_t* sum,
+                                            const float* alpha, double eta, double mu,
+                                            double weight_decay, float* x, float* m,
+                                            double* norm_sq_out, void* workspace,
+                                            size_t workspace_bytes, void* hip_stream);
+intsgd_status intsgd_step_momentum(const intsgd_desc* desc, const float* const* grads,
+                                   float* alpha, double eta, double mu, double weight_decay,
+                                   float* x, float* m, double* r, double beta, double eps,
+                                   double* norm_sq_out, uint64_t* sat_count, void* workspace,
+                                   size_t workspace_bytes, void* hip_stream);
+
 /* Tuning overrides (process-wide; not part of the numerical contract: results do not
  * depend on them except for the summation order of the norm).  A field that is 0
  * means "automatic": the library picks per call (by rounding mode) what measured best

@@ -16,6 +16,7 @@ __all__ = [
     "intsgd_release", "intsgd_compress", "intsgd_int_sum", "intsgd_decode_update",
     "intsgd_update_norm", "intsgd_next_alpha", "intsgd_next_alpha_host", "intsgd_compress_sum",
     "intsgd_decode_update_norm", "intsgd_step_fused", "intsgd_step_fused_next_alpha",
+    "intsgd_decode_update_momentum", "intsgd_step_momentum",
     "intsgd_tap_next_launch", "intsgd_set_tuning", "intsgd_get_tuning", "intsgd_status_string",
     "new_workspace", "EXPORTED_SYMBOLS",
 ]
@@ -28,7 +29,8 @@ MAX_WORKERS = 128
 
 EXPORTED_SYMBOLS = [
     "intsgd_workspace_bytes", "intsgd_tap_next_launch", "intsgd_prepare", "intsgd_release",
-    "intsgd_compress", "intsgd_step_fused_next_alpha",
+    "intsgd_compress", "intsgd_step_fused_next_alpha", "intsgd_decode_update_momentum",
+    "intsgd_step_momentum",
     "intsgd_int_sum", "intsgd_decode_update", "intsgd_update_norm", "intsgd_next_alpha",
     "intsgd_next_alpha_host", "intsgd_compress_sum", "intsgd_decode_update_norm",
     "intsgd_step_fused", "intsgd_set_tuning", "intsgd_get_tuning", "intsgd_status_string",
@@ -85,6 +87,10 @@ _lib.intsgd_step_fused.argtypes = [_DP, _PP, _P, C.c_double, _P, _P, _P, _P, C.c
 _lib.intsgd_step_fused_next_alpha.argtypes = [_DP, _PP, _P, C.c_double, _P, _P, C.c_double,
                                               C.c_double, _P, _P, _P, C.c_size_t, _P]
 _lib.intsgd_tap_next_launch.argtypes = [_P, _P]
+_lib.intsgd_decode_update_momentum.argtypes = [_DP, _P, _P, C.c_double, C.c_double, C.c_double, _P,
+                                               _P, _P, _P, C.c_size_t, _P]
+_lib.intsgd_step_momentum.argtypes = [_DP, _PP, _P, C.c_double, C.c_double, C.c_double, _P, _P, _P,
+                                      C.c_double, C.c_double, _P, _P, _P, C.c_size_t, _P]
 _lib.intsgd_set_tuning.argtypes = [C.POINTER(_CTuning)]
 _lib.intsgd_get_tuning.argtypes = [C.POINTER(_CTuning)]
 _lib.intsgd_get_tuning.restype = None
@@ -95,7 +101,8 @@ _lib.intsgd_last_hip_error.restype = C.c_char_p
 for _name in ("intsgd_prepare", "intsgd_compress", "intsgd_int_sum", "intsgd_decode_update",
               "intsgd_update_norm", "intsgd_next_alpha", "intsgd_next_alpha_host",
               "intsgd_compress_sum", "intsgd_decode_update_norm", "intsgd_step_fused",
-              "intsgd_step_fused_next_alpha", "intsgd_tap_next_launch", "intsgd_set_tuning"):
+              "intsgd_step_fused_next_alpha", "intsgd_tap_next_launch", "intsgd_set_tuning",
+              "intsgd_decode_update_momentum", "intsgd_step_momentum"):
     getattr(_lib, _name).restype = C.c_int
 
 
@@ -330,6 +337,37 @@ def intsgd_step_fused_next_alpha(desc, grads, alpha, eta, x, r, beta, eps, norm_
                                              _ptr(x), _ptr(r), float(beta), float(eps),
                                              _ptr(norm_sq_out), _ptr(sat_count), w, wb,
                                              _stream(stream)), "intsgd_step_fused_next_alpha")
+
+
+def intsgd_decode_update_momentum(desc, sum_, alpha, eta, mu, weight_decay, x, m, norm_sq_out,
+                                  workspace, stream=None):
+    _need(sum_, desc.d, torch.int32, "sum")
+    _need(alpha, desc.num_blocks, torch.float32, "alpha")
+    _need(x, desc.d, torch.float32, "x")
+    _need(m, desc.d, torch.float32, "m")
+    _need(norm_sq_out, desc.num_blocks, torch.float64, "norm_sq_out")
+    w, wb = _ws(workspace)
+    _check(_lib.intsgd_decode_update_momentum(desc.ref(), _ptr(sum_), _ptr(alpha), float(eta),
+                                              float(mu), float(weight_decay), _ptr(x), _ptr(m),
+                                              _ptr(norm_sq_out), w, wb, _stream(stream)),
+           "intsgd_decode_update_momentum")
+
+
+def intsgd_step_momentum(desc, grads, alpha, eta, mu, weight_decay, x, m, r, beta, eps, norm_sq_out,
+                         sat_count, workspace, stream=None):
+    """r may be None: alpha is then only read (no a8)."""
+    _need_rows(desc, grads, torch.float32, "grads")
+    _need(alpha, desc.num_blocks, torch.float32, "alpha")
+    _need(x, desc.d, torch.float32, "x")
+    _need(m, desc.d, torch.float32, "m")
+    _need(r, desc.num_blocks, torch.float64, "r")
+    _need(norm_sq_out, desc.num_blocks, torch.float64, "norm_sq_out")
+    _need(sat_count, desc.n, torch.int64, "sat_count")
+    w, wb = _ws(workspace)
+    _check(_lib.intsgd_step_momentum(desc.ref(), _ptr_array(grads), _ptr(alpha), float(eta),
+                                     float(mu), float(weight_decay), _ptr(x), _ptr(m), _ptr(r),
+                                     float(beta), float(eps), _ptr(norm_sq_out), _ptr(sat_count),
+                                     w, wb, _stream(stream)), "intsgd_step_momentum")
 
 
 def intsgd_set_tuning(tile_coords=0, max_workgroups=0, workgroups_per_cu=0):

@@ -311,16 +311,25 @@ using namespace intsgd;
 namespace {
 
 // Shared body of intsgd_step_fused and intsgd_step_fused_next_alpha.
+intsgd_status validate_momentum(const Momentum* mom) {
+  if (mom == nullptr) return INTSGD_OK;
+  INTSGD_TRY(validate_vec(mom->m));
+  if (!(mom->mu >= 0.0 && mom->mu < 1.0)) return INTSGD_EINVAL;
+  if (!(mom->wd >= 0.0) || !std::isfinite(mom->wd)) return INTSGD_EINVAL;
+  return INTSGD_OK;
+}
+
 intsgd_status step_fused_impl(const intsgd_desc* desc, const float* const* grads,
                               const float* alpha, double eta, float* x, double* norm_sq_out,
                               uint64_t* sat_count, void* workspace, size_t workspace_bytes,
                               void* hip_stream, double* r, float* alpha_out, double beta,
-                              double eps) {
+                              double eps, const Momentum* mom = nullptr) {
   INTSGD_TRY(validate_desc(desc));
   INTSGD_TRY(validate_worker_ptrs((const void* const*)grads, desc->n));
   INTSGD_TRY(validate_vec(x));
   if (alpha == nullptr || norm_sq_out == nullptr || sat_count == nullptr) return INTSGD_EINVAL;
   INTSGD_TRY(validate_rule(beta, eps, eta));
+  INTSGD_TRY(validate_momentum(mom));
   INTSGD_TRY(validate_workspace(desc, workspace, workspace_bytes));
   Tiling t;
   INTSGD_TRY(make_tiling(desc, hip_stream, &t));
@@ -328,7 +337,7 @@ intsgd_status step_fused_impl(const intsgd_desc* desc, const float* const* grads
   fill_ptrs(&g, (const void* const*)grads, desc->n);
   Finish fin = make_finish(desc, t, workspace, norm_sq_out, sat_count);
   if (r != nullptr) fin.rule = AlphaRule{r, alpha_out, t.offsets_dev, beta, eps, eta};
-  return done(launch_step_fused(t.tm, t.ls, desc->n, round_spec(desc), g, alpha, eta, x, fin));
+  return done(launch_step_fused(t.tm, t.ls, desc->n, round_spec(desc), g, alpha, eta, x, mom, fin));
 }
 
 }  // namespace
@@ -496,8 +505,37 @@ intsgd_status intsgd_decode_update_norm(const intsgd_desc* desc, const int32_t* 
   INTSGD_TRY(validate_workspace(desc, workspace, workspace_bytes));
   Tiling t;
   INTSGD_TRY(make_tiling(desc, hip_stream, &t));
-  return done(launch_decode_update_norm(t.tm, t.ls, desc->n, sum, alpha, eta, x,
+  return done(launch_decode_update_norm(t.tm, t.ls, desc->n, sum, alpha, eta, x, nullptr,
                                         make_finish(desc, t, workspace, norm_sq_out, nullptr)));
+}
+
+intsgd_status intsgd_decode_update_momentum(const intsgd_desc* desc, const int32_t* sum,
+                                            const float* alpha, double eta, double mu,
+                                            double weight_decay, float* x, float* m,
+                                            double* norm_sq_out, void* workspace,
+                                            size_t workspace_bytes, void* hip_stream) {
+  INTSGD_TRY(validate_desc(desc));
+  INTSGD_TRY(validate_vec(sum));
+  INTSGD_TRY(validate_vec(x));
+  if (alpha == nullptr || norm_sq_out == nullptr) return INTSGD_EINVAL;
+  INTSGD_TRY(validate_rule(0.0, 0.0, eta));
+  const Momentum mom{m, mu, weight_decay};
+  INTSGD_TRY(validate_momentum(&mom));
+  INTSGD_TRY(validate_workspace(desc, workspace, workspace_bytes));
+  Tiling t;
+  INTSGD_TRY(make_tiling(desc, hip_stream, &t));
+  return done(launch_decode_update_norm(t.tm, t.ls, desc->n, sum, alpha, eta, x, &mom,
+                                        make_finish(desc, t, workspace, norm_sq_out, nullptr)));
+}
+
+intsgd_status intsgd_step_momentum(const intsgd_desc* desc, const float* const* grads,
+                                   float* alpha, double eta, double mu, double weight_decay,
+                                   float* x, float* m, double* r, double beta, double eps,
+                                   double* norm_sq_out, uint64_t* sat_count, void* workspace,
+                                   size_t workspace_bytes, void* hip_stream) {
+  const Momentum mom{m, mu, weight_decay};
+  return step_fused_impl(desc, grads, alpha, eta, x, norm_sq_out, sat_count, workspace,
+                         workspace_bytes, hip_stream, r, alpha, r ? beta : 0.0, r ? eps : 0.0, &mom);
 }
 
 intsgd_status intsgd_step_fused(const intsgd_desc* desc, const float* const* grads,

@@ -60,6 +60,12 @@ struct AlphaRule {
   double beta, eps, eta;
 };
 
+// Momentum / weight-decay form of the update: state vector and coefficients.
+struct Momentum {
+  float* m;      // device, d
+  double mu, wd;
+};
+
 // What the final-sum kernel behind a sweep needs.
 struct Finish {
   double* norm_partial;           // one slot per tile
@@ -96,10 +102,10 @@ hipError_t launch_compress_sum(const TileMap& tm, const LaunchShape& ls, uint32_
                                int32_t* sum_out, const Finish& fin);
 hipError_t launch_decode_update_norm(const TileMap& tm, const LaunchShape& ls, uint32_t n,
                                      const int32_t* sum, const float* alpha, double eta, float* x,
-                                     const Finish& fin);
+                                     const Momentum* mom, const Finish& fin);
 hipError_t launch_step_fused(const TileMap& tm, const LaunchShape& ls, uint32_t n,
                              const RoundSpec& rs, const WorkerPtrs& grads, const float* alpha,
-                             double eta, float* x, const Finish& fin);
+                             double eta, float* x, const Momentum* mom, const Finish& fin);
 hipError_t launch_next_alpha(hipStream_t stream, const double* norm_sq, const AlphaRule& rule,
                              uint32_t B, uint32_t n, uint64_t d);
 

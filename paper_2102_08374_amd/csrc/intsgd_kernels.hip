@@ -343,6 +343,41 @@ __device__ __forceinline__ double decode_constant(double eta, uint32_t n, float 
   return eta / ((double)n * (double)alpha);
 }
 
+// Momentum / weight-decay form of a6 (PyTorch's SGD rule, the optimizer of Section 5's
+// experiments), fp64 with every operation rounded on its own, state stored in fp32:
+//   g~ = cg S (cg = 1/(n alpha));  dd = g~ + wd x;  m' = fl32(mu m + dd);  x' = fl32(x - eta m').
+struct MomentumRule {
+  double cg, eta, mu, wd;
+};
+
+__device__ __forceinline__ float momentum_coord(float x, float& m, int32_t S,
+                                                const MomentumRule& u, double& acc) {
+  const double xo = (double)x;
+  const double gt = u.cg * (double)S;
+  const double decay = u.wd * xo;
+  const double dd = gt + decay;
+  const double carried = u.mu * (double)m;
+  const float mn = (float)(carried + dd);
+  const double stepv = u.eta * (double)mn;
+  const float xn = (float)(xo - stepv);
+  const double delta = (double)xn - xo;
+  acc = __builtin_fma(delta, delta, acc);
+  m = mn;
+  return xn;
+}
+
+__device__ __forceinline__ vf4 momentum_quad(vf4 xv, vf4& mv, vi4 S, const MomentumRule& u,
+                                             double& acc) {
+  vf4 xn;
+  float m0 = mv.x, m1 = mv.y, m2 = mv.z, m3 = mv.w;
+  xn.x = momentum_coord(xv.x, m0, S.x, u, acc);
+  xn.y = momentum_coord(xv.y, m1, S.y, u, acc);
+  xn.z = momentum_coord(xv.z, m2, S.z, u, acc);
+  xn.w = momentum_coord(xv.w, m3, S.w, u, acc);
+  mv = vf4{m0, m1, m2, m3};
+  return xn;
+}
+
 // ------------------------------------------------------------------ a8
 // Section 4.1 (Proposition 2) for one block, Algorithm 2 otherwise; fp64, in the
 // operation order written in the public header.
@@ -478,11 +513,13 @@ struct AggregateArgs {
   double eta;            // F3
   float* x;              // F3
   int32_t* sum_out;      // F1
+  float* m;              // F3 with momentum
+  double mu, wd;         // F3 with momentum
   Finish fin;
   WorkerPtrs grads;
 };
 
-template <int ROUND, bool FUSED>
+template <int ROUND, bool FUSED, bool MOMENTUM>
 struct AggregateOp {
   const AggregateArgs& a;
   ReduceLds& lds;
@@ -491,30 +528,49 @@ struct AggregateOp {
   uint64_t q0;
   uint32_t nq;
   __amdgpu_buffer_rsrc_t out;   // x (F3) or the aggregate (F1) of this tile body
+  __amdgpu_buffer_rsrc_t mom;   // momentum buffer of this tile body
+  MomentumRule rule;
 
   __device__ __forceinline__ AggregateOp(const AggregateArgs& args, ReduceLds& l)
       : a(args), lds(l), alpha(0.f), c(0.0), acc(0.0), q0(0), nq(0) {}
   __device__ __forceinline__ void begin_tile(uint32_t blk) {
     alpha = a.alpha[blk];
-    if (FUSED) c = decode_constant(a.eta, a.n, alpha);
+    if (FUSED && !MOMENTUM) c = decode_constant(a.eta, a.n, alpha);
+    if (MOMENTUM) rule = MomentumRule{1.0 / ((double)a.n * (double)alpha), a.eta, a.mu, a.wd};
     acc = 0.0;
   }
   __device__ __forceinline__ void scalar(uint64_t j) {
     const int32_t S = aggregate_scalar<ROUND>(a.grads, a.n, j, alpha, a.rs, lds.sat);
-    if (FUSED) a.x[j] = update_coord(a.x[j], S, c, acc);
-    else a.sum_out[j] = S;
+    if (MOMENTUM) {
+      float mj = a.m[j];
+      a.x[j] = momentum_coord(a.x[j], mj, S, rule, acc);
+      a.m[j] = mj;
+    } else if (FUSED) {
+      a.x[j] = update_coord(a.x[j], S, c, acc);
+    } else {
+      a.sum_out[j] = S;
+    }
   }
   __device__ __forceinline__ void begin_body(uint64_t first_quad, uint32_t quads) {
     q0 = first_quad;
     nq = quads;
     out = FUSED ? make_stream((vf4*)a.x + q0, nq * 16u) : make_stream((vi4*)a.sum_out + q0, nq * 16u);
+    if (MOMENTUM) mom = make_stream((vf4*)a.m + q0, nq * 16u);
   }
   __device__ __forceinline__ void quad(uint32_t ql) {
-    vf4 xv = vf4{0.f, 0.f, 0.f, 0.f};
+    vf4 xv = vf4{0.f, 0.f, 0.f, 0.f}, mv = vf4{0.f, 0.f, 0.f, 0.f};
     if (FUSED) xv = as_f(load128<INTSGD_X_LOAD_POLICY>(out, ql * 16u));
+    if (MOMENTUM) mv = as_f(load128<INTSGD_X_LOAD_POLICY>(mom, ql * 16u));
     const vi4 S = aggregate_quad<ROUND>(a.grads, a.n, q0, nq, ql, alpha, a.rs, lds.sat);
-    if (FUSED) store128<INTSGD_X_STORE_POLICY>(out, ql * 16u, as_u(update_quad(xv, S, c, acc)));
-    else store128<INTSGD_X_STORE_POLICY>(out, ql * 16u, as_u(S));
+    if (MOMENTUM) {
+      const vf4 xn = momentum_quad(xv, mv, S, rule, acc);
+      store128<INTSGD_X_STORE_POLICY>(mom, ql * 16u, as_u(mv));
+      store128<INTSGD_X_STORE_POLICY>(out, ql * 16u, as_u(xn));
+    } else if (FUSED) {
+      store128<INTSGD_X_STORE_POLICY>(out, ql * 16u, as_u(update_quad(xv, S, c, acc)));
+    } else {
+      store128<INTSGD_X_STORE_POLICY>(out, ql * 16u, as_u(S));
+    }
   }
   __device__ __forceinline__ void end_tile(uint32_t t, uint32_t iter) {
     if (FUSED) {
@@ -524,11 +580,11 @@ struct AggregateOp {
   }
 };
 
-template <int ROUND, bool FUSED>
+template <int ROUND, bool FUSED, bool MOMENTUM>
 __global__ __launch_bounds__(kThreads) void k_aggregate(const AggregateArgs a) {
   __shared__ ReduceLds lds;
   zero_sat(lds);
-  AggregateOp<ROUND, FUSED> op(a, lds);
+  AggregateOp<ROUND, FUSED, MOMENTUM> op(a, lds);
   drive_tiles(a.tm, op);
   __syncthreads();
   if (threadIdx.x == 0) publish_sat(a.fin, lds, blockIdx.x);
@@ -660,15 +716,18 @@ struct DecodeArgs {
   double eta;
   float* x;
   float* gtilde;         // decode_update only, may be null
+  float* m;              // momentum form only
+  double mu, wd;         // momentum form only
   Finish fin;            // F2 only
 };
 
-template <bool WITH_NORM, bool WITH_GTILDE>
+template <bool WITH_NORM, bool WITH_GTILDE, bool MOMENTUM>
 struct DecodeOp {
   const DecodeArgs& a;
   ReduceLds& lds;
   double c, na, acc;
-  __amdgpu_buffer_rsrc_t sum_s, x_s, gt_s;
+  __amdgpu_buffer_rsrc_t sum_s, x_s, gt_s, m_s;
+  MomentumRule rule;
 
   __device__ __forceinline__ DecodeOp(const DecodeArgs& args, ReduceLds& l)
       : a(args), lds(l), c(0.0), na(0.0), acc(0.0) {}
@@ -676,23 +735,38 @@ struct DecodeOp {
     const float alpha = a.alpha[blk];
     na = (double)a.n * (double)alpha;
     c = decode_constant(a.eta, a.n, alpha);
+    if (MOMENTUM) rule = MomentumRule{1.0 / na, a.eta, a.mu, a.wd};
     acc = 0.0;
   }
   __device__ __forceinline__ float gtilde_of(int32_t S) const { return (float)((double)S / na); }
   __device__ __forceinline__ void scalar(uint64_t j) {
     const int32_t S = a.sum[j];
-    a.x[j] = update_coord(a.x[j], S, c, acc);
+    if (MOMENTUM) {
+      float mj = a.m[j];
+      a.x[j] = momentum_coord(a.x[j], mj, S, rule, acc);
+      a.m[j] = mj;
+    } else {
+      a.x[j] = update_coord(a.x[j], S, c, acc);
+    }
     if (WITH_GTILDE) a.gtilde[j] = gtilde_of(S);
   }
   __device__ __forceinline__ void begin_body(uint64_t q0, uint32_t quads) {
     sum_s = make_stream((const vi4*)a.sum + q0, quads * 16u);
     x_s = make_stream((vf4*)a.x + q0, quads * 16u);
     if (WITH_GTILDE) gt_s = make_stream((vf4*)a.gtilde + q0, quads * 16u);
+    if (MOMENTUM) m_s = make_stream((vf4*)a.m + q0, quads * 16u);
   }
   __device__ __forceinline__ void quad(uint32_t ql) {
     const vi4 S = as_i(load128<kNonTemporal>(sum_s, ql * 16u));
     const vf4 xv = as_f(load128<INTSGD_X_LOAD_POLICY>(x_s, ql * 16u));
-    store128<INTSGD_X_STORE_POLICY>(x_s, ql * 16u, as_u(update_quad(xv, S, c, acc)));
+    if (MOMENTUM) {
+      vf4 mv = as_f(load128<INTSGD_X_LOAD_POLICY>(m_s, ql * 16u));
+      const vf4 xn = momentum_quad(xv, mv, S, rule, acc);
+      store128<INTSGD_X_STORE_POLICY>(m_s, ql * 16u, as_u(mv));
+      store128<INTSGD_X_STORE_POLICY>(x_s, ql * 16u, as_u(xn));
+    } else {
+      store128<INTSGD_X_STORE_POLICY>(x_s, ql * 16u, as_u(update_quad(xv, S, c, acc)));
+    }
     if (WITH_GTILDE) {
       const vf4 gt = vf4{gtilde_of(S.x), gtilde_of(S.y), gtilde_of(S.z), gtilde_of(S.w)};
       store128<kPlain>(gt_s, ql * 16u, as_u(gt));
@@ -706,10 +780,10 @@ struct DecodeOp {
   }
 };
 
-template <bool WITH_NORM, bool WITH_GTILDE>
+template <bool WITH_NORM, bool WITH_GTILDE, bool MOMENTUM>
 __global__ __launch_bounds__(kThreads) void k_decode(const DecodeArgs a) {
   __shared__ ReduceLds lds;
-  DecodeOp<WITH_NORM, WITH_GTILDE> op(a, lds);
+  DecodeOp<WITH_NORM, WITH_GTILDE, MOMENTUM> op(a, lds);
   drive_tiles(a.tm, op);
 }
 
@@ -836,11 +910,11 @@ hipError_t launch_int_sum(uint64_t d, const LaunchShape& ls, uint32_t n, int32_t
 hipError_t launch_decode_update(const TileMap& tm, const LaunchShape& ls, uint32_t n,
                                 const int32_t* sum, const float* alpha, double eta, float* x,
                                 float* gtilde_out) {
-  DecodeArgs a{tm, n, sum, alpha, eta, x, gtilde_out, Finish{}};
+  DecodeArgs a{tm, n, sum, alpha, eta, x, gtilde_out, nullptr, 0.0, 0.0, Finish{}};
   const dim3 grid(ls.grid), block(kThreads);
   Tapped tap(ls);
-  if (gtilde_out) hipLaunchKernelGGL((k_decode<false, true>), grid, block, 0, ls.stream, a);
-  else hipLaunchKernelGGL((k_decode<false, false>), grid, block, 0, ls.stream, a);
+  if (gtilde_out) hipLaunchKernelGGL((k_decode<false, true, false>), grid, block, 0, ls.stream, a);
+  else hipLaunchKernelGGL((k_decode<false, false, false>), grid, block, 0, ls.stream, a);
   return after_launch();
 }
 
@@ -859,14 +933,14 @@ hipError_t launch_update_norm(const TileMap& tm, const LaunchShape& ls, const fl
 hipError_t launch_compress_sum(const TileMap& tm, const LaunchShape& ls, uint32_t n,
                                const RoundSpec& rs, const WorkerPtrs& grads, const float* alpha,
                                int32_t* sum_out, const Finish& fin) {
-  AggregateArgs a{tm, rs, n, alpha, 0.0, nullptr, sum_out, fin, grads};
+  AggregateArgs a{tm, rs, n, alpha, 0.0, nullptr, sum_out, nullptr, 0.0, 0.0, fin, grads};
   const dim3 grid(ls.grid), block(kThreads);
   {
     Tapped tap(ls);
     if (rs.rounding == INTSGD_ROUND_STOCHASTIC)
-      hipLaunchKernelGGL((k_aggregate<1, false>), grid, block, ls.lds_reserve, ls.stream, a);
+      hipLaunchKernelGGL((k_aggregate<1, false, false>), grid, block, ls.lds_reserve, ls.stream, a);
     else
-      hipLaunchKernelGGL((k_aggregate<0, false>), grid, block, ls.lds_reserve, ls.stream, a);
+      hipLaunchKernelGGL((k_aggregate<0, false, false>), grid, block, ls.lds_reserve, ls.stream, a);
   }
   hipError_t e = after_launch();
   if (e != hipSuccess) return e;
@@ -875,11 +949,15 @@ hipError_t launch_compress_sum(const TileMap& tm, const LaunchShape& ls, uint32_
 
 hipError_t launch_decode_update_norm(const TileMap& tm, const LaunchShape& ls, uint32_t n,
                                      const int32_t* sum, const float* alpha, double eta, float* x,
-                                     const Finish& fin) {
-  DecodeArgs a{tm, n, sum, alpha, eta, x, nullptr, fin};
+                                     const Momentum* mom, const Finish& fin) {
+  DecodeArgs a{tm, n, sum, alpha, eta, x, nullptr, mom ? mom->m : nullptr, mom ? mom->mu : 0.0,
+               mom ? mom->wd : 0.0, fin};
   {
     Tapped tap(ls);
-    hipLaunchKernelGGL((k_decode<true, false>), dim3(ls.grid), dim3(kThreads), 0, ls.stream, a);
+    if (mom)
+      hipLaunchKernelGGL((k_decode<true, false, true>), dim3(ls.grid), dim3(kThreads), 0, ls.stream, a);
+    else
+      hipLaunchKernelGGL((k_decode<true, false, false>), dim3(ls.grid), dim3(kThreads), 0, ls.stream, a);
   }
   hipError_t e = after_launch();
   if (e != hipSuccess) return e;
@@ -888,15 +966,20 @@ hipError_t launch_decode_update_norm(const TileMap& tm, const LaunchShape& ls, u
 
 hipError_t launch_step_fused(const TileMap& tm, const LaunchShape& ls, uint32_t n,
                              const RoundSpec& rs, const WorkerPtrs& grads, const float* alpha,
-                             double eta, float* x, const Finish& fin) {
-  AggregateArgs a{tm, rs, n, alpha, eta, x, nullptr, fin, grads};
+                             double eta, float* x, const Momentum* mom, const Finish& fin) {
+  AggregateArgs a{tm, rs, n, alpha, eta, x, nullptr, mom ? mom->m : nullptr, mom ? mom->mu : 0.0,
+                  mom ? mom->wd : 0.0, fin, grads};
   const dim3 grid(ls.grid), block(kThreads);
+  const bool random = rs.rounding == INTSGD_ROUND_STOCHASTIC;
   {
     Tapped tap(ls);
-    if (rs.rounding == INTSGD_ROUND_STOCHASTIC)
-      hipLaunchKernelGGL((k_aggregate<1, true>), grid, block, ls.lds_reserve, ls.stream, a);
-    else
-      hipLaunchKernelGGL((k_aggregate<0, true>), grid, block, ls.lds_reserve, ls.stream, a);
+    if (mom) {
+      if (random) hipLaunchKernelGGL((k_aggregate<1, true, true>), grid, block, ls.lds_reserve, ls.stream, a);
+      else hipLaunchKernelGGL((k_aggregate<0, true, true>), grid, block, ls.lds_reserve, ls.stream, a);
+    } else {
+      if (random) hipLaunchKernelGGL((k_aggregate<1, true, false>), grid, block, ls.lds_reserve, ls.stream, a);
+      else hipLaunchKernelGGL((k_aggregate<0, true, false>), grid, block, ls.lds_reserve, ls.stream, a);
+    }
   }
   hipError_t e = after_launch();
   if (e != hipSuccess) return e;

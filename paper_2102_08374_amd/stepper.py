@@ -69,3 +69,10 @@ class Stepper:
         B.intsgd_update_norm(self.desc, x, x_old, self.norm_sq, self.workspace, stream)
         if chain_alpha:
             self.next_alpha(stream)
+
+    def step_momentum(self, grads, x, m, k, mu, weight_decay, stream=None, chain_alpha=True):
+        """The whole step with the momentum / weight-decay update (m: device fp32[d] state)."""
+        self.desc.step = k
+        B.intsgd_step_momentum(self.desc, grads, self.alpha, self.eta, mu, weight_decay, x, m,
+                               self.r if chain_alpha else None, self.beta, self.eps, self.norm_sq,
+                               self.sat_count, self.workspace, stream)

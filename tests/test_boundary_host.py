@@ -170,6 +170,26 @@ def test_whole_step_call_validation():
     assert f(*ok_args(desc=None)) == EINVAL
 
 
+def test_momentum_calls_validation():
+    desc = P.Desc(1000, 4)
+    need = P.intsgd_workspace_bytes(desc)
+    f = lib.intsgd_step_momentum
+    args = lambda **kw: [desc.ref(), ptrs(4), FAKE, kw.get("eta", 0.1), kw.get("mu", 0.9),
+                         kw.get("wd", 1e-4), kw.get("x", FAKE), kw.get("m", FAKE), kw.get("r", None),
+                         0.9, 1e-8, FAKE, FAKE, FAKE, need, None]
+    assert f(*args(m=None)) == EINVAL
+    assert f(*args(m=FAKE_ODD)) == EALIGN
+    for mu in (-0.1, 1.0, float("nan")):
+        assert f(*args(mu=mu)) == EINVAL
+    for wd in (-1e-4, float("inf"), float("nan")):
+        assert f(*args(wd=wd)) == EINVAL
+    assert f(*args(eta=0.0)) == EINVAL
+    g = lib.intsgd_decode_update_momentum
+    assert g(desc.ref(), FAKE, FAKE, 0.1, 0.9, 1e-4, FAKE, None, FAKE, FAKE, need, None) == EINVAL
+    assert g(desc.ref(), FAKE, FAKE, 0.1, 1.5, 1e-4, FAKE, FAKE, FAKE, FAKE, need, None) == EINVAL
+    assert g(desc.ref(), FAKE, FAKE, 0.1, 0.9, 1e-4, FAKE, FAKE, FAKE, None, need, None) == EWORKSPACE
+
+
 def test_status_strings():
     for st in (0, -1, -2, -3, -4, -5):
         assert P.intsgd_status_string(st) not in ("", "unknown status")

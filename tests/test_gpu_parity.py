@@ -465,3 +465,67 @@ def test_coordinates_beyond_32_bit_quad_index():
     assert abs(host(d_ns)[0] / expect - 1.0) < 0.05
     del g, x
     torch.cuda.empty_cache()
+
+
+# --------------------------------------------------------------------------- momentum form
+@pytest.mark.parametrize("rounding", [P.ROUND_NEAREST_EVEN, P.ROUND_STOCHASTIC])
+@pytest.mark.parametrize("shape", SHAPES[:4] + SHAPES[6:], ids=lambda s: "d%d-n%d" % (s[0], s[1]))
+def test_momentum_update_matches_oracle(shape, rounding):
+    """intsgd_step_momentum (one sweep) and intsgd_decode_update_momentum (on a given
+    aggregate): x and m within 1 fp32 ulp of the oracle, norms within 1e-5, same integers."""
+    d, n, offsets, tile = shape
+    P.intsgd_set_tuning(tile_coords=tile)
+    alpha, g, x = make_case(d, n, offsets, seed=3 * d + rounding)
+    B = alpha.size
+    rng = np.random.default_rng(d)
+    m = rng.normal(0, 0.01, d).astype(F32)
+    eta, mu, wd, L, seed, step = 0.1, 0.9, 1e-4, P.default_clip(n), 99, 4
+    off_np = None if offsets is None else np.array(offsets, np.uint64)
+    out = oracle.step_momentum(list(g), alpha, x, m, rounding=rounding, L=L, eta=eta, mu=mu, wd=wd,
+                               seed=seed, step=step, offsets=off_np)
+    desc = P.Desc(d, n, rounding=rounding, clip=L, seed=seed, step=step, block_offsets=offsets)
+    ws = P.new_workspace(desc, DEV)
+    rows = rows_on_device(g)
+    d_x, d_m, d_a = dev(x), dev(m), dev(alpha)
+    d_ns = torch.zeros(B, dtype=torch.float64, device=DEV)
+    d_cnt = torch.zeros(n, dtype=torch.int64, device=DEV)
+    P.intsgd_step_momentum(desc, rows, d_a, eta, mu, wd, d_x, d_m, None, 0.0, 0.0, d_ns, d_cnt, ws)
+    assert_within_ulp(host(d_x), out["x_new"], 1, "x")
+    assert_within_ulp(host(d_m), out["m_new"], 1, "m")
+    assert u64(d_cnt).tolist() == out["sat_count"].tolist()
+    assert rel_err(host(d_ns), out["normsq"]) <= NORM_RTOL
+    assert np.array_equal(host(d_a), alpha)                  # r == NULL: alpha untouched
+    # two-pass form on the aggregate
+    d_S = torch.zeros(d, dtype=torch.int32, device=DEV)
+    P.intsgd_compress_sum(desc, rows, d_a, d_S, d_cnt, ws)
+    assert np.array_equal(host(d_S), out["S"])
+    d_x2, d_m2 = dev(x), dev(m)
+    d_ns2 = torch.zeros(B, dtype=torch.float64, device=DEV)
+    P.intsgd_decode_update_momentum(desc, d_S, d_a, eta, mu, wd, d_x2, d_m2, d_ns2, ws)
+    assert torch.equal(d_x2, d_x) and torch.equal(d_m2, d_m)
+    assert rel_err(host(d_ns2), host(d_ns)) <= 1e-12
+
+
+def test_momentum_multi_step_with_alpha_rule():
+    """Ten chained steps (momentum 0.9, weight decay 1e-4, alpha recomputed each step from a
+    norm that now contains the momentum term), replayed in the oracle with the GPU's alpha."""
+    w = W.config(2).scaled(300_001)
+    mu, wd = 0.9, 1e-4
+    desc = P.Desc(w.d, w.n, rounding=P.ROUND_STOCHASTIC, clip=w.clip, seed=11)
+    st = Stepper(desc, eta=w.eta, beta=w.beta, eps=w.eps, device=DEV)
+    st.start(w.first_normsq)
+    x = W.make_params(w, DEV)
+    m = torch.zeros_like(x)
+    r_or = np.zeros(1)
+    r_or, _, _, _ = oracle.next_alpha(w.first_normsq, r_or, d=w.d, n=w.n, beta=w.beta, eps=w.eps, eta=w.eta)
+    for k in range(1, 11):
+        _, rows = W.make_gradients(w, k, DEV)
+        a_gpu, x_old, m_old = host(st.alpha).copy(), host(x).copy(), host(m).copy()
+        st.step_momentum(rows, x, m, k, mu, wd)
+        out = oracle.step_momentum([host(r_) for r_ in rows], a_gpu, x_old, m_old, rounding=1,
+                                   L=w.clip, eta=w.eta, mu=mu, wd=wd, seed=11, step=k)
+        assert_within_ulp(host(x), out["x_new"], 1, "x at step %d" % k)
+        assert_within_ulp(host(m), out["m_new"], 1, "m at step %d" % k)
+        assert rel_err(host(st.norm_sq), out["normsq"]) <= NORM_RTOL
+        r_or, ad, _, _ = oracle.next_alpha(out["normsq"], r_or, d=w.d, n=w.n, beta=w.beta, eps=w.eps, eta=w.eta)
+        assert rel_err(host(st.alpha), ad) <= ALPHA_RTOL
