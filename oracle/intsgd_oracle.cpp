@@ -257,6 +257,79 @@ uint64_t oracle_step(const float* const* grads, uint32_t n, uint64_t j0, uint64_
   return overflow;
 }
 
+// IntDIANA (Appendix A.2, Algorithm 3), worker side, for one worker on a slice: the
+// worker compresses the DIFFERENCE to its local shift, Q_i = Int(alpha (g_i - h_i))
+// (clipped like every integer message), and moves the shift by the decoded message,
+// h_i <- h_i + Q_i / alpha.  (The algorithm box writes h_i + Q(g_i); its proofs use
+// g = (1/n) sum (h_i + Q(g_i)), so Q there carries the 1/alpha of eq. (Q).)
+// fp32: delta = g - h_i, t = alpha delta.  fp64: h_i + q (1/alpha), stored fp32.
+uint64_t oracle_diana_compress(const float* g, const float* h_local, uint64_t j0, uint64_t len,
+                               const float* alpha, const uint64_t* offsets, uint32_t B,
+                               int rounding, int32_t L, uint64_t seed, uint32_t step,
+                               uint32_t worker, int32_t* q, float* h_local_new) {
+  uint64_t count = 0;
+  for (uint64_t t_ = 0; t_ < len; ++t_) {
+    const uint64_t j = j0 + t_;
+    const float a = alpha[block_of(j, offsets, B)];
+    const float delta = g[t_] - h_local[t_];
+    const float t = a * delta;
+    float r;
+    if (rounding == 1) {
+      r = oracle_int_random(t, oracle_random_word(seed, step, worker, j));
+    } else {
+      r = oracle_int_nearest(t);
+    }
+    int clipped;
+    q[t_] = oracle_saturate(r, L, &clipped);
+    count += (uint64_t)clipped;
+    const double inv = 1.0 / (double)a;
+    const double moved = (double)q[t_] * inv;
+    h_local_new[t_] = (float)((double)h_local[t_] + moved);
+  }
+  return count;
+}
+
+// IntDIANA, after aggregation: g~ = h + S/(n alpha), x <- x - eta g~, h <- h + S/(n alpha)
+// (Algorithm 3, estimator / update / global-shift lines).  fp64, each operation
+// rounded on its own, x and h stored fp32.
+void oracle_diana_update(const int32_t* sum, uint64_t j0, uint64_t len, const float* alpha,
+                         const uint64_t* offsets, uint32_t B, uint32_t n, double eta,
+                         const float* x, const float* h, float* x_new, float* h_new) {
+  for (uint64_t t_ = 0; t_ < len; ++t_) {
+    const uint64_t j = j0 + t_;
+    const double a = (double)alpha[block_of(j, offsets, B)];
+    const double cg = 1.0 / ((double)n * a);
+    const double ghat = cg * (double)sum[t_];
+    const double gt = (double)h[t_] + ghat;
+    const double stepv = eta * gt;
+    x_new[t_] = (float)((double)x[t_] - stepv);
+    h_new[t_] = (float)gt;
+  }
+}
+
+// One whole IntDIANA step on a slice.  h_local / h_local_new: n pointers to len floats.
+uint64_t oracle_diana_step(const float* const* grads, const float* const* h_local, uint32_t n,
+                           uint64_t j0, uint64_t len, const float* alpha, const uint64_t* offsets,
+                           uint32_t B, int rounding, int32_t L, uint64_t seed, uint32_t step,
+                           double eta, const float* x, const float* h, float* x_new, float* h_new,
+                           float* const* h_local_new, int32_t* sum_out, uint64_t* sat_count,
+                           double* normsq) {
+  std::vector<std::vector<int32_t>> q(n, std::vector<int32_t>(len));
+  std::vector<const int32_t*> qp(n);
+  for (uint32_t i = 0; i < n; ++i) {
+    sat_count[i] = oracle_diana_compress(grads[i], h_local[i], j0, len, alpha, offsets, B,
+                                         rounding, L, seed, step, i, q[i].data(), h_local_new[i]);
+    qp[i] = q[i].data();
+  }
+  std::vector<int32_t> local_sum;
+  int32_t* s = sum_out;
+  if (!s) { local_sum.resize(len); s = local_sum.data(); }
+  const uint64_t overflow = oracle_int_sum(qp.data(), n, len, s);
+  oracle_diana_update(s, j0, len, alpha, offsets, B, n, eta, x, h, x_new, h_new);
+  oracle_update_norm(x_new, x, j0, len, offsets, B, normsq);
+  return overflow;
+}
+
 // oracle_step with the momentum / weight-decay update in place of the plain one.
 uint64_t oracle_step_momentum(const float* const* grads, uint32_t n, uint64_t j0, uint64_t len,
                               const float* alpha, const uint64_t* offsets, uint32_t B,

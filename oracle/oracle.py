@@ -14,7 +14,7 @@ from . import build as _build
 __all__ = [
     "philox4x32_10", "random_word", "int_random", "int_nearest", "saturate", "compress",
     "int_sum", "decode_update", "update_norm", "next_alpha", "step", "decode_update_momentum",
-    "step_momentum",
+    "step_momentum", "diana_compress", "diana_update", "diana_step",
     "ROUND_NEAREST_EVEN", "ROUND_STOCHASTIC",
 ]
 
@@ -56,6 +56,18 @@ _lib.oracle_step_momentum.argtypes = [C.POINTER(_f32p), C.c_uint32, C.c_uint64, 
                                       C.c_double, C.c_double, C.c_double, _f32p, _f32p, _f32p, _f32p,
                                       _i32p, _u64p, _f64p]
 _lib.oracle_step_momentum.restype = C.c_uint64
+_lib.oracle_diana_compress.argtypes = [_f32p, _f32p, C.c_uint64, C.c_uint64, _f32p, _u64p, C.c_uint32,
+                                       C.c_int, C.c_int32, C.c_uint64, C.c_uint32, C.c_uint32,
+                                       _i32p, _f32p]
+_lib.oracle_diana_compress.restype = C.c_uint64
+_lib.oracle_diana_update.argtypes = [_i32p, C.c_uint64, C.c_uint64, _f32p, _u64p, C.c_uint32,
+                                     C.c_uint32, C.c_double, _f32p, _f32p, _f32p, _f32p]
+_lib.oracle_diana_update.restype = None
+_lib.oracle_diana_step.argtypes = [C.POINTER(_f32p), C.POINTER(_f32p), C.c_uint32, C.c_uint64,
+                                   C.c_uint64, _f32p, _u64p, C.c_uint32, C.c_int, C.c_int32,
+                                   C.c_uint64, C.c_uint32, C.c_double, _f32p, _f32p, _f32p, _f32p,
+                                   C.POINTER(_f32p), _i32p, _u64p, _f64p]
+_lib.oracle_diana_step.restype = C.c_uint64
 _lib.oracle_update_norm.argtypes = [_f32p, _f32p, C.c_uint64, C.c_uint64, _u64p, C.c_uint32,
                                     _f64p]
 _lib.oracle_update_norm.restype = None
@@ -247,3 +259,62 @@ def step_momentum(grads, alpha, x, m, *, rounding, L, eta, mu, wd, seed=0, step=
                                     _ptr(mn, C.c_float), _ptr(S, C.c_int32), _ptr(sat, C.c_uint64),
                                     _ptr(ns, C.c_double))
     return dict(x_new=xn, m_new=mn, S=S, sat_count=sat, normsq=ns, overflow=int(ovf))
+
+
+def diana_compress(g, h_local, alpha, *, rounding, L, seed=0, step=0, worker=0, j0=0, offsets=None):
+    """IntDIANA worker side -> (q int32[len], h_local_new, clip count)."""
+    g = _arr(g, np.float32)
+    hl = _arr(h_local, np.float32)
+    assert g.size == hl.size
+    a, ap = _alpha(alpha)
+    off, offp = _offsets(offsets, a.size)
+    q = np.empty(g.size, np.int32)
+    hn = np.empty_like(hl)
+    cnt = _lib.oracle_diana_compress(_ptr(g, C.c_float), _ptr(hl, C.c_float), int(j0), g.size, ap,
+                                     offp, a.size, int(rounding), int(L), int(seed), int(step),
+                                     int(worker), _ptr(q, C.c_int32), _ptr(hn, C.c_float))
+    return q, hn, int(cnt)
+
+
+def diana_update(S, alpha, x, h, *, n, eta, j0=0, offsets=None):
+    """IntDIANA after aggregation -> (x_new, h_new)."""
+    S = _arr(S, np.int32)
+    x = _arr(x, np.float32)
+    h = _arr(h, np.float32)
+    a, ap = _alpha(alpha)
+    off, offp = _offsets(offsets, a.size)
+    xn = np.empty_like(x)
+    hn = np.empty_like(h)
+    _lib.oracle_diana_update(_ptr(S, C.c_int32), int(j0), S.size, ap, offp, a.size, int(n),
+                             float(eta), _ptr(x, C.c_float), _ptr(h, C.c_float),
+                             _ptr(xn, C.c_float), _ptr(hn, C.c_float))
+    return xn, hn
+
+
+def diana_step(grads, h_local, alpha, x, h, *, rounding, L, eta, seed=0, step=0, j0=0,
+               offsets=None, normsq=None):
+    """One whole IntDIANA step on a slice."""
+    gs = [_arr(g, np.float32) for g in grads]
+    hs = [_arr(v, np.float32) for v in h_local]
+    n, ln = len(gs), gs[0].size
+    assert len(hs) == n and all(v.size == ln for v in gs + hs)
+    x = _arr(x, np.float32)
+    h = _arr(h, np.float32)
+    a, ap = _alpha(alpha)
+    B = a.size
+    off, offp = _offsets(offsets, B)
+    gp = (_f32p * n)(*[_ptr(g, C.c_float) for g in gs])
+    hp = (_f32p * n)(*[_ptr(v, C.c_float) for v in hs])
+    hn_local = [np.empty(ln, np.float32) for _ in range(n)]
+    hnp = (_f32p * n)(*[_ptr(v, C.c_float) for v in hn_local])
+    xn = np.empty_like(x)
+    hn = np.empty_like(h)
+    S = np.empty(ln, np.int32)
+    sat = np.zeros(n, np.uint64)
+    ns = np.zeros(B, np.float64) if normsq is None else normsq
+    ovf = _lib.oracle_diana_step(gp, hp, n, int(j0), ln, ap, offp, B, int(rounding), int(L),
+                                 int(seed), int(step), float(eta), _ptr(x, C.c_float),
+                                 _ptr(h, C.c_float), _ptr(xn, C.c_float), _ptr(hn, C.c_float), hnp,
+                                 _ptr(S, C.c_int32), _ptr(sat, C.c_uint64), _ptr(ns, C.c_double))
+    return dict(x_new=xn, h_new=hn, h_local_new=hn_local, S=S, sat_count=sat, normsq=ns,
+                overflow=int(ovf))

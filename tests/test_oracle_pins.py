@@ -477,3 +477,100 @@ def test_step_momentum_composes():
     assert np.array_equal(xn, mom["x_new"]) and np.array_equal(mn, mom["m_new"])
     nrm = float(((xn.astype(np.float64) - x.astype(np.float64)) ** 2).sum())
     assert math.isclose(mom["normsq"][0], nrm, rel_tol=1e-13)
+
+
+# ----------------------------------------------------------------------------- IntDIANA (Algorithm 3)
+def test_diana_lines_in_rationals():
+    """Every stored value of one IntDIANA step is the correctly rounded rational value of
+    its line of Algorithm 3; zero shifts reproduce IntSGD's integers and (to 1 ulp) its x."""
+    rng = np.random.default_rng(43)
+    n, d = 3, 16
+    alpha = F32(411.75)
+    eta = 0.1
+    g = rng.normal(0, 0.02, (n, d)).astype(F32)
+    hl = rng.normal(0, 0.02, (n, d)).astype(F32)
+    x = rng.normal(0, 1, d).astype(F32)
+    h = hl.astype(np.float64).mean(0).astype(F32)
+    kw = dict(rounding=1, L=10**6, seed=21, step=6)
+    out = oracle.diana_step(list(g), list(hl), alpha, x, h, eta=eta, **kw)
+    a = Fraction(float(alpha))
+    half = Fraction(501, 1000)
+    S = [0] * d
+    for i in range(n):
+        for j in range(d):
+            delta = F32(g[i, j]) - F32(hl[i, j])
+            t = pyref.scale(alpha, delta)
+            q = pyref.int_random_exact(t, pyref.random_word(21, 6, i, j))
+            S[j] += q
+            H = Fraction(float(hl[i, j])) + Fraction(q) / a
+            got = Fraction(float(out["h_local_new"][i][j]))
+            assert abs(got - H) <= Fraction(pyref.ulp32(H)) * half + Fraction(1, 10**12)
+    assert out["S"].tolist() == S
+    for j in range(d):
+        G = Fraction(float(h[j])) + Fraction(S[j]) / (n * a)
+        assert abs(Fraction(float(out["h_new"][j])) - G) <= Fraction(pyref.ulp32(G)) * half
+        X = Fraction(float(x[j])) - Fraction(eta) * G
+        assert abs(Fraction(float(out["x_new"][j])) - X) <= Fraction(pyref.ulp32(X)) * half
+    zero = [np.zeros(d, F32)] * n
+    o0 = oracle.diana_step(list(g), zero, alpha, x, np.zeros(d, F32), eta=eta, **kw)
+    p0 = oracle.step(list(g), alpha, x, eta=eta, **kw)
+    assert np.array_equal(o0["S"], p0["S"])
+    assert np.all(np.abs(o0["x_new"].astype(np.float64) - p0["x_new"].astype(np.float64))
+                  <= np.spacing(np.abs(p0["x_new"])).astype(np.float64))
+
+
+def test_diana_global_shift_is_mean_of_local_shifts():
+    """Algorithm 3 keeps h = (1/n) sum_i h_i (both start at 0 and move by the same decoded
+    messages); in fp32 storage the identity holds to rounding over many steps."""
+    rng = np.random.default_rng(47)
+    n, d, eta = 4, 200, 0.2
+    b = rng.normal(0, 1, (n, d))
+    x = rng.normal(0, 1, d).astype(F32)
+    hl = [np.zeros(d, F32) for _ in range(n)]
+    h = np.zeros(d, F32)
+    alpha = F32(50.0)
+    for k in range(1, 40):
+        g = [(x.astype(np.float64) - b[i]).astype(F32) for i in range(n)]
+        out = oracle.diana_step(g, hl, alpha, x, h, rounding=1, L=10**6, eta=eta, seed=1, step=k)
+        x, h, hl = out["x_new"], out["h_new"], out["h_local_new"]
+        mean = np.mean([v.astype(np.float64) for v in hl], axis=0)
+        scale = np.max(np.abs(np.array(hl + [h])), axis=0).astype(F32)      # rounding happens at |h_i|
+        assert np.all(np.abs(h - mean) <= 40 * np.spacing(scale + F32(1e-3)))
+
+
+def test_diana_keeps_integers_small_where_intsgd_does_not():
+    """Appendix A.2: with heterogeneous workers and exact gradients, IntSGD's integers grow
+    like |grad f_i(x*)| / ||x^k - x^{k-1}|| while IntDIANA's stay bounded, and IntDIANA's
+    iterates converge linearly.  f_i(x) = 0.5 ||x - b_i||^2, adaptive alpha with beta = 0."""
+    rng = np.random.default_rng(53)
+    n, d, eta = 4, 64, 0.25
+    b = rng.normal(0, 1, (n, d))
+    xstar = b.mean(0)
+    def run(diana):
+        x = np.zeros(d, F32)
+        hl = [np.zeros(d, F32) for _ in range(n)]
+        h = np.zeros(d, F32)
+        nrm = float(eta**2 * ((x - xstar) ** 2).sum())       # exact first step
+        x = (x.astype(np.float64) - eta * (x - xstar)).astype(F32)
+        maxint, dist = [], []
+        for k in range(1, 45):
+            _, ad, af, bad = oracle.next_alpha([nrm], [0.0], d=d, n=n, beta=0.0, eps=1e-12, eta=eta)
+            g = [(x.astype(np.float64) - b[i]).astype(F32) for i in range(n)]
+            kw = dict(rounding=1, L=2**31 - 1 >> 2, seed=3, step=k)
+            if diana:
+                sent = [oracle.diana_compress(g[i], hl[i], af, worker=i, **kw)[0] for i in range(n)]
+                out = oracle.diana_step(g, hl, af, x, h, eta=eta, **kw)
+                h, hl = out["h_new"], out["h_local_new"]
+            else:
+                sent = [oracle.compress(g[i], af, worker=i, **kw)[0] for i in range(n)]
+                out = oracle.step(g, af, x, eta=eta, **kw)
+            assert np.array_equal(np.sum(sent, axis=0), out["S"])
+            maxint.append(int(np.abs(np.array(sent)).max()))    # largest integer a worker transmits
+            x, nrm = out["x_new"], max(float(out["normsq"][0]), 1e-300)
+            dist.append(float(np.linalg.norm(x - xstar)))
+        return maxint, dist
+    mi_sgd, _ = run(False)
+    mi_dia, dist = run(True)
+    assert max(mi_dia[10:]) <= 64                      # a few bits per coordinate
+    assert max(mi_sgd[25:]) > 50 * max(mi_dia[25:])    # IntSGD's messages blow up
+    assert dist[30] < 1e-3 * dist[0]                   # linear convergence of IntDIANA
