@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--no-taps", action="store_true",
                     help="do not record per-kernel events (roofline numbers are then null)")
     ap.add_argument("--global-alpha", action="store_true", help="config 4 with one alpha")
+    ap.add_argument("--diana", action="store_true",
+                    help="IntDIANA step (Algorithm 3): n local shifts + a global shift in HBM")
     ap.add_argument("--momentum", action="store_true",
                     help="momentum 0.9 / weight decay 1e-4 form of the update (fused mode)")
     return ap.parse_args()
@@ -152,11 +154,19 @@ def main():
         sets.append((buf, rows))
     sum_buf = torch.empty(w.d, dtype=torch.int32, device=dev) if args.mode == "two_pass" else None
     mom = torch.zeros_like(x) if args.momentum else None
+    if args.diana:
+        hbuf = torch.zeros((w.n, W.row_stride(w.d)), dtype=torch.float32, device=dev)
+        h_local = [hbuf[i, :w.d] for i in range(w.n)]
+        h_global = torch.zeros_like(x)
     torch.cuda.synchronize()
 
     def one_step(k):
         rows = sets[(k - 1) % pool][1]
-        if args.momentum:
+        if args.diana:
+            desc.step = k
+            P.intsgd_diana_step(desc, rows, h_local, st.alpha, st.eta, x, h_global, st.r, st.beta,
+                                st.eps, st.norm_sq, st.sat_count, st.workspace)
+        elif args.momentum:
             st.step_momentum(rows, x, mom, k, 0.9, 1e-4)  # a1-a8 with the momentum update
         elif args.mode == "fused":
             st.step_fused(rows, x, k)                    # a1-a8, one call
@@ -192,6 +202,8 @@ def main():
     per_coord = (4 * w.n + 8) if args.mode == "fused" else (4 * w.n + 4)
     if args.momentum:
         per_coord = 4 * w.n + 16
+    if args.diana:
+        per_coord = 12 * w.n + 16
     algo_bytes = per_coord * w.d
     achieved = algo_bytes / (avg_kernel_ms * 1e-3) / 1e9
     sat = int(st.sat_count.cpu().numpy().view("uint64").sum())
@@ -214,7 +226,8 @@ def main():
             "workload": w.name, "d": w.d, "n_workers": w.n, "blocks": w.num_blocks,
             "rounding": "stochastic" if w.rounding else "nearest-even", "wire": "int%d" % w.wire,
             "clip": w.clip, "grad_dist": w.grad_kind,
-            "mode": args.mode + ("+momentum" if args.momentum else ""), "gradient_sets": pool,
+            "mode": "diana" if args.diana else args.mode + ("+momentum" if args.momentum else ""),
+            "gradient_sets": pool,
             "tuning_overrides": {"tile_coords": tile, "max_workgroups": grid,
                                  "workgroups_per_cu": wgs_per_cu},
             "alpha_last": alpha_last,
@@ -223,7 +236,7 @@ def main():
         "roofline": {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": None if args.momentum else load_traffic(w.name, args.mode),
+            "traffic": None if (args.momentum or args.diana) else load_traffic(w.name, args.mode),
             "kernel": "k_aggregate<ROUND, FUSED=true>: a1-a7 in one sweep" if args.mode == "fused"
                       else "k_aggregate<ROUND, FUSED=false>: a1-a4 (first of the two sweeps)",
             "algorithmic_bytes_per_launch": algo_bytes,
@@ -231,7 +244,7 @@ def main():
             "kernel_ms_median": kernel_ms[len(kernel_ms) // 2],
         },
     }
-    if not args.no_cpu_baseline and not args.momentum:
+    if not args.no_cpu_baseline and not args.momentum and not args.diana:
         result["cpu_baseline"] = cpu_baseline(w, sets[0][1], alpha0, x0)
     print(json.dumps(result))
 

@@ -236,6 +236,28 @@ intsgd_status intsgd_step_momentum(const intsgd_desc* desc, const float* const* 
                                    double* norm_sq_out, uint64_t* sat_count, void* workspace,
                                    size_t workspace_bytes, void* hip_stream);
 
+/*
+ * IntDIANA (Appendix A.2, Algorithm 3) in one sweep, for heterogeneous workers: every
+ * worker compresses the difference to its local shift and moves the shift by the decoded
+ * message; the aggregate is decoded on top of the global shift.
+ *   Q_i = Int(alpha (g_i - h_i)) clipped to [-L, L] (counted in sat_count[i]),
+ *   h_i <- fl32(h_i + Q_i (1/alpha)),   S = sum_i Q_i,
+ *   g~ = h + S (1/(n alpha)),   x <- fl32(x - eta g~),   h <- fl32(g~).
+ * fp32 for the difference and the scale, fp64 with every operation rounded on its own for
+ * the rest.  (The algorithm box writes h_i + Q(g_i); its analysis uses g = (1/n) sum (h_i +
+ * Q(g_i)), i.e. Q carries the 1/alpha there.)
+ *   grads    HOST array of n DEVICE pointers (d floats each, read only)
+ *   h_local  HOST array of n DEVICE pointers (d floats each, in/out), 16-byte aligned
+ *   h        DEVICE float[d], global shift, in/out;  x DEVICE float[d], in/out
+ *   r        DEVICE double[B] or NULL.  Not NULL: a8 is applied afterwards (alpha in/out) with
+ *            the given beta, eps; Algorithm 3's own rule is beta = 0, eps = 0.
+ */
+intsgd_status intsgd_diana_step(const intsgd_desc* desc, const float* const* grads,
+                                float* const* h_local, float* alpha, double eta, float* x,
+                                float* h, double* r, double beta, double eps, double* norm_sq_out,
+                                uint64_t* sat_count, void* workspace, size_t workspace_bytes,
+                                void* hip_stream);
+
 /* Tuning overrides (process-wide; not part of the numerical contract: results do not
  * depend on them except for the summation order of the norm).  A field that is 0
  * means "automatic": the library picks per call (by rounding mode) what measured best

@@ -16,7 +16,7 @@ __all__ = [
     "intsgd_release", "intsgd_compress", "intsgd_int_sum", "intsgd_decode_update",
     "intsgd_update_norm", "intsgd_next_alpha", "intsgd_next_alpha_host", "intsgd_compress_sum",
     "intsgd_decode_update_norm", "intsgd_step_fused", "intsgd_step_fused_next_alpha",
-    "intsgd_decode_update_momentum", "intsgd_step_momentum",
+    "intsgd_decode_update_momentum", "intsgd_step_momentum", "intsgd_diana_step",
     "intsgd_tap_next_launch", "intsgd_set_tuning", "intsgd_get_tuning", "intsgd_status_string",
     "new_workspace", "EXPORTED_SYMBOLS",
 ]
@@ -30,7 +30,7 @@ MAX_WORKERS = 128
 EXPORTED_SYMBOLS = [
     "intsgd_workspace_bytes", "intsgd_tap_next_launch", "intsgd_prepare", "intsgd_release",
     "intsgd_compress", "intsgd_step_fused_next_alpha", "intsgd_decode_update_momentum",
-    "intsgd_step_momentum",
+    "intsgd_step_momentum", "intsgd_diana_step",
     "intsgd_int_sum", "intsgd_decode_update", "intsgd_update_norm", "intsgd_next_alpha",
     "intsgd_next_alpha_host", "intsgd_compress_sum", "intsgd_decode_update_norm",
     "intsgd_step_fused", "intsgd_set_tuning", "intsgd_get_tuning", "intsgd_status_string",
@@ -89,6 +89,8 @@ _lib.intsgd_step_fused_next_alpha.argtypes = [_DP, _PP, _P, C.c_double, _P, _P, 
 _lib.intsgd_tap_next_launch.argtypes = [_P, _P]
 _lib.intsgd_decode_update_momentum.argtypes = [_DP, _P, _P, C.c_double, C.c_double, C.c_double, _P,
                                                _P, _P, _P, C.c_size_t, _P]
+_lib.intsgd_diana_step.argtypes = [_DP, _PP, _PP, _P, C.c_double, _P, _P, _P, C.c_double, C.c_double,
+                                   _P, _P, _P, C.c_size_t, _P]
 _lib.intsgd_step_momentum.argtypes = [_DP, _PP, _P, C.c_double, C.c_double, C.c_double, _P, _P, _P,
                                       C.c_double, C.c_double, _P, _P, _P, C.c_size_t, _P]
 _lib.intsgd_set_tuning.argtypes = [C.POINTER(_CTuning)]
@@ -102,7 +104,7 @@ for _name in ("intsgd_prepare", "intsgd_compress", "intsgd_int_sum", "intsgd_dec
               "intsgd_update_norm", "intsgd_next_alpha", "intsgd_next_alpha_host",
               "intsgd_compress_sum", "intsgd_decode_update_norm", "intsgd_step_fused",
               "intsgd_step_fused_next_alpha", "intsgd_tap_next_launch", "intsgd_set_tuning",
-              "intsgd_decode_update_momentum", "intsgd_step_momentum"):
+              "intsgd_decode_update_momentum", "intsgd_step_momentum", "intsgd_diana_step"):
     getattr(_lib, _name).restype = C.c_int
 
 
@@ -368,6 +370,24 @@ def intsgd_step_momentum(desc, grads, alpha, eta, mu, weight_decay, x, m, r, bet
                                      float(mu), float(weight_decay), _ptr(x), _ptr(m), _ptr(r),
                                      float(beta), float(eps), _ptr(norm_sq_out), _ptr(sat_count),
                                      w, wb, _stream(stream)), "intsgd_step_momentum")
+
+
+def intsgd_diana_step(desc, grads, h_local, alpha, eta, x, h, r, beta, eps, norm_sq_out, sat_count,
+                      workspace, stream=None):
+    """IntDIANA step; r may be None (alpha only read)."""
+    _need_rows(desc, grads, torch.float32, "grads")
+    _need_rows(desc, h_local, torch.float32, "h_local")
+    _need(alpha, desc.num_blocks, torch.float32, "alpha")
+    _need(x, desc.d, torch.float32, "x")
+    _need(h, desc.d, torch.float32, "h")
+    _need(r, desc.num_blocks, torch.float64, "r")
+    _need(norm_sq_out, desc.num_blocks, torch.float64, "norm_sq_out")
+    _need(sat_count, desc.n, torch.int64, "sat_count")
+    w, wb = _ws(workspace)
+    _check(_lib.intsgd_diana_step(desc.ref(), _ptr_array(grads), _ptr_array(h_local), _ptr(alpha),
+                                  float(eta), _ptr(x), _ptr(h), _ptr(r), float(beta), float(eps),
+                                  _ptr(norm_sq_out), _ptr(sat_count), w, wb, _stream(stream)),
+           "intsgd_diana_step")
 
 
 def intsgd_set_tuning(tile_coords=0, max_workgroups=0, workgroups_per_cu=0):

@@ -556,6 +556,31 @@ intsgd_status intsgd_step_fused_next_alpha(const intsgd_desc* desc, const float*
                          workspace_bytes, hip_stream, r, alpha, beta, eps);
 }
 
+intsgd_status intsgd_diana_step(const intsgd_desc* desc, const float* const* grads,
+                                float* const* h_local, float* alpha, double eta, float* x,
+                                float* h, double* r, double beta, double eps, double* norm_sq_out,
+                                uint64_t* sat_count, void* workspace, size_t workspace_bytes,
+                                void* hip_stream) {
+  INTSGD_TRY(validate_desc(desc));
+  INTSGD_TRY(validate_worker_ptrs((const void* const*)grads, desc->n));
+  INTSGD_TRY(validate_worker_ptrs((const void* const*)h_local, desc->n));
+  INTSGD_TRY(validate_vec(x));
+  INTSGD_TRY(validate_vec(h));
+  if (alpha == nullptr || norm_sq_out == nullptr || sat_count == nullptr) return INTSGD_EINVAL;
+  INTSGD_TRY(validate_rule(r ? beta : 0.0, r ? eps : 0.0, eta));
+  INTSGD_TRY(validate_workspace(desc, workspace, workspace_bytes));
+  Tiling t;
+  INTSGD_TRY(make_tiling(desc, hip_stream, &t));
+  WorkerPtrs g;
+  WorkerOutPtrs hl;
+  fill_ptrs(&g, (const void* const*)grads, desc->n);
+  std::memset(&hl, 0, sizeof(hl));
+  for (uint32_t i = 0; i < desc->n; ++i) hl.p[i] = h_local[i];
+  Finish fin = make_finish(desc, t, workspace, norm_sq_out, sat_count);
+  if (r != nullptr) fin.rule = AlphaRule{r, alpha, t.offsets_dev, beta, eps, eta};
+  return done(launch_diana_step(t.tm, t.ls, desc->n, round_spec(desc), g, hl, alpha, eta, x, h, fin));
+}
+
 intsgd_status intsgd_set_tuning(const intsgd_tuning* tuning) {
   if (tuning == nullptr) return INTSGD_EINVAL;
   const uint32_t tile = tuning->tile_coords, grid = tuning->max_workgroups,

@@ -106,6 +106,10 @@ hipError_t launch_decode_update_norm(const TileMap& tm, const LaunchShape& ls, u
 hipError_t launch_step_fused(const TileMap& tm, const LaunchShape& ls, uint32_t n,
                              const RoundSpec& rs, const WorkerPtrs& grads, const float* alpha,
                              double eta, float* x, const Momentum* mom, const Finish& fin);
+hipError_t launch_diana_step(const TileMap& tm, const LaunchShape& ls, uint32_t n,
+                             const RoundSpec& rs, const WorkerPtrs& grads,
+                             const WorkerOutPtrs& h_local, const float* alpha, double eta, float* x,
+                             float* h, const Finish& fin);
 hipError_t launch_next_alpha(hipStream_t stream, const double* norm_sq, const AlphaRule& rule,
                              uint32_t B, uint32_t n, uint64_t d);
 

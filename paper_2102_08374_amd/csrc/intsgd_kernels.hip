@@ -590,6 +590,154 @@ __global__ __launch_bounds__(kThreads) void k_aggregate(const AggregateArgs a) {
   if (threadIdx.x == 0) publish_sat(a.fin, lds, blockIdx.x);
 }
 
+// ================================================================== IntDIANA (Algorithm 3) in one sweep
+// Per worker: Q_i = Int(alpha (g_i - h_i)) clipped, h_i <- h_i + Q_i / alpha; then
+// g~ = h + S/(n alpha), x <- x - eta g~, h <- g~.  fp32 for the difference and the
+// scale, fp64 (each operation rounded on its own) for the shifts and the update.
+struct DianaArgs {
+  TileMap tm;
+  RoundSpec rs;
+  uint32_t n;
+  const float* alpha;
+  double eta;
+  float* x;
+  float* h;              // global shift, in/out
+  Finish fin;
+  WorkerPtrs grads;
+  WorkerOutPtrs h_local; // n local shifts, in/out
+};
+
+__device__ __forceinline__ float shift_local(float h, int32_t q, double inv_alpha) {
+  const double moved = (double)q * inv_alpha;
+  return (float)((double)h + moved);
+}
+
+__device__ __forceinline__ float diana_coord(float x, float& h, int32_t S, double cg, double eta,
+                                             double& acc) {
+  const double xo = (double)x;
+  const double ghat = cg * (double)S;
+  const double gt = (double)h + ghat;
+  const double stepv = eta * gt;
+  const float xn = (float)(xo - stepv);
+  h = (float)gt;
+  const double delta = (double)xn - xo;
+  acc = __builtin_fma(delta, delta, acc);
+  return xn;
+}
+
+template <int ROUND>
+struct DianaOp {
+  const DianaArgs& a;
+  ReduceLds& lds;
+  float alpha;
+  double inv_alpha, cg, acc;
+  uint64_t q0;
+  uint32_t nq;
+  __amdgpu_buffer_rsrc_t x_s, h_s;
+
+  __device__ __forceinline__ DianaOp(const DianaArgs& args, ReduceLds& l)
+      : a(args), lds(l), alpha(0.f), inv_alpha(0.0), cg(0.0), acc(0.0), q0(0), nq(0) {}
+  __device__ __forceinline__ void begin_tile(uint32_t blk) {
+    alpha = a.alpha[blk];
+    inv_alpha = 1.0 / (double)alpha;
+    cg = 1.0 / ((double)a.n * (double)alpha);
+    acc = 0.0;
+  }
+  __device__ __forceinline__ void scalar(uint64_t j) {
+    int32_t S = 0;
+    for (uint32_t i = 0; i < a.n; ++i) {
+      float* hl = (float*)a.h_local.p[i];
+      const float hv = hl[j];
+      const float delta = ((const float*)a.grads.p[i])[j] - hv;
+      uint32_t word = 0;
+      if (ROUND == INTSGD_ROUND_STOCHASTIC) {
+        const uint64_t quad = j >> 2;
+        const vu4 rw = philox4x32_10((uint32_t)quad, (uint32_t)(quad >> 32), i, a.rs.step,
+                                     a.rs.key0, a.rs.key1);
+        word = pick_word(rw, (uint32_t)(j & 3));
+      }
+      bool sat;
+      const int32_t q = round_clip<ROUND>(alpha * delta, word, a.rs, sat);
+      if (sat) atomicAdd(&lds.sat[i], 1ull);
+      hl[j] = shift_local(hv, q, inv_alpha);
+      S += q;
+    }
+    float hj = a.h[j];
+    a.x[j] = diana_coord(a.x[j], hj, S, cg, a.eta, acc);
+    a.h[j] = hj;
+  }
+  __device__ __forceinline__ void begin_body(uint64_t first_quad, uint32_t quads) {
+    q0 = first_quad;
+    nq = quads;
+    x_s = make_stream((vf4*)a.x + q0, nq * 16u);
+    h_s = make_stream((vf4*)a.h + q0, nq * 16u);
+  }
+  template <int W>
+  __device__ __forceinline__ void workers(uint32_t i0, uint32_t ql, vi4& S) {
+    vf4 g[W], hl[W];
+    __amdgpu_buffer_rsrc_t hs[W];
+#pragma unroll
+    for (int w = 0; w < W; ++w) {
+      const __amdgpu_buffer_rsrc_t gs = make_stream((const vf4*)a.grads.p[i0 + w] + q0, nq * 16u);
+      hs[w] = make_stream((vf4*)a.h_local.p[i0 + w] + q0, nq * 16u);
+      g[w] = as_f(load128<INTSGD_GRAD_LOAD_POLICY>(gs, ql * 16u));
+      hl[w] = as_f(load128<INTSGD_GRAD_LOAD_POLICY>(hs[w], ql * 16u));
+    }
+    const uint64_t quad = q0 + ql;
+#pragma unroll
+    for (int w = 0; w < W; ++w) {
+      vu4 rw = vu4{0u, 0u, 0u, 0u};
+      if (ROUND == INTSGD_ROUND_STOCHASTIC)
+        rw = philox4x32_10((uint32_t)quad, (uint32_t)(quad >> 32), i0 + w, a.rs.step, a.rs.key0,
+                           a.rs.key1);
+      bool s0, s1, s2, s3;
+      vi4 q;
+      q.x = round_clip<ROUND>(alpha * (g[w].x - hl[w].x), rw.x, a.rs, s0);
+      q.y = round_clip<ROUND>(alpha * (g[w].y - hl[w].y), rw.y, a.rs, s1);
+      q.z = round_clip<ROUND>(alpha * (g[w].z - hl[w].z), rw.z, a.rs, s2);
+      q.w = round_clip<ROUND>(alpha * (g[w].w - hl[w].w), rw.w, a.rs, s3);
+      const uint32_t cnt = count_lanes(s0) + count_lanes(s1) + count_lanes(s2) + count_lanes(s3);
+      if (cnt != 0 && (threadIdx.x & 63u) == 0)
+        atomicAdd(&lds.sat[i0 + w], (unsigned long long)cnt);
+      const vf4 hn = vf4{shift_local(hl[w].x, q.x, inv_alpha), shift_local(hl[w].y, q.y, inv_alpha),
+                         shift_local(hl[w].z, q.z, inv_alpha), shift_local(hl[w].w, q.w, inv_alpha)};
+      store128<INTSGD_X_STORE_POLICY>(hs[w], ql * 16u, as_u(hn));
+      S += q;
+    }
+  }
+  __device__ __forceinline__ void quad(uint32_t ql) {
+    const vf4 xv = as_f(load128<INTSGD_X_LOAD_POLICY>(x_s, ql * 16u));
+    vf4 hv = as_f(load128<INTSGD_X_LOAD_POLICY>(h_s, ql * 16u));
+    vi4 S = vi4{0, 0, 0, 0};
+    uint32_t i = 0;
+    for (; i + 4 <= a.n; i += 4) workers<4>(i, ql, S);
+    if (a.n - i >= 2) { workers<2>(i, ql, S); i += 2; }
+    if (a.n - i >= 1) workers<1>(i, ql, S);
+    vf4 xn;
+    float h0 = hv.x, h1 = hv.y, h2 = hv.z, h3 = hv.w;
+    xn.x = diana_coord(xv.x, h0, S.x, cg, a.eta, acc);
+    xn.y = diana_coord(xv.y, h1, S.y, cg, a.eta, acc);
+    xn.z = diana_coord(xv.z, h2, S.z, cg, a.eta, acc);
+    xn.w = diana_coord(xv.w, h3, S.w, cg, a.eta, acc);
+    store128<INTSGD_X_STORE_POLICY>(h_s, ql * 16u, as_u(vf4{h0, h1, h2, h3}));
+    store128<INTSGD_X_STORE_POLICY>(x_s, ql * 16u, as_u(xn));
+  }
+  __device__ __forceinline__ void end_tile(uint32_t t, uint32_t iter) {
+    const double total = block_sum(acc, lds, iter & 1u);
+    if (threadIdx.x == 0) a.fin.norm_partial[t] = total;
+  }
+};
+
+template <int ROUND>
+__global__ __launch_bounds__(kThreads) void k_diana(const DianaArgs a) {
+  __shared__ ReduceLds lds;
+  zero_sat(lds);
+  DianaOp<ROUND> op(a, lds);
+  drive_tiles(a.tm, op);
+  __syncthreads();
+  if (threadIdx.x == 0) publish_sat(a.fin, lds, blockIdx.x);
+}
+
 // ================================================================== a1-a3 (one worker per blockIdx.y)
 struct CompressArgs {
   TileMap tm;
@@ -980,6 +1128,24 @@ hipError_t launch_step_fused(const TileMap& tm, const LaunchShape& ls, uint32_t 
       if (random) hipLaunchKernelGGL((k_aggregate<1, true, false>), grid, block, ls.lds_reserve, ls.stream, a);
       else hipLaunchKernelGGL((k_aggregate<0, true, false>), grid, block, ls.lds_reserve, ls.stream, a);
     }
+  }
+  hipError_t e = after_launch();
+  if (e != hipSuccess) return e;
+  return finish(ls.stream, fin, true, true);
+}
+
+hipError_t launch_diana_step(const TileMap& tm, const LaunchShape& ls, uint32_t n,
+                             const RoundSpec& rs, const WorkerPtrs& grads,
+                             const WorkerOutPtrs& h_local, const float* alpha, double eta, float* x,
+                             float* h, const Finish& fin) {
+  DianaArgs a{tm, rs, n, alpha, eta, x, h, fin, grads, h_local};
+  const dim3 grid(ls.grid), block(kThreads);
+  {
+    Tapped tap(ls);
+    if (rs.rounding == INTSGD_ROUND_STOCHASTIC)
+      hipLaunchKernelGGL((k_diana<1>), grid, block, ls.lds_reserve, ls.stream, a);
+    else
+      hipLaunchKernelGGL((k_diana<0>), grid, block, ls.lds_reserve, ls.stream, a);
   }
   hipError_t e = after_launch();
   if (e != hipSuccess) return e;

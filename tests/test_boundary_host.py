@@ -190,6 +190,23 @@ def test_momentum_calls_validation():
     assert g(desc.ref(), FAKE, FAKE, 0.1, 0.9, 1e-4, FAKE, FAKE, FAKE, None, need, None) == EWORKSPACE
 
 
+def test_diana_call_validation():
+    desc = P.Desc(1000, 4)
+    need = P.intsgd_workspace_bytes(desc)
+    f = lib.intsgd_diana_step
+    args = lambda **kw: [desc.ref(), kw.get("g", ptrs(4)), kw.get("hl", ptrs(4)), kw.get("alpha", FAKE),
+                         kw.get("eta", 0.1), kw.get("x", FAKE), kw.get("h", FAKE), kw.get("r", None),
+                         kw.get("beta", 0.0), 0.0, FAKE, FAKE, FAKE, kw.get("wb", need), None]
+    assert f(*args(hl=None)) == EINVAL
+    assert f(*args(hl=ptrs(4, FAKE_ODD))) == EALIGN
+    assert f(*args(h=None)) == EINVAL
+    assert f(*args(h=FAKE_ODD)) == EALIGN
+    assert f(*args(alpha=None)) == EINVAL
+    assert f(*args(eta=-1.0)) == EINVAL
+    assert f(*args(r=FAKE, beta=1.0)) == EINVAL
+    assert f(*args(wb=16)) == EWORKSPACE
+
+
 def test_status_strings():
     for st in (0, -1, -2, -3, -4, -5):
         assert P.intsgd_status_string(st) not in ("", "unknown status")

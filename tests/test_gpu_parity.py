@@ -529,3 +529,72 @@ def test_momentum_multi_step_with_alpha_rule():
         assert rel_err(host(st.norm_sq), out["normsq"]) <= NORM_RTOL
         r_or, ad, _, _ = oracle.next_alpha(out["normsq"], r_or, d=w.d, n=w.n, beta=w.beta, eps=w.eps, eta=w.eta)
         assert rel_err(host(st.alpha), ad) <= ALPHA_RTOL
+
+
+# --------------------------------------------------------------------------- IntDIANA
+@pytest.mark.parametrize("rounding", [P.ROUND_NEAREST_EVEN, P.ROUND_STOCHASTIC])
+@pytest.mark.parametrize("shape", SHAPES[:4] + SHAPES[6:], ids=lambda s: "d%d-n%d" % (s[0], s[1]))
+def test_diana_step_matches_oracle(shape, rounding):
+    """Algorithm 3 in one sweep: integers via the clip counts and the shifts (bit-exact
+    messages imply h_i within 1 ulp), x, h, h_i within 1 fp32 ulp, norm within 1e-5."""
+    d, n, offsets, tile = shape
+    P.intsgd_set_tuning(tile_coords=tile)
+    alpha, g, x = make_case(d, n, offsets, seed=7 * d + rounding)
+    B = alpha.size
+    rng = np.random.default_rng(d + 1)
+    hl = rng.normal(0, 0.01, (n, d)).astype(F32)
+    h = hl.astype(np.float64).mean(0).astype(F32)
+    eta, L, seed, step = 0.1, P.default_clip(n), 5, 9
+    off_np = None if offsets is None else np.array(offsets, np.uint64)
+    out = oracle.diana_step(list(g), list(hl), alpha, x, h, rounding=rounding, L=L, eta=eta,
+                            seed=seed, step=step, offsets=off_np)
+    desc = P.Desc(d, n, rounding=rounding, clip=L, seed=seed, step=step, block_offsets=offsets)
+    ws = P.new_workspace(desc, DEV)
+    d_g, d_hl = rows_on_device(g), rows_on_device(hl)
+    d_x, d_h, d_a = dev(x), dev(h), dev(alpha)
+    d_ns = torch.zeros(B, dtype=torch.float64, device=DEV)
+    d_cnt = torch.zeros(n, dtype=torch.int64, device=DEV)
+    P.intsgd_diana_step(desc, d_g, d_hl, d_a, eta, d_x, d_h, None, 0.0, 0.0, d_ns, d_cnt, ws)
+    assert u64(d_cnt).tolist() == out["sat_count"].tolist()
+    for i in range(n):
+        assert_within_ulp(host(d_hl[i]), out["h_local_new"][i], 1, "local shift %d" % i)
+    assert_within_ulp(host(d_h), out["h_new"], 1, "global shift")
+    assert_within_ulp(host(d_x), out["x_new"], 1, "x")
+    assert rel_err(host(d_ns), out["normsq"]) <= NORM_RTOL
+    for i in range(n):
+        assert np.array_equal(host(d_g[i]).view(np.uint32), g[i].view(np.uint32))
+
+
+def test_diana_heterogeneous_quadratic_multi_step():
+    """f_i(x) = 0.5 ||x - b_i||^2 with exact gradients and Algorithm 3's own alpha rule
+    (beta = 0): 25 chained GPU steps replayed in the oracle with the GPU's alpha; the
+    iterates converge and the clip counts stay zero with a modest clip bound."""
+    rng = np.random.default_rng(61)
+    n, d, eta = 4, 100_003, 0.25
+    b = [dev(rng.normal(0, 1, d).astype(F32)) for _ in range(n)]
+    xstar = torch.stack(b).double().mean(0)
+    desc = P.Desc(d, n, rounding=P.ROUND_STOCHASTIC, clip=4096, seed=2)
+    st = Stepper(desc, eta=eta, beta=0.0, eps=1e-12, device=DEV)
+    x = torch.zeros(d, dtype=torch.float32, device=DEV)
+    first = float(eta**2 * (x.double() - xstar).pow(2).sum())
+    x = (x.double() - eta * (x.double() - xstar)).float()            # exact first step
+    st.start([first])
+    hl = [torch.zeros(d, dtype=torch.float32, device=DEV) for _ in range(n)]
+    h = torch.zeros(d, dtype=torch.float32, device=DEV)
+    d0 = float((x.double() - xstar).norm())
+    for k in range(1, 26):
+        g = [(x - b[i]) for i in range(n)]
+        a_gpu = host(st.alpha).copy()
+        snap = [host(t).copy() for t in [x, h] + hl + g]
+        desc.step = k
+        P.intsgd_diana_step(desc, g, hl, st.alpha, eta, x, h, st.r, 0.0, 1e-12, st.norm_sq,
+                            st.sat_count, st.workspace)
+        out = oracle.diana_step(snap[2 + n:], snap[2:2 + n], a_gpu, snap[0], snap[1], rounding=1,
+                                L=4096, eta=eta, seed=2, step=k)
+        assert_within_ulp(host(x), out["x_new"], 1, "x at step %d" % k)
+        assert_within_ulp(host(h), out["h_new"], 1, "h at step %d" % k)
+        for i in range(n):
+            assert_within_ulp(host(hl[i]), out["h_local_new"][i], 1, "h_%d at step %d" % (i, k))
+        assert u64(st.sat_count).sum() == 0 == out["sat_count"].sum()
+        assert rel_err(host(st.norm_sq), out["normsq"]) <= NORM_RTOL
+    assert float((x.double() - xstar).norm()) < 1e-2 * d0
