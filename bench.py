@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--no-taps", action="store_true",
                     help="do not record per-kernel events (roofline numbers are then null)")
     ap.add_argument("--global-alpha", action="store_true", help="config 4 with one alpha")
+    ap.add_argument("--heuristic", action="store_true",
+                    help="Heuristic IntSGD: a profiling pass (max |g|) sets alpha before every step")
     ap.add_argument("--diana", action="store_true",
                     help="IntDIANA step (Algorithm 3): n local shifts + a global shift in HBM")
     ap.add_argument("--momentum", action="store_true",
@@ -162,7 +164,11 @@ def main():
 
     def one_step(k):
         rows = sets[(k - 1) % pool][1]
-        if args.diana:
+        if args.heuristic:
+            nb = 7 if w.wire == 8 else 31
+            P.intsgd_heuristic_alpha(desc, rows, nb, st.alpha, st.workspace)   # extra sweep
+            st.step_fused(rows, x, k, chain_alpha=False)
+        elif args.diana:
             desc.step = k
             P.intsgd_diana_step(desc, rows, h_local, st.alpha, st.eta, x, h_global, st.r, st.beta,
                                 st.eps, st.norm_sq, st.sat_count, st.workspace)
@@ -226,7 +232,7 @@ def main():
             "workload": w.name, "d": w.d, "n_workers": w.n, "blocks": w.num_blocks,
             "rounding": "stochastic" if w.rounding else "nearest-even", "wire": "int%d" % w.wire,
             "clip": w.clip, "grad_dist": w.grad_kind,
-            "mode": "diana" if args.diana else args.mode + ("+momentum" if args.momentum else ""),
+            "mode": "heuristic-alpha+fused" if args.heuristic else "diana" if args.diana else args.mode + ("+momentum" if args.momentum else ""),
             "gradient_sets": pool,
             "tuning_overrides": {"tile_coords": tile, "max_workgroups": grid,
                                  "workgroups_per_cu": wgs_per_cu},

@@ -258,6 +258,20 @@ intsgd_status intsgd_diana_step(const intsgd_desc* desc, const float* const* gra
                                 uint64_t* sat_count, void* workspace, size_t workspace_bytes,
                                 void* hip_stream);
 
+/*
+ * Heuristic IntSGD scaling (Section 5.2: the SwitchML rule the paper compares with), which
+ * needs a profiling pass over all gradients before they can be compressed:
+ *   alpha_l = (2^nb - 1) / (n 2^max_exp),  2^max_exp = smallest power of two >= the largest
+ *   finite |g_i[j]| over all n workers and all coordinates j of block l,
+ * so that |alpha g| <= (2^nb - 1)/n.  nb in [1, 31] is the number of magnitude bits (7 for
+ * an int8 aggregate, 31 for int32).  An all-zero block gets alpha = 1; alpha is capped at
+ * the largest finite fp32.  alpha_out: DEVICE float[B].  The result can be passed to any
+ * of the compress / step calls in place of the adaptive alpha.
+ */
+intsgd_status intsgd_heuristic_alpha(const intsgd_desc* desc, const float* const* grads,
+                                     uint32_t nb, float* alpha_out, void* workspace,
+                                     size_t workspace_bytes, void* hip_stream);
+
 /* Tuning overrides (process-wide; not part of the numerical contract: results do not
  * depend on them except for the summation order of the norm).  A field that is 0
  * means "automatic": the library picks per call (by rounding mode) what measured best

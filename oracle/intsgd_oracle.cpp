@@ -35,6 +35,7 @@
 #include <cmath>
 #include <cstdint>
 #include <cstring>
+#include <limits>
 #include <vector>
 
 namespace {
@@ -328,6 +329,41 @@ uint64_t oracle_diana_step(const float* const* grads, const float* const* h_loca
   oracle_diana_update(s, j0, len, alpha, offsets, B, n, eta, x, h, x_new, h_new);
   oracle_update_norm(x_new, x, j0, len, offsets, B, normsq);
   return overflow;
+}
+
+// Heuristic IntSGD scaling (Section 5.2; the SwitchML rule the paper compares with):
+// alpha = (2^nb - 1) / (n 2^max_exp), max_exp the exponent of the largest absolute value
+// in the package, read here as the smallest integer e with 2^e >= max|g| over all n
+// workers and all coordinates of the block (so that |alpha g| <= (2^nb - 1)/n).
+// Step 1, the profiling pass: running maximum of |g| per block over a slice; non-finite
+// entries are skipped (they are clipped and counted later anyway).
+void oracle_max_abs(const float* g, uint64_t j0, uint64_t len, const uint64_t* offsets, uint32_t B,
+                    float* max_abs) {
+  for (uint64_t t_ = 0; t_ < len; ++t_) {
+    const float v = std::fabs(g[t_]);
+    if (!std::isfinite(v)) continue;
+    float& slot = max_abs[block_of(j0 + t_, offsets, B)];
+    if (v > slot) slot = v;
+  }
+}
+
+// Step 2: the scaling factors.  An all-zero block gets alpha = 1 (every alpha gives zero
+// integers there); alpha is capped at the largest finite fp32 number.
+void oracle_heuristic_alpha(const float* max_abs, uint32_t B, uint32_t n, uint32_t nb,
+                            double* alpha_d, float* alpha_f) {
+  for (uint32_t l = 0; l < B; ++l) {
+    double a = 1.0;
+    if (max_abs[l] > 0.0f) {
+      int e = 0;
+      const double frac = std::frexp((double)max_abs[l], &e);    // max = frac 2^e, frac in [0.5, 1)
+      const int max_exp = (frac == 0.5) ? e - 1 : e;              // smallest e with 2^e >= max
+      const double top = std::ldexp(1.0, (int)nb) - 1.0;
+      a = std::ldexp(top / (double)n, -max_exp);
+      if (a > (double)std::numeric_limits<float>::max()) a = (double)std::numeric_limits<float>::max();
+    }
+    if (alpha_d) alpha_d[l] = a;
+    alpha_f[l] = (float)a;
+  }
 }
 
 // oracle_step with the momentum / weight-decay update in place of the plain one.

@@ -15,6 +15,7 @@ __all__ = [
     "philox4x32_10", "random_word", "int_random", "int_nearest", "saturate", "compress",
     "int_sum", "decode_update", "update_norm", "next_alpha", "step", "decode_update_momentum",
     "step_momentum", "diana_compress", "diana_update", "diana_step",
+    "max_abs", "heuristic_alpha",
     "ROUND_NEAREST_EVEN", "ROUND_STOCHASTIC",
 ]
 
@@ -68,6 +69,10 @@ _lib.oracle_diana_step.argtypes = [C.POINTER(_f32p), C.POINTER(_f32p), C.c_uint3
                                    C.c_uint64, C.c_uint32, C.c_double, _f32p, _f32p, _f32p, _f32p,
                                    C.POINTER(_f32p), _i32p, _u64p, _f64p]
 _lib.oracle_diana_step.restype = C.c_uint64
+_lib.oracle_max_abs.argtypes = [_f32p, C.c_uint64, C.c_uint64, _u64p, C.c_uint32, _f32p]
+_lib.oracle_max_abs.restype = None
+_lib.oracle_heuristic_alpha.argtypes = [_f32p, C.c_uint32, C.c_uint32, C.c_uint32, _f64p, _f32p]
+_lib.oracle_heuristic_alpha.restype = None
 _lib.oracle_update_norm.argtypes = [_f32p, _f32p, C.c_uint64, C.c_uint64, _u64p, C.c_uint32,
                                     _f64p]
 _lib.oracle_update_norm.restype = None
@@ -318,3 +323,22 @@ def diana_step(grads, h_local, alpha, x, h, *, rounding, L, eta, seed=0, step=0,
                                  _ptr(S, C.c_int32), _ptr(sat, C.c_uint64), _ptr(ns, C.c_double))
     return dict(x_new=xn, h_new=hn, h_local_new=hn_local, S=S, sat_count=sat, normsq=ns,
                 overflow=int(ovf))
+
+
+def max_abs(g, *, j0=0, offsets=None, B=1, out=None):
+    """Running per-block maximum of |g| over finite entries (accumulated into ``out``)."""
+    g = _arr(g, np.float32)
+    off, offp = _offsets(offsets, B)
+    m = np.zeros(B, np.float32) if out is None else out
+    _lib.oracle_max_abs(_ptr(g, C.c_float), int(j0), g.size, offp, B, _ptr(m, C.c_float))
+    return m
+
+
+def heuristic_alpha(max_abs_per_block, *, n, nb):
+    """Heuristic IntSGD scaling -> (alpha f64[B], alpha f32[B])."""
+    m = np.atleast_1d(_arr(max_abs_per_block, np.float32))
+    ad = np.empty(m.size, np.float64)
+    af = np.empty(m.size, np.float32)
+    _lib.oracle_heuristic_alpha(_ptr(m, C.c_float), m.size, int(n), int(nb), _ptr(ad, C.c_double),
+                                _ptr(af, C.c_float))
+    return ad, af

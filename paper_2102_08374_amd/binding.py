@@ -17,7 +17,7 @@ __all__ = [
     "intsgd_update_norm", "intsgd_next_alpha", "intsgd_next_alpha_host", "intsgd_compress_sum",
     "intsgd_decode_update_norm", "intsgd_step_fused", "intsgd_step_fused_next_alpha",
     "intsgd_decode_update_momentum", "intsgd_step_momentum", "intsgd_diana_step",
-    "intsgd_tap_next_launch", "intsgd_set_tuning", "intsgd_get_tuning", "intsgd_status_string",
+    "intsgd_heuristic_alpha", "intsgd_tap_next_launch", "intsgd_set_tuning", "intsgd_get_tuning", "intsgd_status_string",
     "new_workspace", "EXPORTED_SYMBOLS",
 ]
 
@@ -30,7 +30,7 @@ MAX_WORKERS = 128
 EXPORTED_SYMBOLS = [
     "intsgd_workspace_bytes", "intsgd_tap_next_launch", "intsgd_prepare", "intsgd_release",
     "intsgd_compress", "intsgd_step_fused_next_alpha", "intsgd_decode_update_momentum",
-    "intsgd_step_momentum", "intsgd_diana_step",
+    "intsgd_step_momentum", "intsgd_diana_step", "intsgd_heuristic_alpha",
     "intsgd_int_sum", "intsgd_decode_update", "intsgd_update_norm", "intsgd_next_alpha",
     "intsgd_next_alpha_host", "intsgd_compress_sum", "intsgd_decode_update_norm",
     "intsgd_step_fused", "intsgd_set_tuning", "intsgd_get_tuning", "intsgd_status_string",
@@ -91,6 +91,7 @@ _lib.intsgd_decode_update_momentum.argtypes = [_DP, _P, _P, C.c_double, C.c_doub
                                                _P, _P, _P, C.c_size_t, _P]
 _lib.intsgd_diana_step.argtypes = [_DP, _PP, _PP, _P, C.c_double, _P, _P, _P, C.c_double, C.c_double,
                                    _P, _P, _P, C.c_size_t, _P]
+_lib.intsgd_heuristic_alpha.argtypes = [_DP, _PP, C.c_uint32, _P, _P, C.c_size_t, _P]
 _lib.intsgd_step_momentum.argtypes = [_DP, _PP, _P, C.c_double, C.c_double, C.c_double, _P, _P, _P,
                                       C.c_double, C.c_double, _P, _P, _P, C.c_size_t, _P]
 _lib.intsgd_set_tuning.argtypes = [C.POINTER(_CTuning)]
@@ -104,7 +105,8 @@ for _name in ("intsgd_prepare", "intsgd_compress", "intsgd_int_sum", "intsgd_dec
               "intsgd_update_norm", "intsgd_next_alpha", "intsgd_next_alpha_host",
               "intsgd_compress_sum", "intsgd_decode_update_norm", "intsgd_step_fused",
               "intsgd_step_fused_next_alpha", "intsgd_tap_next_launch", "intsgd_set_tuning",
-              "intsgd_decode_update_momentum", "intsgd_step_momentum", "intsgd_diana_step"):
+              "intsgd_decode_update_momentum", "intsgd_step_momentum", "intsgd_diana_step",
+              "intsgd_heuristic_alpha"):
     getattr(_lib, _name).restype = C.c_int
 
 
@@ -388,6 +390,14 @@ def intsgd_diana_step(desc, grads, h_local, alpha, eta, x, h, r, beta, eps, norm
                                   float(eta), _ptr(x), _ptr(h), _ptr(r), float(beta), float(eps),
                                   _ptr(norm_sq_out), _ptr(sat_count), w, wb, _stream(stream)),
            "intsgd_diana_step")
+
+
+def intsgd_heuristic_alpha(desc, grads, nb, alpha_out, workspace, stream=None):
+    _need_rows(desc, grads, torch.float32, "grads")
+    _need(alpha_out, desc.num_blocks, torch.float32, "alpha_out")
+    w, wb = _ws(workspace)
+    _check(_lib.intsgd_heuristic_alpha(desc.ref(), _ptr_array(grads), int(nb), _ptr(alpha_out), w, wb,
+                                       _stream(stream)), "intsgd_heuristic_alpha")
 
 
 def intsgd_set_tuning(tile_coords=0, max_workgroups=0, workgroups_per_cu=0):

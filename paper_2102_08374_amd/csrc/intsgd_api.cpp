@@ -581,6 +581,23 @@ intsgd_status intsgd_diana_step(const intsgd_desc* desc, const float* const* gra
   return done(launch_diana_step(t.tm, t.ls, desc->n, round_spec(desc), g, hl, alpha, eta, x, h, fin));
 }
 
+intsgd_status intsgd_heuristic_alpha(const intsgd_desc* desc, const float* const* grads,
+                                     uint32_t nb, float* alpha_out, void* workspace,
+                                     size_t workspace_bytes, void* hip_stream) {
+  INTSGD_TRY(validate_desc(desc));
+  INTSGD_TRY(validate_worker_ptrs((const void* const*)grads, desc->n));
+  if (alpha_out == nullptr) return INTSGD_EINVAL;
+  if (nb < 1 || nb > 31) return INTSGD_ERANGE;
+  INTSGD_TRY(validate_workspace(desc, workspace, workspace_bytes));
+  Tiling t;
+  INTSGD_TRY(make_tiling(desc, hip_stream, &t));
+  WorkerPtrs g;
+  fill_ptrs(&g, (const void* const*)grads, desc->n);
+  const WorkspaceLayout w = workspace_layout(desc);
+  return done(launch_heuristic_alpha(t.tm, t.ls, desc->n, nb, g, ws_at<uint32_t>(workspace, w.norm_off),
+                                     t.tile_prefix, desc->num_blocks, alpha_out));
+}
+
 intsgd_status intsgd_set_tuning(const intsgd_tuning* tuning) {
   if (tuning == nullptr) return INTSGD_EINVAL;
   const uint32_t tile = tuning->tile_coords, grid = tuning->max_workgroups,

@@ -110,6 +110,9 @@ hipError_t launch_diana_step(const TileMap& tm, const LaunchShape& ls, uint32_t 
                              const RoundSpec& rs, const WorkerPtrs& grads,
                              const WorkerOutPtrs& h_local, const float* alpha, double eta, float* x,
                              float* h, const Finish& fin);
+hipError_t launch_heuristic_alpha(const TileMap& tm, const LaunchShape& ls, uint32_t n, uint32_t nb,
+                                  const WorkerPtrs& grads, uint32_t* tile_max,
+                                  const uint32_t* tile_prefix, uint32_t B, float* alpha_out);
 hipError_t launch_next_alpha(hipStream_t stream, const double* norm_sq, const AlphaRule& rule,
                              uint32_t B, uint32_t n, uint64_t d);
 

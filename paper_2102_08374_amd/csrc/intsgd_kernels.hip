@@ -738,6 +738,109 @@ __global__ __launch_bounds__(kThreads) void k_diana(const DianaArgs a) {
   if (threadIdx.x == 0) publish_sat(a.fin, lds, blockIdx.x);
 }
 
+// ================================================================== Heuristic IntSGD scaling
+// Section 5.2's comparison rule (from SwitchML): alpha = (2^nb - 1)/(n 2^max_exp), where
+// 2^max_exp is the smallest power of two >= the largest finite |g| of the block over all
+// workers.  Pass 1 ("profiling"): per-tile maximum of the absolute bit patterns, which
+// order like the values and make the reduction exact and order-free.
+struct MaxAbsArgs {
+  TileMap tm;
+  uint32_t n;
+  uint32_t* tile_max;    // one slot per tile
+  WorkerPtrs grads;
+};
+
+__device__ __forceinline__ uint32_t finite_abs_bits(float v) {
+  const uint32_t b = __float_as_uint(v) & 0x7FFFFFFFu;
+  return b < 0x7F800000u ? b : 0u;      // Inf / NaN do not take part
+}
+
+struct MaxAbsOp {
+  const MaxAbsArgs& a;
+  uint32_t* lds_max;
+  uint32_t best;
+  uint64_t q0;
+  uint32_t nq;
+
+  __device__ __forceinline__ MaxAbsOp(const MaxAbsArgs& args, uint32_t* l)
+      : a(args), lds_max(l), best(0), q0(0), nq(0) {}
+  __device__ __forceinline__ void begin_tile(uint32_t) {
+    best = 0;
+    if (threadIdx.x == 0) *lds_max = 0u;
+    __syncthreads();
+  }
+  __device__ __forceinline__ void scalar(uint64_t j) {
+    for (uint32_t i = 0; i < a.n; ++i) best = max(best, finite_abs_bits(((const float*)a.grads.p[i])[j]));
+  }
+  __device__ __forceinline__ void begin_body(uint64_t first_quad, uint32_t quads) {
+    q0 = first_quad;
+    nq = quads;
+  }
+  template <int W>
+  __device__ __forceinline__ void workers(uint32_t i0, uint32_t ql) {
+    vf4 g[W];
+#pragma unroll
+    for (int w = 0; w < W; ++w) {
+      const __amdgpu_buffer_rsrc_t src = make_stream((const vf4*)a.grads.p[i0 + w] + q0, nq * 16u);
+      g[w] = as_f(load128<kNonTemporal>(src, ql * 16u));
+    }
+#pragma unroll
+    for (int w = 0; w < W; ++w)
+      best = max(max(best, finite_abs_bits(g[w].x)),
+                 max(max(finite_abs_bits(g[w].y), finite_abs_bits(g[w].z)), finite_abs_bits(g[w].w)));
+  }
+  __device__ __forceinline__ void quad(uint32_t ql) {
+    uint32_t i = 0;
+    for (; i + 8 <= a.n; i += 8) workers<8>(i, ql);
+    if (a.n - i >= 4) { workers<4>(i, ql); i += 4; }
+    if (a.n - i >= 2) { workers<2>(i, ql); i += 2; }
+    if (a.n - i >= 1) workers<1>(i, ql);
+  }
+  __device__ __forceinline__ void end_tile(uint32_t t, uint32_t) {
+    if (best != 0u) atomicMax(lds_max, best);
+    __syncthreads();
+    if (threadIdx.x == 0) a.tile_max[t] = *lds_max;
+    __syncthreads();
+  }
+};
+
+__global__ __launch_bounds__(kThreads) void k_max_abs(const MaxAbsArgs a) {
+  __shared__ uint32_t lds_max;
+  MaxAbsOp op(a, &lds_max);
+  drive_tiles(a.tm, op);
+}
+
+// Pass 2: workgroup l takes the maximum over block l's tiles and writes alpha_l.
+__global__ __launch_bounds__(kThreads) void k_heuristic_alpha(const uint32_t* tile_max,
+                                                              const uint32_t* tile_prefix,
+                                                              uint32_t num_tiles, uint32_t B,
+                                                              uint32_t n, uint32_t nb,
+                                                              float* alpha_out) {
+  __shared__ uint32_t lds_max;
+  const uint32_t l = blockIdx.x;
+  const uint32_t t0 = (B == 1) ? 0u : tile_prefix[l];
+  const uint32_t t1 = (B == 1) ? num_tiles : tile_prefix[l + 1];
+  if (threadIdx.x == 0) lds_max = 0u;
+  __syncthreads();
+  uint32_t best = 0;
+  for (uint32_t t = t0 + threadIdx.x; t < t1; t += kThreads) best = max(best, tile_max[t]);
+  if (best != 0u) atomicMax(&lds_max, best);
+  __syncthreads();
+  if (threadIdx.x != 0) return;
+  const uint32_t bits = lds_max;
+  double alpha = 1.0;                               // all-zero block: any alpha gives zeros
+  if (bits != 0u) {
+    const uint32_t field = bits >> 23, mant = bits & 0x7FFFFFu;
+    int max_exp;                                    // smallest e with 2^e >= the maximum
+    if (field != 0u) max_exp = (int)field - 127 + (mant != 0u ? 1 : 0);
+    else max_exp = -149 + (mant > 1u ? 32 - __clz((int)(mant - 1u)) : 0);
+    const double top = ldexp(1.0, (int)nb) - 1.0;
+    alpha = ldexp(top / (double)n, -max_exp);
+    if (alpha > 3.4028234663852886e38) alpha = 3.4028234663852886e38;   // largest finite fp32
+  }
+  alpha_out[l] = (float)alpha;
+}
+
 // ================================================================== a1-a3 (one worker per blockIdx.y)
 struct CompressArgs {
   TileMap tm;
@@ -1150,6 +1253,21 @@ hipError_t launch_diana_step(const TileMap& tm, const LaunchShape& ls, uint32_t 
   hipError_t e = after_launch();
   if (e != hipSuccess) return e;
   return finish(ls.stream, fin, true, true);
+}
+
+hipError_t launch_heuristic_alpha(const TileMap& tm, const LaunchShape& ls, uint32_t n, uint32_t nb,
+                                  const WorkerPtrs& grads, uint32_t* tile_max,
+                                  const uint32_t* tile_prefix, uint32_t B, float* alpha_out) {
+  MaxAbsArgs a{tm, n, tile_max, grads};
+  {
+    Tapped tap(ls);
+    hipLaunchKernelGGL(k_max_abs, dim3(ls.grid), dim3(kThreads), ls.lds_reserve, ls.stream, a);
+  }
+  hipError_t e = after_launch();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(k_heuristic_alpha, dim3(B), dim3(kThreads), 0, ls.stream, tile_max, tile_prefix,
+                     tm.num_tiles, B, n, nb, alpha_out);
+  return after_launch();
 }
 
 hipError_t launch_next_alpha(hipStream_t stream, const double* norm_sq, const AlphaRule& rule,

@@ -207,6 +207,18 @@ def test_diana_call_validation():
     assert f(*args(wb=16)) == EWORKSPACE
 
 
+def test_heuristic_alpha_validation():
+    desc = P.Desc(1000, 4)
+    need = P.intsgd_workspace_bytes(desc)
+    f = lib.intsgd_heuristic_alpha
+    assert f(desc.ref(), ptrs(4), 0, FAKE, FAKE, need, None) == ERANGE
+    assert f(desc.ref(), ptrs(4), 32, FAKE, FAKE, need, None) == ERANGE
+    assert f(desc.ref(), ptrs(4), 7, None, FAKE, need, None) == EINVAL
+    assert f(desc.ref(), None, 7, FAKE, FAKE, need, None) == EINVAL
+    assert f(desc.ref(), ptrs(4, FAKE_ODD), 7, FAKE, FAKE, need, None) == EALIGN
+    assert f(desc.ref(), ptrs(4), 7, FAKE, None, need, None) == EWORKSPACE
+
+
 def test_status_strings():
     for st in (0, -1, -2, -3, -4, -5):
         assert P.intsgd_status_string(st) not in ("", "unknown status")

@@ -598,3 +598,45 @@ def test_diana_heterogeneous_quadratic_multi_step():
         assert u64(st.sat_count).sum() == 0 == out["sat_count"].sum()
         assert rel_err(host(st.norm_sq), out["normsq"]) <= NORM_RTOL
     assert float((x.double() - xstar).norm()) < 1e-2 * d0
+
+
+# --------------------------------------------------------------------------- Heuristic IntSGD
+@pytest.mark.parametrize("nb", [7, 31])
+@pytest.mark.parametrize("shape", SHAPES[:4] + SHAPES[6:], ids=lambda s: "d%d-n%d" % (s[0], s[1]))
+def test_heuristic_alpha_matches_oracle(shape, nb):
+    """The profiling pass and the SwitchML scaling rule: alpha bit-exact against the oracle
+    (maximum and power-of-two arithmetic are exact), incl. non-finite entries, an all-zero
+    block, denormal and power-of-two maxima; then a step with that alpha still matches."""
+    d, n, offsets, tile = shape
+    P.intsgd_set_tuning(tile_coords=tile)
+    rng = np.random.default_rng(d * nb)
+    g = rng.normal(0, 1e-3, (n, d)).astype(F32)
+    g[rng.integers(0, n), rng.integers(0, d)] = np.inf
+    g[rng.integers(0, n), rng.integers(0, d)] = np.nan
+    B = 1 if offsets is None else len(offsets) - 1
+    off = [0, d] if offsets is None else offsets
+    if B >= 3:
+        g[:, off[0]:off[1]] = 0.0                                   # all-zero block
+        g[:, off[1]:off[2]] = np.where(rng.random((n, off[2] - off[1])) < 0.5, 1e-42, -3e-43)
+        g[1, off[2]] = 0.25                                          # exact power of two
+    off_np = None if offsets is None else np.array(offsets, np.uint64)
+    m = np.zeros(B, F32)
+    for i in range(n):
+        oracle.max_abs(g[i], offsets=off_np, B=B, out=m)
+    _, want = oracle.heuristic_alpha(m, n=n, nb=nb)
+    desc = P.Desc(d, n, rounding=P.ROUND_STOCHASTIC, clip=min(P.default_clip(n), 2**nb - 1), seed=4,
+                  step=1, block_offsets=offsets)
+    ws = P.new_workspace(desc, DEV)
+    rows = rows_on_device(g)
+    d_a = torch.zeros(B, dtype=torch.float32, device=DEV)
+    P.intsgd_heuristic_alpha(desc, rows, nb, d_a, ws)
+    assert np.array_equal(host(d_a).view(np.uint32), want.view(np.uint32))
+    x = rng.normal(0, 1, d).astype(F32)
+    out = oracle.step(list(g), want, x, rounding=1, L=desc.c.clip, eta=0.1, seed=4, step=1,
+                      offsets=off_np)
+    d_x = dev(x)
+    d_ns = torch.zeros(B, dtype=torch.float64, device=DEV)
+    d_cnt = torch.zeros(n, dtype=torch.int64, device=DEV)
+    P.intsgd_step_fused(desc, rows, d_a, 0.1, d_x, d_ns, d_cnt, ws)
+    assert_within_ulp(host(d_x), out["x_new"], 1, "x")
+    assert u64(d_cnt).tolist() == out["sat_count"].tolist()

@@ -574,3 +574,45 @@ def test_diana_keeps_integers_small_where_intsgd_does_not():
     assert max(mi_dia[10:]) <= 64                      # a few bits per coordinate
     assert max(mi_sgd[25:]) > 50 * max(mi_dia[25:])    # IntSGD's messages blow up
     assert dist[30] < 1e-3 * dist[0]                   # linear convergence of IntDIANA
+
+
+# ----------------------------------------------------------------------------- Heuristic IntSGD
+def test_heuristic_scaling_rule():
+    """Section 5.2: alpha = (2^nb - 1)/(n 2^max_exp) with 2^max_exp >= max|g|: hand-picked
+    values, exact rationals, power-of-two scale invariance, and the no-overflow property
+    |alpha g| <= (2^nb - 1)/n that the paper credits the rule with."""
+    n = 8
+    cases = {0.75: 0, 1.0: 0, 1.0000001: 1, 0.5: -1, 0.50000006: 0, 3.0: 2, 1e-3: -9, 1e-45: -149,
+             3e-45: -147, 2.0**-126: -126, 3.0e38: 128}
+    for m, e in cases.items():
+        for nb in (7, 31):
+            ad, af = oracle.heuristic_alpha([m], n=n, nb=nb)
+            want = Fraction(2**nb - 1, n) / Fraction(2) ** e
+            if want > Fraction(float(np.finfo(F32).max)):
+                want = Fraction(float(np.finfo(F32).max))
+            assert Fraction(float(ad[0])) == want, (m, nb)
+            assert af[0] == F32(float(want))
+    assert oracle.heuristic_alpha([0.0], n=n, nb=7)[1][0] == 1.0
+    rng = np.random.default_rng(59)
+    g = rng.normal(0, 1e-3, (n, 5000)).astype(F32)
+    g[2, 17] = np.inf
+    g[3, 99] = np.nan
+    offsets = np.array([0, 100, 4000, 5000], np.uint64)
+    m = np.zeros(3, F32)
+    for i in range(n):
+        oracle.max_abs(g[i, :3000], offsets=offsets, B=3, out=m)
+        oracle.max_abs(g[i, 3000:], j0=3000, offsets=offsets, B=3, out=m)
+    fin = np.where(np.isfinite(g), np.abs(g), 0)
+    want = [fin[:, 0:100].max(), fin[:, 100:4000].max(), fin[:, 4000:].max()]
+    assert m.tolist() == [float(v) for v in want]
+    for nb in (7, 31):
+        ad, af = oracle.heuristic_alpha(m, n=n, nb=nb)
+        for l, (a, b) in enumerate([(0, 100), (100, 4000), (4000, 5000)]):
+            assert float(ad[l]) * float(want[l]) <= (2**nb - 1) / n
+            assert float(ad[l]) * float(want[l]) > (2**nb - 1) / n / 2      # and not more than 2x slack
+        ad2, _ = oracle.heuristic_alpha(m * F32(1024.0), n=n, nb=nb)
+        assert np.array_equal(ad2 * 1024.0, ad)
+        # the integers it produces fit: nearest rounding of |alpha g| <= (2^nb - 1)/n
+        q, cnt = oracle.compress(np.where(np.isfinite(g[0]), g[0], 0).astype(F32), af, rounding=0,
+                                 L=2**nb - 1, offsets=offsets)
+        assert cnt == 0 and np.abs(q).max() <= math.ceil((2**nb - 1) / n)
