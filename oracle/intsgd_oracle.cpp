@@ -14,7 +14,7 @@
 // large vector: all per-coordinate quantities depend only on the GLOBAL index j.
 //
 // Arithmetic contract (where the paper leaves precision open, the reading is
-// fixed here and listed in the design notes):
+// fixed here):
 //   * scale: one IEEE fp32 multiply alpha_f * g (the paper's gradients are fp32);
 //   * deterministic rounding: round-half-to-even (the paper names torch.round);
 //   * randomized rounding: floor(t) + [u < t - floor(t)], u a 24-bit uniform
