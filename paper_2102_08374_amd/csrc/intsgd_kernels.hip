@@ -80,15 +80,21 @@ __device__ __forceinline__ vu4 as_u(vi4 v) { return __builtin_bit_cast(vu4, v); 
 // ------------------------------------------------------------------ Philox4x32-10
 // Counter-based generator of Salmon et al. (SC'11), written from its description:
 // ten rounds of two 32x32->64 multiplies, a word permutation and key injection,
-// with the key bumped by Weyl constants between rounds.
+// with the key bumped by Weyl constants between rounds.  On gfx950 the 32-bit
+// multiplies issue at full rate, so the two three-way xors of a round are half of its
+// cost as plain xors; v_bitop3_b32 (truth table 0x96 = a ^ b ^ c) does each in one.
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
+  return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
+}
+
 __device__ __forceinline__ vu4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
                                              uint32_t k0, uint32_t k1) {
 #pragma unroll
   for (int round = 0; round < 10; ++round) {
     const uint64_t p0 = (uint64_t)0xD2511F53u * (uint64_t)c0;
     const uint64_t p1 = (uint64_t)0xCD9E8D57u * (uint64_t)c2;
-    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
-    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    const uint32_t n0 = xor3((uint32_t)(p1 >> 32), c1, k0);
+    const uint32_t n2 = xor3((uint32_t)(p0 >> 32), c3, k1);
     c1 = (uint32_t)p1;
     c3 = (uint32_t)p0;
     c0 = n0;
