@@ -467,23 +467,15 @@ __global__ __launch_bounds__(kThreads) void k_finish(const Finish f) {
     if (tid < INTSGD_MAX_WORKERS) lds.sat[tid] = 0ull;
     __syncthreads();
     if (*f.sat_hint != 0u) {              // something clipped (or first use): read the rows
-      auto add_row = [&](uint32_t g) {
-        for (uint32_t i = 0; i < f.n; ++i) {
-          const unsigned long long c = f.sat_rows[(uint64_t)g * f.n + i];
-          if (c != 0ull) atomicAdd(&lds.sat[i], c);
-        }
-      };
-      uint32_t g = tid;
-      for (; g + 7u * kThreads < f.workgroups; g += 8u * kThreads) {
-        uint32_t flag[8];
-#pragma unroll
-        for (uint32_t u = 0; u < 8; ++u) flag[u] = f.sat_any[g + u * kThreads];
-#pragma unroll
-        for (uint32_t u = 0; u < 8; ++u)
-          if (flag[u] != 0u) add_row(g + u * kThreads);
+      // one wavefront per worker; every lane sums its share of the flagged workgroups'
+      // rows privately, so at most 64 LDS atomics per worker however much clipped
+      const uint32_t lane = tid & 63u;
+      for (uint32_t i = tid >> 6; i < f.n; i += kWaves) {
+        unsigned long long acc = 0ull;
+        for (uint32_t g = lane; g < f.workgroups; g += 64u)
+          if (f.sat_any[g] != 0u) acc += f.sat_rows[(uint64_t)g * f.n + i];
+        if (acc != 0ull) atomicAdd(&lds.sat[i], acc);
       }
-      for (; g < f.workgroups; g += kThreads)
-        if (f.sat_any[g] != 0u) add_row(g);
     }
     __syncthreads();
     if (tid < f.n) f.sat_count[tid] = lds.sat[tid];
