@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime_api.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdint>
 #include <cstring>
@@ -271,6 +272,14 @@ void fill_ptrs(WorkerPtrs* w, const void* const* src, uint32_t n) {
   for (uint32_t i = 0; i < n; ++i) w->p[i] = src[i];
 }
 
+// Ids that tag the clip hint of a launch: non-zero and different from call to call.
+uint32_t next_launch_id() {
+  static std::atomic<uint32_t> counter{0};
+  uint32_t id = ++counter;
+  if (id == 0) id = ++counter;
+  return id;
+}
+
 // The end-of-kernel reduction descriptor.  norm_sq_out / sat_count may be null when the
 // kernel does not produce them.
 Finish make_finish(const intsgd_desc* desc, const Tiling& t, void* ws, double* norm_sq_out,
@@ -280,6 +289,7 @@ Finish make_finish(const intsgd_desc* desc, const Tiling& t, void* ws, double* n
   f.norm_partial = ws_at<double>(ws, w.norm_off);
   f.norm_mid = ws_at<double>(ws, w.mid_off);
   f.sat_hint = ws_at<uint32_t>(ws, w.hint_off);
+  f.launch_id = next_launch_id();
   f.tile_prefix = t.tile_prefix;
   f.num_tiles = t.tm.num_tiles;
   f.B = desc->num_blocks;

@@ -75,9 +75,10 @@ struct Finish {
   uint32_t B;
   double* norm_sq_out;            // B
   uint32_t workgroups;            // grid of the sweep
-  uint32_t* sat_hint;             // non-zero: some workgroup clipped (or never used yet)
+  uint32_t* sat_hint;             // holds launch_id if some workgroup of this launch clipped
+  uint32_t launch_id;             // non-zero, different for consecutive launches
   uint32_t* sat_any;              // one flag per workgroup
-  uint64_t* sat_rows;             // [workgroup][n], written only where the flag is set
+  uint64_t* sat_rows;             // [worker][workgroup], written only where the flag is set
   uint32_t n;                     // workers (clip counts)
   uint64_t* sat_count;            // n
   uint32_t n_workers;             // n of the problem (alpha rule)

@@ -407,15 +407,16 @@ __device__ __forceinline__ void apply_alpha_rule(const AlphaRule& rule, uint32_t
 }
 
 // ------------------------------------------------------------------ reductions behind a sweep
-// Clip counts of this workgroup -> its flag and, only when some are non-zero, its row
-// plus the launch-wide hint that tells the final-sum kernel to look at the rows at all.
+// Clip counts of this workgroup -> its flag and, only when some are non-zero, its column
+// of the [worker][workgroup] count table plus the launch-wide hint (this launch's id)
+// that tells the final-sum kernel to look at the table at all.
 __device__ __forceinline__ void publish_sat(const Finish& f, const ReduceLds& lds, uint32_t wg) {
   bool any = false;
   for (uint32_t i = 0; i < f.n; ++i) any |= lds.sat[i] != 0ull;
   f.sat_any[wg] = any ? 1u : 0u;
   if (any) {
-    for (uint32_t i = 0; i < f.n; ++i) f.sat_rows[(uint64_t)wg * f.n + i] = lds.sat[i];
-    *f.sat_hint = 1u;       // every writer stores the same value
+    for (uint32_t i = 0; i < f.n; ++i) f.sat_rows[(uint64_t)i * f.workgroups + wg] = lds.sat[i];
+    *f.sat_hint = f.launch_id;      // every writer stores the same value
   }
 }
 
@@ -446,14 +447,17 @@ __global__ __launch_bounds__(kThreads) void k_finish_chunks(const double* partia
   if (threadIdx.x == 0) mid[blockIdx.x] = total;
 }
 
-// Workgroup l sums the norm partials of block l in a fixed order and applies the
-// optional alpha rule to it; workgroup 0 also totals the clip counts.
+// Workgroups [0, norm_blocks) sum the norm partials of one block each in a fixed order and
+// apply the optional alpha rule to it; the n workgroups after them total one worker's clip
+// counts each (reading the table only if this launch's id is in the hint word, i.e. if
+// something clipped; a stale or uninitialised hint can at worst cause a needless read).
 template <bool WITH_NORM, bool WITH_SAT>
 __global__ __launch_bounds__(kThreads) void k_finish(const Finish f) {
   __shared__ ReduceLds lds;
   const uint32_t tid = threadIdx.x;
-  const uint32_t l = blockIdx.x;
-  if (WITH_NORM) {
+  const uint32_t norm_blocks = WITH_NORM ? f.B : 0u;
+  if (WITH_NORM && blockIdx.x < norm_blocks) {
+    const uint32_t l = blockIdx.x;
     const uint32_t t0 = (f.B == 1) ? 0u : f.tile_prefix[l];
     const uint32_t t1 = (f.B == 1) ? f.num_tiles : f.tile_prefix[l + 1];
     const double total = ordered_sum(f.norm_partial, t0, t1, lds);
@@ -461,25 +465,30 @@ __global__ __launch_bounds__(kThreads) void k_finish(const Finish f) {
       f.norm_sq_out[l] = total;
       if (f.rule.r != nullptr) apply_alpha_rule(f.rule, f.B, f.n_workers, f.d, l, total);
     }
+    return;
   }
-  if (WITH_SAT && l == 0) {
+  if (WITH_SAT) {
+    const uint32_t i = blockIdx.x - norm_blocks;           // worker
+    if (tid == 0) lds.sat[0] = 0ull;
     __syncthreads();
-    if (tid < INTSGD_MAX_WORKERS) lds.sat[tid] = 0ull;
-    __syncthreads();
-    if (*f.sat_hint != 0u) {              // something clipped (or first use): read the rows
-      // one wavefront per worker; every lane sums its share of the flagged workgroups'
-      // rows privately, so at most 64 LDS atomics per worker however much clipped
-      const uint32_t lane = tid & 63u;
-      for (uint32_t i = tid >> 6; i < f.n; i += kWaves) {
-        unsigned long long acc = 0ull;
-        for (uint32_t g = lane; g < f.workgroups; g += 64u)
-          if (f.sat_any[g] != 0u) acc += f.sat_rows[(uint64_t)g * f.n + i];
-        if (acc != 0ull) atomicAdd(&lds.sat[i], acc);
+    if (*f.sat_hint == f.launch_id) {
+      const uint64_t* row = f.sat_rows + (uint64_t)i * f.workgroups;
+      unsigned long long acc = 0ull;
+      uint32_t g = tid;
+      for (; g + 7u * kThreads < f.workgroups; g += 8u * kThreads) {
+        uint32_t flag[8];
+#pragma unroll
+        for (uint32_t u = 0; u < 8; ++u) flag[u] = f.sat_any[g + u * kThreads];
+#pragma unroll
+        for (uint32_t u = 0; u < 8; ++u)
+          if (flag[u] != 0u) acc += row[g + u * kThreads];
       }
+      for (; g < f.workgroups; g += kThreads)
+        if (f.sat_any[g] != 0u) acc += row[g];
+      if (acc != 0ull) atomicAdd(&lds.sat[0], acc);
     }
     __syncthreads();
-    if (tid < f.n) f.sat_count[tid] = lds.sat[tid];
-    if (tid == 0) *f.sat_hint = 0u;
+    if (tid == 0) f.sat_count[i] = lds.sat[0];
   }
 }
 
@@ -1112,7 +1121,7 @@ hipError_t finish(hipStream_t stream, const Finish& fin_in, bool with_norm, bool
     fin.norm_partial = fin.norm_mid;
     fin.num_tiles = chunks;
   }
-  const dim3 grid(with_norm ? fin.B : 1u), block(kThreads);
+  const dim3 grid((with_norm ? fin.B : 0u) + (with_sat ? fin.n : 0u)), block(kThreads);
   if (with_norm && with_sat) hipLaunchKernelGGL((k_finish<true, true>), grid, block, 0, stream, fin);
   else if (with_norm) hipLaunchKernelGGL((k_finish<true, false>), grid, block, 0, stream, fin);
   else hipLaunchKernelGGL((k_finish<false, true>), grid, block, 0, stream, fin);
