@@ -640,3 +640,95 @@ def test_heuristic_alpha_matches_oracle(shape, nb):
     P.intsgd_step_fused(desc, rows, d_a, 0.1, d_x, d_ns, d_cnt, ws)
     assert_within_ulp(host(d_x), out["x_new"], 1, "x")
     assert u64(d_cnt).tolist() == out["sat_count"].tolist()
+
+
+# --------------------------------------------------------------------------- more edge cases
+def _check_fused_step(d, n, offsets, rounding, L, g, x, alpha, seed=7, step=2, eta=0.1):
+    off_np = None if offsets is None else np.array(offsets, np.uint64)
+    out = oracle.step(list(g), alpha, x, rounding=rounding, L=L, eta=eta, seed=seed, step=step,
+                      offsets=off_np)
+    desc = P.Desc(d, n, rounding=rounding, clip=L, seed=seed, step=step, block_offsets=offsets)
+    ws = P.new_workspace(desc, DEV)
+    B = alpha.size
+    d_x = dev(x)
+    d_ns = torch.full((B,), -1.0, dtype=torch.float64, device=DEV)
+    d_cnt = torch.full((n,), -1, dtype=torch.int64, device=DEV)
+    P.intsgd_step_fused(desc, rows_on_device(g), dev(alpha), eta, d_x, d_ns, d_cnt, ws)
+    assert_within_ulp(host(d_x), out["x_new"], 1, "x")
+    assert u64(d_cnt).tolist() == out["sat_count"].tolist()
+    assert rel_err(host(d_ns), out["normsq"]) <= NORM_RTOL or np.allclose(host(d_ns), out["normsq"], atol=1e-300)
+    return out
+
+
+@pytest.mark.parametrize("rounding", [P.ROUND_NEAREST_EVEN, P.ROUND_STOCHASTIC])
+def test_tiny_vectors_max_workers_and_many_small_blocks(rounding):
+    rng = np.random.default_rng(71 + rounding)
+    # one coordinate, one worker
+    _check_fused_step(1, 1, None, rounding, 1000, np.array([[0.0123]], F32), np.array([0.5], F32),
+                      np.array([77.7], F32))
+    # the largest worker count the ABI takes, on a vector shorter than a quad and a longer one
+    for d in (3, 1031):
+        n = P.MAX_WORKERS
+        g = rng.normal(0, 0.01, (n, d)).astype(F32)
+        _check_fused_step(d, n, None, rounding, P.default_clip(n), g, rng.normal(0, 1, d).astype(F32),
+                          np.array([913.0], F32))
+    # 997 blocks of 1..9 coordinates: almost every tile is handled coordinate by coordinate
+    sizes = rng.integers(1, 10, 997)
+    offsets = [0] + np.cumsum(sizes).tolist()
+    d, n = offsets[-1], 3
+    alpha = rng.uniform(50, 2000, 997).astype(F32)
+    g = sprinkle_adversarial(rng, rng.normal(0, 0.01, (n, d)).astype(F32), 500.0)
+    out = _check_fused_step(d, n, offsets, rounding, 127, g, rng.normal(0, 1, d).astype(F32), alpha)
+    assert out["sat_count"].sum() > 0
+
+
+def test_single_worker_full_int32_range():
+    """n = 1 allows L = INT32_MAX: values at and beyond 2^31 saturate and are counted."""
+    vals = np.array([2147483520.0, 2147483648.0, -2147483648.0, -2147483904.0, 4e9, -4e9, 3.0e38,
+                     np.inf, -np.inf, np.nan, 1.5, -2.5, 0.0, 16777217.0], F32)
+    g = np.tile(vals, 40)[None, :]
+    d = g.shape[1]
+    for rounding in (0, 1):
+        out = _check_fused_step(d, 1, None, rounding, 2**31 - 1, g, np.zeros(d, F32),
+                                np.array([1.0], F32), eta=1e-9)
+        assert out["sat_count"][0] == 40 * 9
+
+
+def test_graph_replay_of_a_whole_step():
+    """A nearest-even step (sweep + final sums + alpha rule) captured in a HIP graph and
+    replayed with fresh gradients: every replay equals the eager result (no memset nodes,
+    no allocation, nothing zeroed between launches)."""
+    w = W.config(2).scaled(1_000_003)
+    desc = P.Desc(w.d, w.n, clip=w.clip)
+    P.intsgd_prepare(desc)
+    st_g = Stepper(desc, eta=w.eta, device=DEV)
+    st_e = Stepper(desc, eta=w.eta, device=DEV)
+    st_g.start(w.first_normsq)
+    st_e.start(w.first_normsq)
+    x_g = W.make_params(w, DEV)
+    x_e = x_g.clone()
+    buf, rows = W.make_gradients(w, 1, DEV)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        st_g.step_fused(rows, x_g, 1)            # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    x_g.copy_(x_e)
+    st_g.start(w.first_normsq)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        st_g.step_fused(rows, x_g, 1)
+    for k in range(1, 5):
+        fresh, fresh_rows = W.make_gradients(w, k, DEV)
+        buf.copy_(fresh)                          # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        st_e.step_fused(fresh_rows, x_e, k)
+        torch.cuda.synchronize()
+        assert torch.equal(x_g, x_e), "replay %d" % k
+        assert torch.equal(st_g.alpha, st_e.alpha) and torch.equal(st_g.r, st_e.r)
+        assert torch.equal(st_g.norm_sq, st_e.norm_sq)
+        assert torch.equal(st_g.sat_count, st_e.sat_count)
