@@ -127,11 +127,28 @@ __device__ __forceinline__ int32_t clamp_sym(int32_t q, int32_t L) {
   return r;
 }
 
+// Clip events are kept as wavefront lane masks: the compares below write an SGPR pair
+// directly, masks combine and are counted on the scalar unit, and no vector
+// instruction is spent on turning a per-lane flag back into a mask.
+typedef unsigned long long LaneMask;
+constexpr int kFcmpNotLess = 11;   // unordered or >=
+constexpr int kIcmpNotEqual = 33;
+
+__device__ __forceinline__ bool lane_in(LaneMask m) {
+  return ((m >> (threadIdx.x & 63u)) & 1ull) != 0ull;
+}
+
+__device__ __forceinline__ uint32_t count_lanes(LaneMask m0, LaneMask m1, LaneMask m2, LaneMask m3) {
+  if ((m0 | m1 | m2 | m3) == 0ull) return 0u;
+  return (uint32_t)(__builtin_popcountll(m0) + __builtin_popcountll(m1) +
+                    __builtin_popcountll(m2) + __builtin_popcountll(m3));
+}
+
 // Section 5.1 deterministic rounding (nearest, ties to even) of t = alpha*g, clipped
-// to [-L, L].  `sat` = the rounded value did not fit (or was not finite).
-__device__ __forceinline__ int32_t round_nearest_clip(float t, const RoundSpec& rs, bool& sat) {
+// to [-L, L].  `sat` = lanes whose rounded value did not fit (or was not finite).
+__device__ __forceinline__ int32_t round_nearest_clip(float t, const RoundSpec& rs, LaneMask& sat) {
   const float r = __builtin_rintf(t);
-  sat = !(__builtin_fabsf(r) < rs.sat_threshold);
+  sat = __builtin_amdgcn_fcmpf(__builtin_fabsf(r), rs.sat_threshold, kFcmpNotLess);
   return clamp_sym(cvt_i32_saturating(r), rs.clip);
 }
 
@@ -139,25 +156,22 @@ __device__ __forceinline__ int32_t round_nearest_clip(float t, const RoundSpec& 
 // draw u = (word>>8) 2^-24 rounds up iff u < p, evaluated as (word>>8) < p 2^24 (both
 // sides exact in fp32).
 __device__ __forceinline__ int32_t round_random_clip(float t, uint32_t word, const RoundSpec& rs,
-                                                     bool& sat) {
+                                                     LaneMask& sat) {
   const float f = __builtin_floorf(t);
   const float p = t - f;
   const bool up = (float)(word >> 8) < p * 16777216.0f;
   const int32_t q = cvt_i32_saturating(f) + (up ? 1 : 0);   // up is false whenever |f| >= 2^24
   const int32_t qc = clamp_sym(q, rs.clip);
-  sat = (qc != q) | !(__builtin_fabsf(f) < 2147483648.0f);
+  sat = __builtin_amdgcn_uicmp((uint32_t)qc, (uint32_t)q, kIcmpNotEqual) |
+        __builtin_amdgcn_fcmpf(__builtin_fabsf(f), 2147483648.0f, kFcmpNotLess);
   return qc;
 }
 
 template <int ROUND>
 __device__ __forceinline__ int32_t round_clip(float t, uint32_t word, const RoundSpec& rs,
-                                              bool& sat) {
+                                              LaneMask& sat) {
   if (ROUND == INTSGD_ROUND_STOCHASTIC) return round_random_clip(t, word, rs, sat);
   return round_nearest_clip(t, rs, sat);
-}
-
-__device__ __forceinline__ uint32_t count_lanes(bool pred) {
-  return (uint32_t)__popcll(__ballot(pred));
 }
 
 // ------------------------------------------------------------------ reductions
@@ -274,12 +288,12 @@ __device__ __forceinline__ void accumulate_workers(const WorkerPtrs& grads, uint
     vu4 rw = vu4{0u, 0u, 0u, 0u};
     if (ROUND == INTSGD_ROUND_STOCHASTIC)
       rw = philox4x32_10((uint32_t)quad, (uint32_t)(quad >> 32), i0 + w, rs.step, rs.key0, rs.key1);
-    bool s0, s1, s2, s3;
+    LaneMask s0, s1, s2, s3;
     S.x += round_clip<ROUND>(alpha * g[w].x, rw.x, rs, s0);
     S.y += round_clip<ROUND>(alpha * g[w].y, rw.y, rs, s1);
     S.z += round_clip<ROUND>(alpha * g[w].z, rw.z, rs, s2);
     S.w += round_clip<ROUND>(alpha * g[w].w, rw.w, rs, s3);
-    const uint32_t cnt = count_lanes(s0) + count_lanes(s1) + count_lanes(s2) + count_lanes(s3);
+    const uint32_t cnt = count_lanes(s0, s1, s2, s3);
     if (cnt != 0 && (threadIdx.x & 63u) == 0) atomicAdd(&lds_sat[i0 + w], (unsigned long long)cnt);
   }
 }
@@ -300,7 +314,7 @@ __device__ __forceinline__ vi4 aggregate_quad(const WorkerPtrs& grads, uint32_t 
 // One coordinate of one worker (head / tail of an unaligned tile).
 template <int ROUND>
 __device__ __forceinline__ int32_t compress_scalar(const void* g, uint64_t j, uint32_t worker,
-                                                   float alpha, const RoundSpec& rs, bool& sat) {
+                                                   float alpha, const RoundSpec& rs, LaneMask& sat) {
   const float gv = ((const float*)g)[j];
   uint32_t word = 0;
   if (ROUND == INTSGD_ROUND_STOCHASTIC) {
@@ -318,9 +332,9 @@ __device__ __forceinline__ int32_t aggregate_scalar(const WorkerPtrs& grads, uin
                                                     unsigned long long* lds_sat) {
   int32_t S = 0;
   for (uint32_t i = 0; i < n; ++i) {
-    bool sat;
+    LaneMask sat;
     S += compress_scalar<ROUND>(grads.p[i], j, i, alpha, rs, sat);
-    if (sat) atomicAdd(&lds_sat[i], 1ull);
+    if (lane_in(sat)) atomicAdd(&lds_sat[i], 1ull);
   }
   return S;
 }
@@ -663,9 +677,9 @@ struct DianaOp {
                                      a.rs.key0, a.rs.key1);
         word = pick_word(rw, (uint32_t)(j & 3));
       }
-      bool sat;
+      LaneMask sat;
       const int32_t q = round_clip<ROUND>(alpha * delta, word, a.rs, sat);
-      if (sat) atomicAdd(&lds.sat[i], 1ull);
+      if (lane_in(sat)) atomicAdd(&lds.sat[i], 1ull);
       hl[j] = shift_local(hv, q, inv_alpha);
       S += q;
     }
@@ -697,13 +711,13 @@ struct DianaOp {
       if (ROUND == INTSGD_ROUND_STOCHASTIC)
         rw = philox4x32_10((uint32_t)quad, (uint32_t)(quad >> 32), i0 + w, a.rs.step, a.rs.key0,
                            a.rs.key1);
-      bool s0, s1, s2, s3;
+      LaneMask s0, s1, s2, s3;
       vi4 q;
       q.x = round_clip<ROUND>(alpha * (g[w].x - hl[w].x), rw.x, a.rs, s0);
       q.y = round_clip<ROUND>(alpha * (g[w].y - hl[w].y), rw.y, a.rs, s1);
       q.z = round_clip<ROUND>(alpha * (g[w].z - hl[w].z), rw.z, a.rs, s2);
       q.w = round_clip<ROUND>(alpha * (g[w].w - hl[w].w), rw.w, a.rs, s3);
-      const uint32_t cnt = count_lanes(s0) + count_lanes(s1) + count_lanes(s2) + count_lanes(s3);
+      const uint32_t cnt = count_lanes(s0, s1, s2, s3);
       if (cnt != 0 && (threadIdx.x & 63u) == 0)
         atomicAdd(&lds.sat[i0 + w], (unsigned long long)cnt);
       const vf4 hn = vf4{shift_local(hl[w].x, q.x, inv_alpha), shift_local(hl[w].y, q.y, inv_alpha),
@@ -873,11 +887,11 @@ struct CompressOp {
       : a(args), lds(l), worker(w), g(args.grads.p[w]), q(args.q_out.p[w]), alpha(0.f), q0(0) {}
   __device__ __forceinline__ void begin_tile(uint32_t blk) { alpha = a.alpha[blk]; }
   __device__ __forceinline__ void scalar(uint64_t j) {
-    bool sat;
+    LaneMask sat;
     const int32_t v = compress_scalar<ROUND>(g, j, worker, alpha, a.rs, sat);
     if (WIRE == INTSGD_WIRE_INT8) ((int8_t*)q)[j] = (int8_t)v;
     else ((int32_t*)q)[j] = v;
-    if (sat) atomicAdd(&lds.sat[0], 1ull);
+    if (lane_in(sat)) atomicAdd(&lds.sat[0], 1ull);
   }
   __device__ __forceinline__ void begin_body(uint64_t first_quad, uint32_t quads) {
     q0 = first_quad;
@@ -892,13 +906,13 @@ struct CompressOp {
     if (ROUND == INTSGD_ROUND_STOCHASTIC)
       rw = philox4x32_10((uint32_t)quad, (uint32_t)(quad >> 32), worker, a.rs.step, a.rs.key0,
                          a.rs.key1);
-    bool s0, s1, s2, s3;
+    LaneMask s0, s1, s2, s3;
     vi4 v;
     v.x = round_clip<ROUND>(alpha * gv.x, rw.x, a.rs, s0);
     v.y = round_clip<ROUND>(alpha * gv.y, rw.y, a.rs, s1);
     v.z = round_clip<ROUND>(alpha * gv.z, rw.z, a.rs, s2);
     v.w = round_clip<ROUND>(alpha * gv.w, rw.w, a.rs, s3);
-    const uint32_t cnt = count_lanes(s0) + count_lanes(s1) + count_lanes(s2) + count_lanes(s3);
+    const uint32_t cnt = count_lanes(s0, s1, s2, s3);
     if (cnt != 0 && (threadIdx.x & 63u) == 0) atomicAdd(&lds.sat[0], (unsigned long long)cnt);
     if (WIRE == INTSGD_WIRE_INT8) {
       const uint32_t packed = ((uint32_t)v.x & 0xFFu) | (((uint32_t)v.y & 0xFFu) << 8) |
