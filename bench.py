@@ -36,6 +36,8 @@ def parse():
     ap.add_argument("--grid", type=int, default=0)
     ap.add_argument("--wgs-per-cu", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-threads", type=int, default=1,
+                    help="threads for the oracle baseline (each runs the unchanged oracle on a slice)")
     ap.add_argument("--no-taps", action="store_true",
                     help="do not record per-kernel events (roofline numbers are then null)")
     ap.add_argument("--global-alpha", action="store_true", help="config 4 with one alpha")
@@ -48,10 +50,14 @@ def parse():
     return ap.parse_args()
 
 
-def cpu_baseline(w, rows, alpha_host, x_host, max_wc=420_000_000, steps=4):
-    """The oracle as it stands, single-threaded, on a bounded sample of the same workload:
-    `steps` consecutive steps on the leading slice of at most max_wc worker-coordinates
-    (the whole vector when it is small enough); reported in the metric's unit."""
+def cpu_baseline(w, rows, alpha_host, x_host, max_wc=420_000_000, steps=4, threads=1):
+    """The oracle as it stands on a bounded sample of the same workload: `steps`
+    consecutive steps on the leading slice of at most max_wc worker-coordinates (the whole
+    vector when it is small enough); reported in the metric's unit.  One thread by default;
+    with threads > 1 the coordinate range is cut into that many slices and each thread
+    calls the unchanged oracle on its slice (coordinates are independent, norms add)."""
+    from concurrent.futures import ThreadPoolExecutor
+
     import numpy as np
 
     import oracle
@@ -60,18 +66,32 @@ def cpu_baseline(w, rows, alpha_host, x_host, max_wc=420_000_000, steps=4):
     if w.block_offsets is not None:
         off = np.array(w.block_offsets, np.uint64)
     g = [r[:ln].cpu().numpy() for r in rows]
-    x = x_host[:ln]
+    x = x_host[:ln].copy()
     alpha = alpha_host
     r = np.zeros(w.num_blocks)
+    threads = max(1, min(int(threads), ln // 4096))
+    cuts = [(ln * i // threads) & ~3 for i in range(threads)] + [ln]
+
+    def one_slice(i, k, xk, a):
+        lo, hi = cuts[i], cuts[i + 1]
+        return oracle.step([gi[lo:hi] for gi in g], a, xk[lo:hi], rounding=w.rounding, L=w.clip,
+                           eta=w.eta, seed=w.philox_seed, step=k, j0=lo, offsets=off)
+
+    pool = ThreadPoolExecutor(threads) if threads > 1 else None
     t0 = time.perf_counter()
     for k in range(1, steps + 1):
-        out = oracle.step(g, alpha, x, rounding=w.rounding, L=w.clip, eta=w.eta,
-                          seed=w.philox_seed, step=k, offsets=off)
-        x = out["x_new"]
-        r, _, alpha, _ = oracle.next_alpha(out["normsq"], r, d=w.d, n=w.n, beta=w.beta, eps=w.eps,
+        if pool is None:
+            outs = [one_slice(0, k, x, alpha)]
+        else:
+            outs = list(pool.map(lambda i: one_slice(i, k, x, alpha), range(threads)))
+        x = outs[0]["x_new"] if threads == 1 else np.concatenate([o["x_new"] for o in outs])
+        normsq = sum(o["normsq"] for o in outs)
+        r, _, alpha, _ = oracle.next_alpha(normsq, r, d=w.d, n=w.n, beta=w.beta, eps=w.eps,
                                            eta=w.eta, offsets=off)
     dt = time.perf_counter() - t0
-    return {"value": 4.0 * w.n * ln * steps / dt / 1e9, "unit": "GB/s", "cores": 1,
+    if pool is not None:
+        pool.shutdown()
+    return {"value": 4.0 * w.n * ln * steps / dt / 1e9, "unit": "GB/s", "cores": threads,
             "kind": "oracle",
             "sample": "%d steps on the first %d of %d coordinates x %d workers (%.1f s)" % (
                 steps, ln, w.d, w.n, dt)}
@@ -251,7 +271,7 @@ def main():
         },
     }
     if not args.no_cpu_baseline and not args.momentum and not args.diana:
-        result["cpu_baseline"] = cpu_baseline(w, sets[0][1], alpha0, x0)
+        result["cpu_baseline"] = cpu_baseline(w, sets[0][1], alpha0, x0, threads=args.cpu_threads)
     print(json.dumps(result))
 
 
