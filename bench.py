@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--no-taps", action="store_true",
                     help="do not record per-kernel events (roofline numbers are then null)")
     ap.add_argument("--global-alpha", action="store_true", help="config 4 with one alpha")
+    ap.add_argument("--rounding", default="config", choices=["config", "nearest", "stochastic"],
+                    help="override the workload's rounding mode")
     ap.add_argument("--heuristic", action="store_true",
                     help="Heuristic IntSGD: a profiling pass (max |g|) sets alpha before every step")
     ap.add_argument("--diana", action="store_true",
@@ -158,7 +160,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    w = W.config(args.config, per_bucket=not args.global_alpha)
+    rounding = {"config": None, "nearest": 0, "stochastic": 1}[args.rounding]
+    w = W.config(args.config, per_bucket=not args.global_alpha, rounding=rounding)
     P.intsgd_set_tuning(args.tile, args.grid, args.wgs_per_cu)
     tile, grid, wgs_per_cu = P.intsgd_get_tuning()
 

@@ -86,7 +86,17 @@ def _int32_clip(n):
     return (2 ** 31 - 1) // n
 
 
-def config(config_id: int, per_bucket: bool = True) -> Workload:
+def config(config_id: int, per_bucket: bool = True, rounding: Optional[int] = None) -> Workload:
+    """Workload `config_id`; `rounding` overrides the recipe's rounding mode (workload 4 does
+    not name one: randomized is its default here, nearest-even the variant)."""
+    w = _config(config_id, per_bucket)
+    if rounding is not None and rounding != w.rounding:
+        suffix = "-stochastic" if rounding == ROUND_STOCHASTIC else "-nearest-even"
+        w = replace(w, rounding=rounding, name=w.name + suffix)
+    return w
+
+
+def _config(config_id: int, per_bucket: bool) -> Workload:
     eta = 0.1
     if config_id == 1:
         d, n = 1_048_576, 4

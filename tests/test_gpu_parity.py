@@ -313,6 +313,14 @@ def test_config4_global_alpha_variant():
     lockstep_run(w, steps=4)
 
 
+def test_config4_nearest_even_variant():
+    """Workload 4 does not name a rounding mode: the other one, per bucket and global."""
+    w = W.config(4, rounding=0).scaled(scaled_blocks(0)[-1], block_offsets=scaled_blocks(0))
+    lockstep_run(w, steps=4)
+    w = W.config(4, per_bucket=False, rounding=0).scaled(scaled_blocks(0)[-1])
+    lockstep_run(w, steps=4)
+
+
 def test_config1_full_size():
     lockstep_run(W.config(1), steps=1, free_running=False)
 
@@ -372,6 +380,10 @@ def sampled_check(w: W.Workload, steps, slices_per_step=48, slice_len=8192):
 
 def test_config4_full_size_sampled():
     sampled_check(W.config(4), steps=2)
+
+
+def test_config4_full_size_sampled_nearest_even():
+    sampled_check(W.config(4, rounding=0), steps=1)
 
 
 def test_config5_full_size_sampled():
