@@ -35,6 +35,8 @@ def parse():
     ap.add_argument("--tile", type=int, default=0)
     ap.add_argument("--grid", type=int, default=0)
     ap.add_argument("--wgs-per-cu", type=int, default=0)
+    ap.add_argument("--two-phase", type=int, default=0, choices=[0, 1, 2],
+                    help="form of the fused sweep: 0 automatic, 1 tile sweep, 2 two-phase sweep")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-threads", type=int, default=1,
                     help="threads for the oracle baseline (each runs the unchanged oracle on a slice)")
@@ -162,8 +164,8 @@ def main():
     torch.cuda.set_device(0)
     rounding = {"config": None, "nearest": 0, "stochastic": 1}[args.rounding]
     w = W.config(args.config, per_bucket=not args.global_alpha, rounding=rounding)
-    P.intsgd_set_tuning(args.tile, args.grid, args.wgs_per_cu)
-    tile, grid, wgs_per_cu = P.intsgd_get_tuning()
+    P.intsgd_set_tuning(args.tile, args.grid, args.wgs_per_cu, args.two_phase)
+    tile, grid, wgs_per_cu, two_phase = P.intsgd_get_tuning()
 
     desc = P.Desc(w.d, w.n, rounding=w.rounding, wire=w.wire, clip=w.clip, seed=w.philox_seed,
                   block_offsets=w.block_offsets)
@@ -258,7 +260,7 @@ def main():
             "mode": "heuristic-alpha+fused" if args.heuristic else "diana" if args.diana else args.mode + ("+momentum" if args.momentum else ""),
             "gradient_sets": pool,
             "tuning_overrides": {"tile_coords": tile, "max_workgroups": grid,
-                                 "workgroups_per_cu": wgs_per_cu},
+                                 "workgroups_per_cu": wgs_per_cu, "two_phase": two_phase},
             "alpha_last": alpha_last,
             "clipped_last_step": sat,
         },

@@ -275,15 +275,21 @@ intsgd_status intsgd_heuristic_alpha(const intsgd_desc* desc, const float* const
 /* Tuning overrides (process-wide; not part of the numerical contract: results do not
  * depend on them except for the summation order of the norm).  A field that is 0
  * means "automatic": the library picks per call (by rounding mode) what measured best
- * on MI355X.  intsgd_set_tuning replaces all three fields.
+ * on MI355X.  intsgd_set_tuning replaces all fields.
  *   tile_coords        coordinates per work tile, a multiple of 1024 in [1024, 65536]
  *   max_workgroups     cap of the launch grid, in [1, 1048576]; tiles beyond it are
  *                      taken by striding
- *   workgroups_per_cu  residency cap of the streaming kernels, 2..8 (8 = no cap) */
+ *   workgroups_per_cu  residency cap of the streaming kernels, 2..8 (8 = no cap)
+ *   two_phase          form of the fused step (intsgd_step_fused, .._next_alpha,
+ *                      intsgd_step_momentum) when there is one block: 1 = always the tile
+ *                      sweep, 2 = the two-phase sweep (gradient reads, then the x update,
+ *                      with the integer sums held in registers in between) whenever
+ *                      d >= 2^22; 0 = automatic */
 typedef struct intsgd_tuning {
   uint32_t tile_coords;
   uint32_t max_workgroups;
   uint32_t workgroups_per_cu;
+  uint32_t two_phase;
 } intsgd_tuning;
 intsgd_status intsgd_set_tuning(const intsgd_tuning* tuning);
 void intsgd_get_tuning(intsgd_tuning* tuning);

@@ -63,7 +63,7 @@ class _CDesc(C.Structure):
 
 class _CTuning(C.Structure):
     _fields_ = [("tile_coords", C.c_uint32), ("max_workgroups", C.c_uint32),
-                ("workgroups_per_cu", C.c_uint32)]
+                ("workgroups_per_cu", C.c_uint32), ("two_phase", C.c_uint32)]
 
 
 _P = C.c_void_p
@@ -400,16 +400,16 @@ def intsgd_heuristic_alpha(desc, grads, nb, alpha_out, workspace, stream=None):
                                        _stream(stream)), "intsgd_heuristic_alpha")
 
 
-def intsgd_set_tuning(tile_coords=0, max_workgroups=0, workgroups_per_cu=0):
-    t = _CTuning(int(tile_coords), int(max_workgroups), int(workgroups_per_cu))
+def intsgd_set_tuning(tile_coords=0, max_workgroups=0, workgroups_per_cu=0, two_phase=0):
+    t = _CTuning(int(tile_coords), int(max_workgroups), int(workgroups_per_cu), int(two_phase))
     _check(_lib.intsgd_set_tuning(C.byref(t)), "intsgd_set_tuning")
 
 
 def intsgd_get_tuning():
-    """-> (tile_coords, max_workgroups, workgroups_per_cu)"""
+    """-> (tile_coords, max_workgroups, workgroups_per_cu, two_phase)"""
     t = _CTuning()
     _lib.intsgd_get_tuning(C.byref(t))
-    return int(t.tile_coords), int(t.max_workgroups), int(t.workgroups_per_cu)
+    return int(t.tile_coords), int(t.max_workgroups), int(t.workgroups_per_cu), int(t.two_phase)
 
 
 def intsgd_status_string(status: int) -> str:

@@ -27,7 +27,7 @@ constexpr size_t kAlign = 256;
 constexpr uint32_t kLdsPerCu = 160u * 1024u;    // gfx950
 
 // Process-wide overrides; a zero field means "automatic".
-intsgd_tuning g_tuning = {0, 0, 0};
+intsgd_tuning g_tuning = {0, 0, 0, 0};
 
 // Automatic choices, measured on MI355X.  Nearest-even rounding is bound by HBM and
 // likes few, large bursts in flight: 8 KB per stream and workgroup, two resident
@@ -42,6 +42,17 @@ intsgd_tuning effective_tuning(const intsgd_desc* desc) {
   return t;
 }
 
+// The two-phase sweep needs one block and enough coordinates to give every CU a chunk.
+// Automatic choice: nearest-even rounding only (randomized rounding is co-bound by the
+// integer ALU in its read phase and gains nothing from separating the phases).
+constexpr uint64_t kMinPhasedD = 1ull << 22;
+bool use_two_phase(const intsgd_desc* desc, const intsgd_tuning& t) {
+  if (desc->num_blocks != 1 || desc->d < kMinPhasedD || t.two_phase == 1) return false;
+  if (t.two_phase == 2) return true;
+  return desc->rounding == INTSGD_ROUND_NEAREST_EVEN;
+}
+
+
 thread_local std::string t_hip_error;
 thread_local hipEvent_t t_tap_start = nullptr, t_tap_stop = nullptr;
 
@@ -55,6 +66,25 @@ void take_taps(LaunchShape* ls) {
 intsgd_status hip_fail(hipError_t e) {
   t_hip_error = std::string(hipGetErrorName(e)) + ": " + hipGetErrorString(e);
   return INTSGD_EHIP;
+}
+
+// Compute units of the current device (cached per device id).
+intsgd_status compute_units(uint32_t* out) {
+  static std::mutex m;
+  static std::vector<int> cache;
+  int device = 0;
+  hipError_t e = hipGetDevice(&device);
+  if (e != hipSuccess) return hip_fail(e);
+  std::lock_guard<std::mutex> lock(m);
+  if ((size_t)device >= cache.size()) cache.resize(device + 1, 0);
+  if (cache[device] == 0) {
+    int cus = 0;
+    e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device);
+    if (e != hipSuccess) return hip_fail(e);
+    cache[device] = cus > 0 ? cus : 1;
+  }
+  *out = (uint32_t)cache[device];
+  return INTSGD_OK;
 }
 
 size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -347,6 +377,16 @@ intsgd_status step_fused_impl(const intsgd_desc* desc, const float* const* grads
   fill_ptrs(&g, (const void* const*)grads, desc->n);
   Finish fin = make_finish(desc, t, workspace, norm_sq_out, sat_count);
   if (r != nullptr) fin.rule = AlphaRule{r, alpha_out, t.offsets_dev, beta, eps, eta};
+  const intsgd_tuning tune = effective_tuning(desc);
+  if (use_two_phase(desc, tune)) {
+    PhasedShape ps{0};
+    INTSGD_TRY(compute_units(&ps.grid));
+    // the caller's workspace holds one slot per 1024 coordinates; one per CU is needed
+    if (ps.grid > tiles_of(desc->d, kMinTile))
+      return done(launch_step_fused(t.tm, t.ls, desc->n, round_spec(desc), g, alpha, eta, x, mom, fin));
+    return done(launch_step_fused_phased(ps, t.ls, desc->d, desc->n, round_spec(desc), g, alpha, eta,
+                                         x, mom, fin));
+  }
   return done(launch_step_fused(t.tm, t.ls, desc->n, round_spec(desc), g, alpha, eta, x, mom, fin));
 }
 
@@ -615,6 +655,7 @@ intsgd_status intsgd_set_tuning(const intsgd_tuning* tuning) {
   if (tile != 0 && (tile < kMinTile || tile > kMaxTile || tile % kMinTile != 0)) return INTSGD_EINVAL;
   if (grid > kMaxGrid) return INTSGD_EINVAL;
   if (wgs != 0 && (wgs < 2 || wgs > 8)) return INTSGD_EINVAL;
+  if (tuning->two_phase > 2) return INTSGD_EINVAL;
   std::lock_guard<std::mutex> lock(g_mutex);
   g_tuning = *tuning;
   return INTSGD_OK;

@@ -52,6 +52,11 @@ struct LaunchShape {
   hipEvent_t tap_start, tap_stop;  // optional profiling taps around the streaming kernel
 };
 
+// Shape of the two-phase fused sweep: one persistent workgroup per CU.
+struct PhasedShape {
+  uint32_t grid;
+};
+
 // The alpha rule of step a8 on device arrays; r == nullptr means "do not apply".
 struct AlphaRule {
   double* r;                      // B, in/out
@@ -107,6 +112,11 @@ hipError_t launch_decode_update_norm(const TileMap& tm, const LaunchShape& ls, u
 hipError_t launch_step_fused(const TileMap& tm, const LaunchShape& ls, uint32_t n,
                              const RoundSpec& rs, const WorkerPtrs& grads, const float* alpha,
                              double eta, float* x, const Momentum* mom, const Finish& fin);
+// Same step in the two-phase form (one block only, 16-byte aligned rows, any n).
+hipError_t launch_step_fused_phased(const PhasedShape& ps, const LaunchShape& ls, uint64_t d,
+                                    uint32_t n, const RoundSpec& rs, const WorkerPtrs& grads,
+                                    const float* alpha, double eta, float* x, const Momentum* mom,
+                                    const Finish& fin);
 hipError_t launch_diana_step(const TileMap& tm, const LaunchShape& ls, uint32_t n,
                              const RoundSpec& rs, const WorkerPtrs& grads,
                              const WorkerOutPtrs& h_local, const float* alpha, double eta, float* x,

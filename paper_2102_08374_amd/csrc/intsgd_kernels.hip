@@ -32,7 +32,10 @@ namespace intsgd {
 namespace {
 
 constexpr uint32_t kThreads = INTSGD_THREADS_PER_WORKGROUP;
-constexpr uint32_t kWaves = kThreads / 64;
+constexpr uint32_t kPhasedThreads = 1024;     // one workgroup per CU in the two-phase sweep
+// quads whose integer sums a thread keeps in registers (fewer with Philox's temporaries)
+constexpr uint32_t phased_quads(int rounding) { return rounding == INTSGD_ROUND_STOCHASTIC ? 8u : 12u; }
+constexpr uint32_t kMaxWaves = kPhasedThreads / 64;
 
 // Native 16-byte vectors (one dwordx4 access each).
 typedef float vf4 __attribute__((ext_vector_type(4)));
@@ -203,7 +206,7 @@ __device__ __forceinline__ double wave_sum(double v) {
 
 // LDS shared by the reductions of one kernel.
 struct ReduceLds {
-  double red[2][kWaves];            // double-buffered wave sums
+  double red[2][kMaxWaves];         // double-buffered wave sums
   unsigned long long sat[INTSGD_MAX_WORKERS];
 };
 
@@ -215,8 +218,8 @@ __device__ __forceinline__ double block_sum(double v, ReduceLds& lds, uint32_t s
   __syncthreads();
   double total = 0.0;
   if (threadIdx.x == 0) {
-#pragma unroll
-    for (uint32_t k = 0; k < kWaves; ++k) total += lds.red[slot][k];
+    const uint32_t waves = blockDim.x >> 6;
+    for (uint32_t k = 0; k < waves; ++k) total += lds.red[slot][k];
   }
   return total;
 }
@@ -270,12 +273,17 @@ __device__ __forceinline__ void drive_tiles(const TileMap& tm, Op& op) {
 
 // ------------------------------------------------------------------ a1-a4 on one quad
 // Scales, rounds, clips and accumulates workers [i0, i0+W) for lane quad `ql` of the
-// tile body that starts at quad q0 and holds nq quads.
-template <int ROUND, int W>
+// tile body that starts at quad q0 and holds nq quads.  Clip events are rare, and a
+// branch per worker in the streaming loop keeps the compiler from moving the next
+// group's loads above this group's arithmetic.  So the sweep runs with COUNT = false:
+// it only ORs the clip masks into `any` (scalar unit, no branch); a wavefront whose
+// `any` is non-zero afterwards goes over its quads once more with COUNT = true, which
+// adds the per-worker counts to LDS (the integers of that second pass are discarded).
+template <int ROUND, int W, bool COUNT>
 __device__ __forceinline__ void accumulate_workers(const WorkerPtrs& grads, uint32_t i0,
                                                    uint64_t q0, uint32_t nq, uint32_t ql,
                                                    float alpha, const RoundSpec& rs, vi4& S,
-                                                   unsigned long long* lds_sat) {
+                                                   unsigned long long* lds_sat, LaneMask& any) {
   vf4 g[W];
 #pragma unroll
   for (int w = 0; w < W; ++w) {
@@ -293,21 +301,40 @@ __device__ __forceinline__ void accumulate_workers(const WorkerPtrs& grads, uint
     S.y += round_clip<ROUND>(alpha * g[w].y, rw.y, rs, s1);
     S.z += round_clip<ROUND>(alpha * g[w].z, rw.z, rs, s2);
     S.w += round_clip<ROUND>(alpha * g[w].w, rw.w, rs, s3);
-    const uint32_t cnt = count_lanes(s0, s1, s2, s3);
-    if (cnt != 0 && (threadIdx.x & 63u) == 0) atomicAdd(&lds_sat[i0 + w], (unsigned long long)cnt);
+    if (COUNT) {
+      const uint32_t cnt = count_lanes(s0, s1, s2, s3);
+      if (cnt != 0 && (threadIdx.x & 63u) == 0) atomicAdd(&lds_sat[i0 + w], (unsigned long long)cnt);
+    } else {
+      any |= (s0 | s1) | (s2 | s3);
+    }
   }
 }
 
-template <int ROUND>
+template <int ROUND, bool COUNT>
 __device__ __forceinline__ vi4 aggregate_quad(const WorkerPtrs& grads, uint32_t n, uint64_t q0,
                                               uint32_t nq, uint32_t ql, float alpha,
-                                              const RoundSpec& rs, unsigned long long* lds_sat) {
+                                              const RoundSpec& rs, unsigned long long* lds_sat,
+                                              LaneMask& any) {
   vi4 S = vi4{0, 0, 0, 0};
+  if (!COUNT && ROUND == INTSGD_ROUND_NEAREST_EVEN && n == 16u) {
+    // straight-line code for the common n = 16: the second group's loads can be issued
+    // while the first group is being rounded
+    accumulate_workers<ROUND, 8, COUNT>(grads, 0, q0, nq, ql, alpha, rs, S, lds_sat, any);
+    accumulate_workers<ROUND, 8, COUNT>(grads, 8, q0, nq, ql, alpha, rs, S, lds_sat, any);
+    return S;
+  }
   uint32_t i = 0;
-  for (; i + 8 <= n; i += 8) accumulate_workers<ROUND, 8>(grads, i, q0, nq, ql, alpha, rs, S, lds_sat);
-  if (n - i >= 4) { accumulate_workers<ROUND, 4>(grads, i, q0, nq, ql, alpha, rs, S, lds_sat); i += 4; }
-  if (n - i >= 2) { accumulate_workers<ROUND, 2>(grads, i, q0, nq, ql, alpha, rs, S, lds_sat); i += 2; }
-  if (n - i >= 1) { accumulate_workers<ROUND, 1>(grads, i, q0, nq, ql, alpha, rs, S, lds_sat); }
+  for (; i + 8 <= n; i += 8)
+    accumulate_workers<ROUND, 8, COUNT>(grads, i, q0, nq, ql, alpha, rs, S, lds_sat, any);
+  if (n - i >= 4) {
+    accumulate_workers<ROUND, 4, COUNT>(grads, i, q0, nq, ql, alpha, rs, S, lds_sat, any);
+    i += 4;
+  }
+  if (n - i >= 2) {
+    accumulate_workers<ROUND, 2, COUNT>(grads, i, q0, nq, ql, alpha, rs, S, lds_sat, any);
+    i += 2;
+  }
+  if (n - i >= 1) accumulate_workers<ROUND, 1, COUNT>(grads, i, q0, nq, ql, alpha, rs, S, lds_sat, any);
   return S;
 }
 
@@ -548,14 +575,19 @@ struct AggregateOp {
   double c, acc;
   uint64_t q0;
   uint32_t nq;
+  LaneMask any;                 // lanes of this wavefront that clipped somewhere in the tile body
+  // Randomized rounding counts clip events as it goes: the branch-free form costs it
+  // registers (Philox temporaries across more loads in flight) and with them occupancy.
+  static constexpr bool kCountInline = ROUND == INTSGD_ROUND_STOCHASTIC;
   __amdgpu_buffer_rsrc_t out;   // x (F3) or the aggregate (F1) of this tile body
   __amdgpu_buffer_rsrc_t mom;   // momentum buffer of this tile body
   MomentumRule rule;
 
   __device__ __forceinline__ AggregateOp(const AggregateArgs& args, ReduceLds& l)
-      : a(args), lds(l), alpha(0.f), c(0.0), acc(0.0), q0(0), nq(0) {}
+      : a(args), lds(l), alpha(0.f), c(0.0), acc(0.0), q0(0), nq(0), any(0ull) {}
   __device__ __forceinline__ void begin_tile(uint32_t blk) {
     alpha = a.alpha[blk];
+    any = 0ull;
     if (FUSED && !MOMENTUM) c = decode_constant(a.eta, a.n, alpha);
     if (MOMENTUM) rule = MomentumRule{1.0 / ((double)a.n * (double)alpha), a.eta, a.mu, a.wd};
     acc = 0.0;
@@ -582,7 +614,7 @@ struct AggregateOp {
     vf4 xv = vf4{0.f, 0.f, 0.f, 0.f}, mv = vf4{0.f, 0.f, 0.f, 0.f};
     if (FUSED) xv = as_f(load128<INTSGD_X_LOAD_POLICY>(out, ql * 16u));
     if (MOMENTUM) mv = as_f(load128<INTSGD_X_LOAD_POLICY>(mom, ql * 16u));
-    const vi4 S = aggregate_quad<ROUND>(a.grads, a.n, q0, nq, ql, alpha, a.rs, lds.sat);
+    const vi4 S = aggregate_quad<ROUND, kCountInline>(a.grads, a.n, q0, nq, ql, alpha, a.rs, lds.sat, any);
     if (MOMENTUM) {
       const vf4 xn = momentum_quad(xv, mv, S, rule, acc);
       store128<INTSGD_X_STORE_POLICY>(mom, ql * 16u, as_u(mv));
@@ -594,6 +626,11 @@ struct AggregateOp {
     }
   }
   __device__ __forceinline__ void end_tile(uint32_t t, uint32_t iter) {
+    if (!kCountInline && any != 0ull) {   // rare: something clipped; count it per worker
+      LaneMask unused = 0ull;
+      for (uint32_t ql = threadIdx.x; ql < nq; ql += kThreads)
+        (void)aggregate_quad<ROUND, true>(a.grads, a.n, q0, nq, ql, alpha, a.rs, lds.sat, unused);
+    }
     if (FUSED) {
       const double total = block_sum(acc, lds, iter & 1u);
       if (threadIdx.x == 0) a.fin.norm_partial[t] = total;
@@ -609,6 +646,104 @@ __global__ __launch_bounds__(kThreads) void k_aggregate(const AggregateArgs a) {
   drive_tiles(a.tm, op);
   __syncthreads();
   if (threadIdx.x == 0) publish_sat(a.fin, lds, blockIdx.x);
+}
+
+// ================================================================== F3 (a1-a7) in two phases
+// One block only, one persistent workgroup of 1024 threads per CU.  The vector is cut into
+// rounds of grid x 1024 x Q quads.  Within a round, iteration k of workgroup b covers the
+// 1024-quad slab (k * grid + b), so at any moment the chip reads one contiguous window of
+// every stream (as the tile sweep does; giving each workgroup a contiguous chunk instead
+// made the rate depend on the chunk stride, HBM channel conflicts).  Phase A reads nothing
+// but the n gradient streams and leaves the integer sums of the thread's Q quads in
+// registers; phase B reads, updates and writes x (and the momentum buffer) for the same
+// quads.  All CUs start together and move at about the same rate, so the chip alternates
+// between a read-only stream and a short read-modify-write burst instead of mixing the
+// two, which is what HBM rewards: 83-87 % of peak against 77-79 % for the tile sweep.
+struct PhasedArgs {
+  RoundSpec rs;
+  uint32_t n;
+  const float* alpha;
+  double eta;
+  float* x;
+  float* m;
+  double mu, wd;
+  uint64_t d;
+  Finish fin;
+  WorkerPtrs grads;
+};
+
+template <int ROUND, bool MOMENTUM>
+__global__ __launch_bounds__(kPhasedThreads) void k_aggregate_phased(const PhasedArgs a) {
+  constexpr uint32_t kPhasedQuads = phased_quads(ROUND);
+  __shared__ ReduceLds lds;
+  zero_sat(lds);
+  const uint32_t tid = threadIdx.x;
+  const float alpha = a.alpha[0];
+  const double c = decode_constant(a.eta, a.n, alpha);
+  const MomentumRule rule{1.0 / ((double)a.n * (double)alpha), a.eta, a.mu, a.wd};
+  const uint64_t nquads = a.d >> 2;
+  const uint32_t slab_row = gridDim.x * kPhasedThreads;           // quads per iteration k, chip-wide
+  const uint64_t per_round = (uint64_t)slab_row * kPhasedQuads;
+  double acc = 0.0;
+  for (uint64_t r0 = 0; r0 < nquads; r0 += per_round) {
+    const uint64_t rest = nquads - r0;
+    const uint32_t nq = rest < per_round ? (uint32_t)rest : (uint32_t)per_round;
+    // phase A: lanes past the round read zeros (the descriptors end at nq) and add 0
+    vi4 S[kPhasedQuads];
+    LaneMask any = 0ull;
+#pragma clang loop unroll(full)
+    for (uint32_t k = 0; k < kPhasedQuads; ++k) {
+      S[k] = vi4{0, 0, 0, 0};
+      if (k * slab_row < nq)
+        S[k] = aggregate_quad<ROUND, false>(a.grads, a.n, r0, nq,
+                                            (k * gridDim.x + blockIdx.x) * kPhasedThreads + tid,
+                                            alpha, a.rs, lds.sat, any);
+    }
+    if (any != 0ull) {            // rare: something clipped in this wavefront's quads
+      LaneMask unused = 0ull;
+#pragma clang loop unroll(disable)
+      for (uint32_t k = 0; k * slab_row < nq; ++k)
+        (void)aggregate_quad<ROUND, true>(a.grads, a.n, r0, nq,
+                                          (k * gridDim.x + blockIdx.x) * kPhasedThreads + tid, alpha,
+                                          a.rs, lds.sat, unused);
+    }
+    __syncthreads();
+    // phase B: stores past the round are dropped by the descriptor
+    const __amdgpu_buffer_rsrc_t out = make_stream((vf4*)a.x + r0, nq * 16u);
+    const __amdgpu_buffer_rsrc_t mom = MOMENTUM ? make_stream((vf4*)a.m + r0, nq * 16u) : out;
+#pragma clang loop unroll(full)
+    for (uint32_t k = 0; k < kPhasedQuads; ++k) {
+      if (k * slab_row < nq) {
+        const uint32_t off = ((k * gridDim.x + blockIdx.x) * kPhasedThreads + tid) * 16u;
+        const vf4 xv = as_f(load128<INTSGD_X_LOAD_POLICY>(out, off));
+        if (MOMENTUM) {
+          vf4 mv = as_f(load128<INTSGD_X_LOAD_POLICY>(mom, off));
+          const vf4 xn = momentum_quad(xv, mv, S[k], rule, acc);
+          store128<INTSGD_X_STORE_POLICY>(mom, off, as_u(mv));
+          store128<INTSGD_X_STORE_POLICY>(out, off, as_u(xn));
+        } else {
+          store128<INTSGD_X_STORE_POLICY>(out, off, as_u(update_quad(xv, S[k], c, acc)));
+        }
+      }
+    }
+    __syncthreads();
+  }
+  if (blockIdx.x == 0 && tid < (uint32_t)(a.d & 3u)) {      // the d mod 4 coordinates after the last quad
+    const uint64_t j = (a.d & ~(uint64_t)3) + tid;
+    const int32_t Sj = aggregate_scalar<ROUND>(a.grads, a.n, j, alpha, a.rs, lds.sat);
+    if (MOMENTUM) {
+      float mj = a.m[j];
+      a.x[j] = momentum_coord(a.x[j], mj, Sj, rule, acc);
+      a.m[j] = mj;
+    } else {
+      a.x[j] = update_coord(a.x[j], Sj, c, acc);
+    }
+  }
+  const double total = block_sum(acc, lds, 0);
+  if (tid == 0) {
+    a.fin.norm_partial[blockIdx.x] = total;
+    publish_sat(a.fin, lds, blockIdx.x);
+  }
 }
 
 // ================================================================== IntDIANA (Algorithm 3) in one sweep
@@ -1251,6 +1386,32 @@ hipError_t launch_step_fused(const TileMap& tm, const LaunchShape& ls, uint32_t 
     } else {
       if (random) hipLaunchKernelGGL((k_aggregate<1, true, false>), grid, block, ls.lds_reserve, ls.stream, a);
       else hipLaunchKernelGGL((k_aggregate<0, true, false>), grid, block, ls.lds_reserve, ls.stream, a);
+    }
+  }
+  hipError_t e = after_launch();
+  if (e != hipSuccess) return e;
+  return finish(ls.stream, fin, true, true);
+}
+
+hipError_t launch_step_fused_phased(const PhasedShape& ps, const LaunchShape& ls, uint64_t d,
+                                    uint32_t n, const RoundSpec& rs, const WorkerPtrs& grads,
+                                    const float* alpha, double eta, float* x, const Momentum* mom,
+                                    const Finish& fin_in) {
+  Finish fin = fin_in;
+  fin.num_tiles = ps.grid;      // one norm partial and one clip-table column per workgroup
+  fin.workgroups = ps.grid;
+  PhasedArgs a{rs, n, alpha, eta, x, mom ? mom->m : nullptr, mom ? mom->mu : 0.0,
+               mom ? mom->wd : 0.0, d, fin, grads};
+  const dim3 grid(ps.grid), block(kPhasedThreads);
+  const bool random = rs.rounding == INTSGD_ROUND_STOCHASTIC;
+  {
+    Tapped tap(ls);
+    if (mom) {
+      if (random) hipLaunchKernelGGL((k_aggregate_phased<1, true>), grid, block, 0, ls.stream, a);
+      else hipLaunchKernelGGL((k_aggregate_phased<0, true>), grid, block, 0, ls.stream, a);
+    } else {
+      if (random) hipLaunchKernelGGL((k_aggregate_phased<1, false>), grid, block, 0, ls.stream, a);
+      else hipLaunchKernelGGL((k_aggregate_phased<0, false>), grid, block, 0, ls.stream, a);
     }
   }
   hipError_t e = after_launch();

@@ -133,15 +133,17 @@ def test_tuning_knobs_are_validated():
     before = P.intsgd_get_tuning()
     T = binding._CTuning
     for bad in (T(1000, 0, 0), T(512, 0, 0), T(131072, 0, 0), T(4097, 0, 0), T(0, (1 << 20) + 1, 0),
-                T(0, 0, 1), T(0, 0, 9)):
+                T(0, 0, 1), T(0, 0, 9), T(0, 0, 0, 3)):
         assert lib.intsgd_set_tuning(C.byref(bad)) == EINVAL
     assert lib.intsgd_set_tuning(None) == EINVAL
     assert P.intsgd_get_tuning() == before
-    assert before == (0, 0, 0)                           # everything automatic by default
+    assert before == (0, 0, 0, 0)                        # everything automatic by default
     P.intsgd_set_tuning(4096, 100, 4)
-    assert P.intsgd_get_tuning() == (4096, 100, 4)
+    assert P.intsgd_get_tuning() == (4096, 100, 4, 0)
     P.intsgd_set_tuning(tile_coords=1024)                # zero fields go back to automatic
-    assert P.intsgd_get_tuning() == (1024, 0, 0)
+    assert P.intsgd_get_tuning() == (1024, 0, 0, 0)
+    P.intsgd_set_tuning(two_phase=2)
+    assert P.intsgd_get_tuning() == (0, 0, 0, 2)
     P.intsgd_set_tuning(*before)
     # the workspace size does not depend on the tuning
     desc = P.Desc(10**7, 8)

@@ -744,3 +744,80 @@ def test_graph_replay_of_a_whole_step():
         assert torch.equal(st_g.alpha, st_e.alpha) and torch.equal(st_g.r, st_e.r)
         assert torch.equal(st_g.norm_sq, st_e.norm_sq)
         assert torch.equal(st_g.sat_count, st_e.sat_count)
+
+
+# --------------------------------------------------------------------------- two-phase sweep
+PHASED_D = (1 << 22) + 4099          # just above the threshold; d mod 4 = 3 (scalar tail)
+
+
+@pytest.mark.parametrize("rounding", [P.ROUND_NEAREST_EVEN, P.ROUND_STOCHASTIC])
+@pytest.mark.parametrize("n,L", [(1, None), (3, 1), (8, 127), (16, None), (21, None)])
+def test_two_phase_sweep_matches_oracle_and_tile_sweep(n, L, rounding):
+    """The two-phase form of the fused step (forced on, both rounding modes, worker counts
+    that use every group size, adversarial values, tight clips) against the oracle; the
+    tile sweep on the same inputs must give the same bits for x and the same counts."""
+    d = PHASED_D
+    L = P.default_clip(n) if L is None else L
+    alpha, g, x = make_case(d, n, None, seed=17 * n + rounding)
+    out = oracle.step(list(g), alpha, x, rounding=rounding, L=L, eta=0.1, seed=5, step=3)
+    desc = P.Desc(d, n, rounding=rounding, clip=L, seed=5, step=3)
+    ws = P.new_workspace(desc, DEV)
+    rows = rows_on_device(g)
+    res = {}
+    for form in (2, 1):
+        P.intsgd_set_tuning(two_phase=form)
+        d_x, d_a = dev(x), dev(alpha)
+        d_ns = torch.zeros(1, dtype=torch.float64, device=DEV)
+        d_cnt = torch.zeros(n, dtype=torch.int64, device=DEV)
+        P.intsgd_step_fused(desc, rows, d_a, 0.1, d_x, d_ns, d_cnt, ws)
+        assert_within_ulp(host(d_x), out["x_new"], 1, "x (form %d)" % form)
+        assert u64(d_cnt).tolist() == out["sat_count"].tolist()
+        assert rel_err(host(d_ns), out["normsq"]) <= NORM_RTOL
+        res[form] = (d_x, host(d_ns))
+    assert torch.equal(res[1][0], res[2][0])
+    assert rel_err(res[1][1], res[2][1]) <= 1e-12
+    if L <= 127:
+        assert out["sat_count"].sum() > 0
+
+
+@pytest.mark.parametrize("rounding", [P.ROUND_NEAREST_EVEN, P.ROUND_STOCHASTIC])
+def test_two_phase_sweep_momentum_form(rounding):
+    d, n = PHASED_D, 8
+    alpha, g, x = make_case(d, n, None, seed=23 + rounding)
+    m = np.random.default_rng(d).normal(0, 0.01, d).astype(F32)
+    eta, mu, wd, L = 0.1, 0.9, 1e-4, P.default_clip(n)
+    out = oracle.step_momentum(list(g), alpha, x, m, rounding=rounding, L=L, eta=eta, mu=mu, wd=wd,
+                               seed=9, step=2)
+    desc = P.Desc(d, n, rounding=rounding, clip=L, seed=9, step=2)
+    ws = P.new_workspace(desc, DEV)
+    rows = rows_on_device(g)
+    P.intsgd_set_tuning(two_phase=2)
+    d_x, d_m, d_a = dev(x), dev(m), dev(alpha)
+    d_ns = torch.zeros(1, dtype=torch.float64, device=DEV)
+    d_cnt = torch.zeros(n, dtype=torch.int64, device=DEV)
+    P.intsgd_step_momentum(desc, rows, d_a, eta, mu, wd, d_x, d_m, None, 0.0, 0.0, d_ns, d_cnt, ws)
+    assert_within_ulp(host(d_x), out["x_new"], 1, "x")
+    assert_within_ulp(host(d_m), out["m_new"], 1, "m")
+    assert u64(d_cnt).tolist() == out["sat_count"].tolist()
+    assert rel_err(host(d_ns), out["normsq"]) <= NORM_RTOL
+
+
+def test_two_phase_sweep_config2_full_size():
+    """Workload 2 at full size: two rounds, the second one partial."""
+    P.intsgd_set_tuning(two_phase=2)
+    lockstep_run(W.config(2), steps=2, free_running=False)
+
+
+def test_two_phase_sweep_config3_full_size_randomized():
+    P.intsgd_set_tuning(two_phase=2)
+    sat = lockstep_run(W.config(3), steps=1, free_running=False)
+    assert sat > 0
+
+
+def test_two_phase_needs_one_block_and_enough_coordinates():
+    """Forced on, the library still takes the tile sweep where the two-phase one does not
+    apply (several blocks, short vectors); results are the oracle's either way."""
+    P.intsgd_set_tuning(two_phase=2)
+    w = W.config(4).scaled(scaled_blocks(0)[-1], block_offsets=scaled_blocks(0))
+    lockstep_run(w, steps=2)
+    lockstep_run(W.config(2).scaled(100_003), steps=2)
