@@ -135,14 +135,14 @@ class HipEvents:
         self.hip.hipEventDestroy(ev)
 
 
-def load_traffic(name, mode):
-    """HBM bytes per launch of the dominant kernel from committed rocprofv3 counter
-    summaries (profiles/traffic.json), or None."""
+def load_traffic(name, form):
+    """HBM bytes per launch of the dominant kernel (fused step, `form` = "tile" or
+    "two_phase") from committed rocprofv3 counter summaries (profiles/traffic.json), or None."""
     path = os.path.join(ROOT, "profiles", "traffic.json")
     try:
         with open(path) as fh:
             table = json.load(fh)
-        return table.get("%s/%s" % (name, mode), {}).get("bytes_per_launch")
+        return table.get("%s/%s" % (name, form), {}).get("bytes_per_launch")
     except (OSError, ValueError):
         return None
 
@@ -187,11 +187,14 @@ def main():
         h_global = torch.zeros_like(x)
     torch.cuda.synchronize()
 
-    def one_step(k):
+    def one_step(k, tap=None):
         rows = sets[(k - 1) % pool][1]
         if args.heuristic:
             nb = 7 if w.wire == 8 else 31
             P.intsgd_heuristic_alpha(desc, rows, nb, st.alpha, st.workspace)   # extra sweep
+        if tap is not None:
+            P.intsgd_tap_next_launch(tap[0], tap[1])     # events right around the next sweep
+        if args.heuristic:
             st.step_fused(rows, x, k, chain_alpha=False)
         elif args.diana:
             desc.step = k
@@ -219,9 +222,7 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        if not args.no_taps:
-            P.intsgd_tap_next_launch(ev[i][0], ev[i][1])
-        one_step(args.warmup + 1 + i)
+        one_step(args.warmup + 1 + i, None if args.no_taps else ev[i])
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
@@ -237,6 +238,14 @@ def main():
         per_coord = 12 * w.n + 16
     algo_bytes = per_coord * w.d
     achieved = algo_bytes / (avg_kernel_ms * 1e-3) / 1e9
+    if args.diana:
+        kernel_name = "k_diana<ROUND>: Algorithm 3 in one sweep"
+    elif args.mode != "fused":
+        kernel_name = "k_aggregate<ROUND, FUSED=false>: a1-a4 (first of the two sweeps)"
+    elif P.intsgd_fused_step_form(desc) == 2:
+        kernel_name = "k_aggregate_phased<ROUND, MOMENTUM>: a1-a7, gradient reads then x update per round"
+    else:
+        kernel_name = "k_aggregate<ROUND, FUSED=true, MOMENTUM>: a1-a7 in one tile sweep"
     sat = int(st.sat_count.cpu().numpy().view("uint64").sum())
     alpha_last = float(st.alpha.cpu()[0])
 
@@ -267,9 +276,9 @@ def main():
         "roofline": {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": None if (args.momentum or args.diana) else load_traffic(w.name, args.mode),
-            "kernel": "k_aggregate<ROUND, FUSED=true>: a1-a7 in one sweep" if args.mode == "fused"
-                      else "k_aggregate<ROUND, FUSED=false>: a1-a4 (first of the two sweeps)",
+            "traffic": None if (args.momentum or args.diana or args.mode != "fused")
+                       else load_traffic(w.name, "two_phase" if P.intsgd_fused_step_form(desc) == 2 else "tile"),
+            "kernel": kernel_name,
             "algorithmic_bytes_per_launch": algo_bytes,
             "kernel_ms_avg": avg_kernel_ms, "kernel_ms_min": kernel_ms[0],
             "kernel_ms_median": kernel_ms[len(kernel_ms) // 2],

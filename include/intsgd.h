@@ -293,6 +293,10 @@ typedef struct intsgd_tuning {
 } intsgd_tuning;
 intsgd_status intsgd_set_tuning(const intsgd_tuning* tuning);
 void intsgd_get_tuning(intsgd_tuning* tuning);
+/* Which form the fused step (intsgd_step_fused, .._next_alpha, intsgd_step_momentum) takes
+ * for this descriptor under the current tuning: 1 = tile sweep, 2 = two-phase sweep;
+ * 0 if the descriptor is invalid.  Host-only, launches nothing. */
+int intsgd_fused_step_form(const intsgd_desc* desc);
 
 const char* intsgd_status_string(intsgd_status status);
 /* Text of the last HIP error seen by this thread's calls ("" if none). */

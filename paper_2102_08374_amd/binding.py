@@ -17,8 +17,8 @@ __all__ = [
     "intsgd_update_norm", "intsgd_next_alpha", "intsgd_next_alpha_host", "intsgd_compress_sum",
     "intsgd_decode_update_norm", "intsgd_step_fused", "intsgd_step_fused_next_alpha",
     "intsgd_decode_update_momentum", "intsgd_step_momentum", "intsgd_diana_step",
-    "intsgd_heuristic_alpha", "intsgd_tap_next_launch", "intsgd_set_tuning", "intsgd_get_tuning", "intsgd_status_string",
-    "new_workspace", "EXPORTED_SYMBOLS",
+    "intsgd_heuristic_alpha", "intsgd_tap_next_launch", "intsgd_set_tuning", "intsgd_get_tuning",
+    "intsgd_fused_step_form", "intsgd_status_string", "new_workspace", "EXPORTED_SYMBOLS",
 ]
 
 ROUND_NEAREST_EVEN = 0
@@ -33,8 +33,8 @@ EXPORTED_SYMBOLS = [
     "intsgd_step_momentum", "intsgd_diana_step", "intsgd_heuristic_alpha",
     "intsgd_int_sum", "intsgd_decode_update", "intsgd_update_norm", "intsgd_next_alpha",
     "intsgd_next_alpha_host", "intsgd_compress_sum", "intsgd_decode_update_norm",
-    "intsgd_step_fused", "intsgd_set_tuning", "intsgd_get_tuning", "intsgd_status_string",
-    "intsgd_last_hip_error",
+    "intsgd_step_fused", "intsgd_set_tuning", "intsgd_get_tuning", "intsgd_fused_step_form",
+    "intsgd_status_string", "intsgd_last_hip_error",
 ]
 
 
@@ -97,6 +97,8 @@ _lib.intsgd_step_momentum.argtypes = [_DP, _PP, _P, C.c_double, C.c_double, C.c_
 _lib.intsgd_set_tuning.argtypes = [C.POINTER(_CTuning)]
 _lib.intsgd_get_tuning.argtypes = [C.POINTER(_CTuning)]
 _lib.intsgd_get_tuning.restype = None
+_lib.intsgd_fused_step_form.argtypes = [_DP]
+_lib.intsgd_fused_step_form.restype = C.c_int
 _lib.intsgd_status_string.argtypes = [C.c_int]
 _lib.intsgd_status_string.restype = C.c_char_p
 _lib.intsgd_last_hip_error.argtypes = []
@@ -410,6 +412,11 @@ def intsgd_get_tuning():
     t = _CTuning()
     _lib.intsgd_get_tuning(C.byref(t))
     return int(t.tile_coords), int(t.max_workgroups), int(t.workgroups_per_cu), int(t.two_phase)
+
+
+def intsgd_fused_step_form(desc: "Desc") -> int:
+    """1 = tile sweep, 2 = two-phase sweep (what the fused step would launch now)."""
+    return int(_lib.intsgd_fused_step_form(desc.ref()))
 
 
 def intsgd_status_string(status: int) -> str:

@@ -665,6 +665,11 @@ void intsgd_get_tuning(intsgd_tuning* tuning) {
   if (tuning) *tuning = g_tuning;
 }
 
+int intsgd_fused_step_form(const intsgd_desc* desc) {
+  if (validate_desc(desc) != INTSGD_OK) return 0;
+  return use_two_phase(desc, effective_tuning(desc)) ? 2 : 1;
+}
+
 const char* intsgd_status_string(intsgd_status status) {
   switch (status) {
     case INTSGD_OK: return "ok";

@@ -248,3 +248,24 @@ def test_host_alpha_rule_equals_the_oracle():
             assert np.array_equal(np.array(a_h, np.float32), af)
     st, _, a = P.intsgd_next_alpha_host(P.Desc(10, 1), [0.0], [0.0], 0.0, 0.0, 0.1)
     assert st == ERANGE and np.isposinf(a[0])
+
+
+def test_fused_step_form_policy():
+    """Host-only query of which sweep the fused step would launch."""
+    before = P.intsgd_get_tuning()
+    big, small = 1 << 22, (1 << 22) - 1
+    try:
+        assert P.intsgd_fused_step_form(P.Desc(big, 16, rounding=P.ROUND_NEAREST_EVEN)) == 2
+        assert P.intsgd_fused_step_form(P.Desc(small, 16, rounding=P.ROUND_NEAREST_EVEN)) == 1
+        assert P.intsgd_fused_step_form(P.Desc(big, 8, rounding=P.ROUND_STOCHASTIC)) == 1
+        blocks = P.Desc(big, 8, rounding=P.ROUND_NEAREST_EVEN, block_offsets=[0, 1000, big])
+        assert P.intsgd_fused_step_form(blocks) == 1
+        P.intsgd_set_tuning(two_phase=2)
+        assert P.intsgd_fused_step_form(P.Desc(big, 8, rounding=P.ROUND_STOCHASTIC)) == 2
+        assert P.intsgd_fused_step_form(blocks) == 1
+        assert P.intsgd_fused_step_form(P.Desc(small, 8)) == 1
+        P.intsgd_set_tuning(two_phase=1)
+        assert P.intsgd_fused_step_form(P.Desc(big, 16, rounding=P.ROUND_NEAREST_EVEN)) == 1
+        assert lib.intsgd_fused_step_form(None) == 0
+    finally:
+        P.intsgd_set_tuning(*before)
