@@ -29,7 +29,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = headline)")
-    ap.add_argument("--mode", default="fused", choices=["fused", "two_pass"])
+    ap.add_argument("--mode", default="fused", choices=["fused", "two_pass", "unfused"],
+                    help="fused: one call; two_pass: F1, F2, a8; unfused: a1-a3, a4, a5-a6, a7, a8")
     ap.add_argument("--pool", type=int, default=0,
                     help="distinct gradient sets resident in HBM, cycled (0 = auto)")
     ap.add_argument("--tile", type=int, default=0)
@@ -179,7 +180,13 @@ def main():
     for s in range(pool):
         buf, rows = W.make_gradients(w, s + 1, dev)
         sets.append((buf, rows))
-    sum_buf = torch.empty(w.d, dtype=torch.int32, device=dev) if args.mode == "two_pass" else None
+    sum_buf = torch.empty(w.d, dtype=torch.int32, device=dev) if args.mode != "fused" else None
+    q_bufs = x_old_buf = None
+    if args.mode == "unfused":
+        qdt = torch.int8 if w.wire == 8 else torch.int32
+        qbuf = torch.empty((w.n, W.row_stride(w.d)), dtype=qdt, device=dev)
+        q_bufs = [qbuf[i, :w.d] for i in range(w.n)]
+        x_old_buf = torch.empty_like(x)
     mom = torch.zeros_like(x) if args.momentum else None
     if args.diana:
         hbuf = torch.zeros((w.n, W.row_stride(w.d)), dtype=torch.float32, device=dev)
@@ -204,8 +211,10 @@ def main():
             st.step_momentum(rows, x, mom, k, 0.9, 1e-4)  # a1-a8 with the momentum update
         elif args.mode == "fused":
             st.step_fused(rows, x, k)                    # a1-a8, one call
-        else:
+        elif args.mode == "two_pass":
             st.step_two_pass(rows, x, k, sum_buf)        # F1, F2, a8
+        else:
+            st.step_unfused(rows, x, k, q_bufs, sum_buf, x_old_buf)   # five calls + a copy of x
 
     st.start(w.first_normsq)
     alpha0 = st.alpha.cpu().numpy().copy()
@@ -232,6 +241,8 @@ def main():
         hip.destroy(b)
     avg_kernel_ms = sum(kernel_ms) / len(kernel_ms)
     per_coord = (4 * w.n + 8) if args.mode == "fused" else (4 * w.n + 4)
+    if args.mode == "unfused":
+        per_coord = (4 + w.wire // 8) * w.n
     if args.momentum:
         per_coord = 4 * w.n + 16
     if args.diana:
@@ -240,6 +251,8 @@ def main():
     achieved = algo_bytes / (avg_kernel_ms * 1e-3) / 1e9
     if args.diana:
         kernel_name = "k_diana<ROUND>: Algorithm 3 in one sweep"
+    elif args.mode == "unfused":
+        kernel_name = "k_compress<ROUND, WIRE>: a1-a3 for all n workers (first of the five calls)"
     elif args.mode != "fused":
         kernel_name = "k_aggregate<ROUND, FUSED=false>: a1-a4 (first of the two sweeps)"
     elif P.intsgd_fused_step_form(desc) == 2:

@@ -280,11 +280,12 @@ intsgd_status intsgd_heuristic_alpha(const intsgd_desc* desc, const float* const
  *   max_workgroups     cap of the launch grid, in [1, 1048576]; tiles beyond it are
  *                      taken by striding
  *   workgroups_per_cu  residency cap of the streaming kernels, 2..8 (8 = no cap)
- *   two_phase          form of the fused step (intsgd_step_fused, .._next_alpha,
- *                      intsgd_step_momentum) when there is one block: 1 = always the tile
- *                      sweep, 2 = the two-phase sweep (gradient reads, then the x update,
- *                      with the integer sums held in registers in between) whenever
- *                      d >= 2^22; 0 = automatic */
+ *   two_phase          form of the sweeps that have one (intsgd_step_fused, .._next_alpha,
+ *                      intsgd_step_momentum, intsgd_compress_sum; one block, d >= 2^22):
+ *                      1 = always the tile sweep, 2 = always the two-phase sweep (gradient
+ *                      reads, then the write-back, with the integer sums held in registers
+ *                      in between), 0 = automatic (two-phase for nearest-even rounding).
+ *                      intsgd_int_sum follows it too: automatic = two-phase for int8 */
 typedef struct intsgd_tuning {
   uint32_t tile_coords;
   uint32_t max_workgroups;
@@ -293,8 +294,9 @@ typedef struct intsgd_tuning {
 } intsgd_tuning;
 intsgd_status intsgd_set_tuning(const intsgd_tuning* tuning);
 void intsgd_get_tuning(intsgd_tuning* tuning);
-/* Which form the fused step (intsgd_step_fused, .._next_alpha, intsgd_step_momentum) takes
- * for this descriptor under the current tuning: 1 = tile sweep, 2 = two-phase sweep;
+/* Which form the fused step (intsgd_step_fused, .._next_alpha, intsgd_step_momentum) and
+ * intsgd_compress_sum take for this descriptor under the current tuning: 1 = tile sweep,
+ * 2 = two-phase sweep;
  * 0 if the descriptor is invalid.  Host-only, launches nothing. */
 int intsgd_fused_step_form(const intsgd_desc* desc);
 

@@ -359,6 +359,16 @@ intsgd_status validate_momentum(const Momentum* mom) {
   return INTSGD_OK;
 }
 
+// Decides the form of a sweep for this call and, for the two-phase form, its grid.
+intsgd_status two_phase_shape(const intsgd_desc* desc, PhasedShape* ps, bool* phased) {
+  *phased = false;
+  if (!use_two_phase(desc, effective_tuning(desc))) return INTSGD_OK;
+  INTSGD_TRY(compute_units(&ps->grid));
+  // the caller's workspace holds one slot per 1024 coordinates; one per CU is needed
+  *phased = ps->grid <= tiles_of(desc->d, kMinTile);
+  return INTSGD_OK;
+}
+
 intsgd_status step_fused_impl(const intsgd_desc* desc, const float* const* grads,
                               const float* alpha, double eta, float* x, double* norm_sq_out,
                               uint64_t* sat_count, void* workspace, size_t workspace_bytes,
@@ -377,16 +387,12 @@ intsgd_status step_fused_impl(const intsgd_desc* desc, const float* const* grads
   fill_ptrs(&g, (const void* const*)grads, desc->n);
   Finish fin = make_finish(desc, t, workspace, norm_sq_out, sat_count);
   if (r != nullptr) fin.rule = AlphaRule{r, alpha_out, t.offsets_dev, beta, eps, eta};
-  const intsgd_tuning tune = effective_tuning(desc);
-  if (use_two_phase(desc, tune)) {
-    PhasedShape ps{0};
-    INTSGD_TRY(compute_units(&ps.grid));
-    // the caller's workspace holds one slot per 1024 coordinates; one per CU is needed
-    if (ps.grid > tiles_of(desc->d, kMinTile))
-      return done(launch_step_fused(t.tm, t.ls, desc->n, round_spec(desc), g, alpha, eta, x, mom, fin));
+  PhasedShape ps{0};
+  bool phased = false;
+  INTSGD_TRY(two_phase_shape(desc, &ps, &phased));
+  if (phased)
     return done(launch_step_fused_phased(ps, t.ls, desc->d, desc->n, round_spec(desc), g, alpha, eta,
                                          x, mom, fin));
-  }
   return done(launch_step_fused(t.tm, t.ls, desc->n, round_spec(desc), g, alpha, eta, x, mom, fin));
 }
 
@@ -434,6 +440,9 @@ intsgd_status intsgd_compress(const intsgd_desc* desc, const float* const* grads
   std::memset(&q, 0, sizeof(q));
   for (uint32_t i = 0; i < desc->n; ++i) q.p[i] = q_out[i];
   const WorkspaceLayout w = workspace_layout(desc);
+  // one read and one write stream per workgroup: a copy-like kernel, which wants every
+  // wavefront slot filled (80 % of peak against 62 % under the sweeps' residency cap)
+  if (g_tuning.workgroups_per_cu == 0) t.ls.lds_reserve = 0;
   return done(launch_compress(t.tm, t.ls, desc->n, desc->wire, round_spec(desc), g, alpha, q,
                               ws_at<uint64_t>(workspace, w.rows_off), sat_count));
 }
@@ -445,6 +454,16 @@ intsgd_status intsgd_int_sum(const intsgd_desc* desc, const void* const* q, int3
   INTSGD_TRY(validate_vec(sum_out));
   WorkerPtrs qp;
   fill_ptrs(&qp, q, desc->n);
+  // int8 streams: 16 coordinates per 16-byte load and the two-phase form (65 us against 77 us
+  // on 8 x 25.6 M); int32 streams measured no better that way and keep the strided loop
+  if ((desc->wire == INTSGD_WIRE_INT8 || effective_tuning(desc).two_phase == 2) &&
+      desc->d >= kMinPhasedD && effective_tuning(desc).two_phase != 1) {
+    PhasedShape ps{0};
+    INTSGD_TRY(compute_units(&ps.grid));
+    LaunchShape pls{ps.grid, 0, static_cast<hipStream_t>(hip_stream), nullptr, nullptr};
+    take_taps(&pls);
+    return done(launch_int_sum_phased(ps, pls, desc->d, desc->n, desc->wire, qp, sum_out));
+  }
   // about four quads per thread and pass of the grid-stride loop
   const uint64_t want = tiles_of((desc->d >> 2) + 1, INTSGD_THREADS_PER_WORKGROUP * 4);
   const uint32_t cap = effective_tuning(desc).max_workgroups;
@@ -539,8 +558,14 @@ intsgd_status intsgd_compress_sum(const intsgd_desc* desc, const float* const* g
   INTSGD_TRY(make_tiling(desc, hip_stream, &t));
   WorkerPtrs g;
   fill_ptrs(&g, (const void* const*)grads, desc->n);
-  return done(launch_compress_sum(t.tm, t.ls, desc->n, round_spec(desc), g, alpha, sum_out,
-                                  make_finish(desc, t, workspace, nullptr, sat_count)));
+  const Finish fin = make_finish(desc, t, workspace, nullptr, sat_count);
+  PhasedShape ps{0};
+  bool phased = false;
+  INTSGD_TRY(two_phase_shape(desc, &ps, &phased));
+  if (phased)
+    return done(launch_compress_sum_phased(ps, t.ls, desc->d, desc->n, round_spec(desc), g, alpha,
+                                           sum_out, fin));
+  return done(launch_compress_sum(t.tm, t.ls, desc->n, round_spec(desc), g, alpha, sum_out, fin));
 }
 
 intsgd_status intsgd_decode_update_norm(const intsgd_desc* desc, const int32_t* sum,

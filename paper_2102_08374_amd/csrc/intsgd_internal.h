@@ -117,6 +117,13 @@ hipError_t launch_step_fused_phased(const PhasedShape& ps, const LaunchShape& ls
                                     uint32_t n, const RoundSpec& rs, const WorkerPtrs& grads,
                                     const float* alpha, double eta, float* x, const Momentum* mom,
                                     const Finish& fin);
+// F1 in the two-phase form: phase B writes the integer sums.
+hipError_t launch_compress_sum_phased(const PhasedShape& ps, const LaunchShape& ls, uint64_t d,
+                                      uint32_t n, const RoundSpec& rs, const WorkerPtrs& grads,
+                                      const float* alpha, int32_t* sum_out, const Finish& fin);
+// a4 in the two-phase form.
+hipError_t launch_int_sum_phased(const PhasedShape& ps, const LaunchShape& ls, uint64_t d, uint32_t n,
+                                 int32_t wire, const WorkerPtrs& q, int32_t* sum_out);
 hipError_t launch_diana_step(const TileMap& tm, const LaunchShape& ls, uint32_t n,
                              const RoundSpec& rs, const WorkerPtrs& grads,
                              const WorkerOutPtrs& h_local, const float* alpha, double eta, float* x,

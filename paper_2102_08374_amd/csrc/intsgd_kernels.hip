@@ -541,7 +541,15 @@ __global__ __launch_bounds__(kThreads) void k_finish_rows(const uint64_t* rows, 
   __syncthreads();
   const uint64_t* row = rows + (uint64_t)blockIdx.x * row_len;
   unsigned long long acc = 0ull;
-  for (uint32_t g = threadIdx.x; g < row_len; g += kThreads) acc += row[g];
+  uint32_t g = threadIdx.x;
+  for (; g + 7u * kThreads < row_len; g += 8u * kThreads) {     // eight loads in flight: pure latency
+    uint64_t v[8];
+#pragma unroll
+    for (uint32_t u = 0; u < 8; ++u) v[u] = row[g + u * kThreads];
+#pragma unroll
+    for (uint32_t u = 0; u < 8; ++u) acc += v[u];
+  }
+  for (; g < row_len; g += kThreads) acc += row[g];
   if (acc != 0ull) atomicAdd(&total, acc);
   __syncthreads();
   if (threadIdx.x == 0) sat_count[blockIdx.x] = total;
@@ -667,14 +675,20 @@ struct PhasedArgs {
   float* x;
   float* m;
   double mu, wd;
+  int32_t* sum_out;      // kPhasedSumOnly
   uint64_t d;
   Finish fin;
   WorkerPtrs grads;
 };
 
-template <int ROUND, bool MOMENTUM>
+constexpr int kPhasedSumOnly = 0;    // F1: phase B writes the integer sums
+constexpr int kPhasedUpdate = 1;     // F3
+constexpr int kPhasedMomentum = 2;   // F3 with the momentum / weight-decay update
+
+template <int ROUND, int MODE>
 __global__ __launch_bounds__(kPhasedThreads) void k_aggregate_phased(const PhasedArgs a) {
   constexpr uint32_t kPhasedQuads = phased_quads(ROUND);
+  constexpr bool MOMENTUM = MODE == kPhasedMomentum;
   __shared__ ReduceLds lds;
   zero_sat(lds);
   const uint32_t tid = threadIdx.x;
@@ -709,20 +723,26 @@ __global__ __launch_bounds__(kPhasedThreads) void k_aggregate_phased(const Phase
     }
     __syncthreads();
     // phase B: stores past the round are dropped by the descriptor
-    const __amdgpu_buffer_rsrc_t out = make_stream((vf4*)a.x + r0, nq * 16u);
+    const __amdgpu_buffer_rsrc_t out = (MODE == kPhasedSumOnly)
+                                           ? make_stream((vi4*)a.sum_out + r0, nq * 16u)
+                                           : make_stream((vf4*)a.x + r0, nq * 16u);
     const __amdgpu_buffer_rsrc_t mom = MOMENTUM ? make_stream((vf4*)a.m + r0, nq * 16u) : out;
 #pragma clang loop unroll(full)
     for (uint32_t k = 0; k < kPhasedQuads; ++k) {
       if (k * slab_row < nq) {
         const uint32_t off = ((k * gridDim.x + blockIdx.x) * kPhasedThreads + tid) * 16u;
-        const vf4 xv = as_f(load128<INTSGD_X_LOAD_POLICY>(out, off));
-        if (MOMENTUM) {
-          vf4 mv = as_f(load128<INTSGD_X_LOAD_POLICY>(mom, off));
-          const vf4 xn = momentum_quad(xv, mv, S[k], rule, acc);
-          store128<INTSGD_X_STORE_POLICY>(mom, off, as_u(mv));
-          store128<INTSGD_X_STORE_POLICY>(out, off, as_u(xn));
+        if (MODE == kPhasedSumOnly) {
+          store128<kPlain>(out, off, as_u(S[k]));
         } else {
-          store128<INTSGD_X_STORE_POLICY>(out, off, as_u(update_quad(xv, S[k], c, acc)));
+          const vf4 xv = as_f(load128<INTSGD_X_LOAD_POLICY>(out, off));
+          if (MOMENTUM) {
+            vf4 mv = as_f(load128<INTSGD_X_LOAD_POLICY>(mom, off));
+            const vf4 xn = momentum_quad(xv, mv, S[k], rule, acc);
+            store128<INTSGD_X_STORE_POLICY>(mom, off, as_u(mv));
+            store128<INTSGD_X_STORE_POLICY>(out, off, as_u(xn));
+          } else {
+            store128<INTSGD_X_STORE_POLICY>(out, off, as_u(update_quad(xv, S[k], c, acc)));
+          }
         }
       }
     }
@@ -731,7 +751,9 @@ __global__ __launch_bounds__(kPhasedThreads) void k_aggregate_phased(const Phase
   if (blockIdx.x == 0 && tid < (uint32_t)(a.d & 3u)) {      // the d mod 4 coordinates after the last quad
     const uint64_t j = (a.d & ~(uint64_t)3) + tid;
     const int32_t Sj = aggregate_scalar<ROUND>(a.grads, a.n, j, alpha, a.rs, lds.sat);
-    if (MOMENTUM) {
+    if (MODE == kPhasedSumOnly) {
+      a.sum_out[j] = Sj;
+    } else if (MOMENTUM) {
       float mj = a.m[j];
       a.x[j] = momentum_coord(a.x[j], mj, Sj, rule, acc);
       a.m[j] = mj;
@@ -741,7 +763,7 @@ __global__ __launch_bounds__(kPhasedThreads) void k_aggregate_phased(const Phase
   }
   const double total = block_sum(acc, lds, 0);
   if (tid == 0) {
-    a.fin.norm_partial[blockIdx.x] = total;
+    if (MODE != kPhasedSumOnly) a.fin.norm_partial[blockIdx.x] = total;
     publish_sat(a.fin, lds, blockIdx.x);
   }
 }
@@ -1052,9 +1074,9 @@ struct CompressOp {
     if (WIRE == INTSGD_WIRE_INT8) {
       const uint32_t packed = ((uint32_t)v.x & 0xFFu) | (((uint32_t)v.y & 0xFFu) << 8) |
                               (((uint32_t)v.z & 0xFFu) << 16) | (((uint32_t)v.w & 0xFFu) << 24);
-      store32<kPlain>(dst, ql * 4u, packed);
+      store32<INTSGD_X_STORE_POLICY>(dst, ql * 4u, packed);
     } else {
-      store128<kPlain>(dst, ql * 16u, as_u(v));
+      store128<INTSGD_X_STORE_POLICY>(dst, ql * 16u, as_u(v));
     }
   }
   __device__ __forceinline__ void end_tile(uint32_t, uint32_t) {}
@@ -1089,6 +1111,26 @@ __device__ __forceinline__ vi4 load_q4(const void* base, uint64_t quad) {
   return __builtin_nontemporal_load((const vi4*)base + quad);
 }
 
+// Adds one 16-byte unit of a worker's integer stream to the running sums.
+template <int WIRE>
+__device__ __forceinline__ void add_unit(vi4 (&S)[(WIRE == INTSGD_WIRE_INT8) ? 4 : 1], const vu4& v) {
+  if (WIRE == INTSGD_WIRE_INT8) {
+    const uint32_t p[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+      S[h].x += (int32_t)(int8_t)(p[h] & 0xFFu);
+      S[h].y += (int32_t)(int8_t)((p[h] >> 8) & 0xFFu);
+      S[h].z += (int32_t)(int8_t)((p[h] >> 16) & 0xFFu);
+      S[h].w += (int32_t)(int8_t)(p[h] >> 24);
+    }
+  } else {
+    S[0].x += (int32_t)v.x;
+    S[0].y += (int32_t)v.y;
+    S[0].z += (int32_t)v.z;
+    S[0].w += (int32_t)v.w;
+  }
+}
+
 template <int WIRE>
 __global__ __launch_bounds__(kThreads) void k_int_sum(const IntSumArgs a) {
   const uint64_t nq = a.d >> 2;
@@ -1110,6 +1152,70 @@ __global__ __launch_bounds__(kThreads) void k_int_sum(const IntSumArgs a) {
         S += (WIRE == INTSGD_WIRE_INT8) ? (int32_t)((const int8_t*)a.q.p[i])[j]
                                         : ((const int32_t*)a.q.p[i])[j];
       a.sum_out[j] = S;
+    }
+  }
+}
+
+// a4 in two phases: per round, read the n integer streams (the sums of Q units per thread stay
+// in registers), then write the sums.  A unit is 16 bytes of one worker's stream: one quad of
+// int32, or 16 coordinates of int8 (whose sums then go out as four 16-byte stores).
+template <int WIRE>
+__global__ __launch_bounds__(kPhasedThreads) void k_int_sum_phased(const IntSumArgs a) {
+  constexpr uint32_t kUnitCoords = (WIRE == INTSGD_WIRE_INT8) ? 16u : 4u;
+  constexpr uint32_t kUnitQuads = kUnitCoords / 4u;
+  constexpr uint32_t Q = (WIRE == INTSGD_WIRE_INT8) ? 4u : 12u;      // units per thread and round
+  const uint32_t tid = threadIdx.x;
+  const uint64_t nunits = a.d / kUnitCoords;
+  const uint32_t slab_row = gridDim.x * kPhasedThreads;
+  const uint64_t per_round = (uint64_t)slab_row * Q;
+  for (uint64_t r0 = 0; r0 < nunits; r0 += per_round) {
+    const uint64_t rest = nunits - r0;
+    const uint32_t nu = rest < per_round ? (uint32_t)rest : (uint32_t)per_round;
+    vi4 S[Q][kUnitQuads];
+#pragma clang loop unroll(full)
+    for (uint32_t k = 0; k < Q; ++k)
+#pragma clang loop unroll(full)
+      for (uint32_t h = 0; h < kUnitQuads; ++h) S[k][h] = vi4{0, 0, 0, 0};
+#pragma clang loop unroll(full)
+    for (uint32_t k = 0; k < Q; ++k) {
+      if (k * slab_row < nu) {
+        const uint32_t off = ((k * gridDim.x + blockIdx.x) * kPhasedThreads + tid) * 16u;
+        uint32_t i = 0;
+        for (; i + 8 <= a.n; i += 8) {
+          vu4 v[8];
+#pragma unroll
+          for (int w = 0; w < 8; ++w)
+            v[w] = load128<kNonTemporal>(make_stream((const vu4*)a.q.p[i + w] + r0, nu * 16u), off);
+#pragma unroll
+          for (int w = 0; w < 8; ++w) add_unit<WIRE>(S[k], v[w]);
+        }
+        for (; i < a.n; ++i)
+          add_unit<WIRE>(S[k], load128<kNonTemporal>(make_stream((const vu4*)a.q.p[i] + r0, nu * 16u), off));
+      }
+    }
+    __syncthreads();
+    const __amdgpu_buffer_rsrc_t out =
+        make_stream((vi4*)a.sum_out + r0 * kUnitQuads, nu * 16u * kUnitQuads);
+#pragma clang loop unroll(full)
+    for (uint32_t k = 0; k < Q; ++k) {
+      if (k * slab_row < nu) {
+        const uint32_t unit = (k * gridDim.x + blockIdx.x) * kPhasedThreads + tid;
+#pragma clang loop unroll(full)
+        for (uint32_t h = 0; h < kUnitQuads; ++h)
+          store128<kPlain>(out, (unit * kUnitQuads + h) * 16u, as_u(S[k][h]));
+      }
+    }
+    __syncthreads();
+  }
+  // the coordinates after the last whole unit
+  if (blockIdx.x == 0) {
+    const uint64_t j = nunits * kUnitCoords + tid;
+    if (j < a.d) {
+      int32_t Sj = 0;
+      for (uint32_t i = 0; i < a.n; ++i)
+        Sj += (WIRE == INTSGD_WIRE_INT8) ? (int32_t)((const int8_t*)a.q.p[i])[j]
+                                         : ((const int32_t*)a.q.p[i])[j];
+      a.sum_out[j] = Sj;
     }
   }
 }
@@ -1304,6 +1410,16 @@ hipError_t launch_compress(const TileMap& tm, const LaunchShape& ls, uint32_t n,
   return after_launch();
 }
 
+hipError_t launch_int_sum_phased(const PhasedShape& ps, const LaunchShape& ls, uint64_t d, uint32_t n,
+                                 int32_t wire, const WorkerPtrs& q, int32_t* sum_out) {
+  IntSumArgs a{d, n, sum_out, q};
+  const dim3 grid(ps.grid), block(kPhasedThreads);
+  Tapped tap(ls);
+  if (wire == INTSGD_WIRE_INT8) hipLaunchKernelGGL((k_int_sum_phased<8>), grid, block, 0, ls.stream, a);
+  else hipLaunchKernelGGL((k_int_sum_phased<32>), grid, block, 0, ls.stream, a);
+  return after_launch();
+}
+
 hipError_t launch_int_sum(uint64_t d, const LaunchShape& ls, uint32_t n, int32_t wire,
                           const WorkerPtrs& q, int32_t* sum_out) {
   IntSumArgs a{d, n, sum_out, q};
@@ -1401,22 +1517,42 @@ hipError_t launch_step_fused_phased(const PhasedShape& ps, const LaunchShape& ls
   fin.num_tiles = ps.grid;      // one norm partial and one clip-table column per workgroup
   fin.workgroups = ps.grid;
   PhasedArgs a{rs, n, alpha, eta, x, mom ? mom->m : nullptr, mom ? mom->mu : 0.0,
-               mom ? mom->wd : 0.0, d, fin, grads};
+               mom ? mom->wd : 0.0, nullptr, d, fin, grads};
   const dim3 grid(ps.grid), block(kPhasedThreads);
   const bool random = rs.rounding == INTSGD_ROUND_STOCHASTIC;
   {
     Tapped tap(ls);
     if (mom) {
-      if (random) hipLaunchKernelGGL((k_aggregate_phased<1, true>), grid, block, 0, ls.stream, a);
-      else hipLaunchKernelGGL((k_aggregate_phased<0, true>), grid, block, 0, ls.stream, a);
+      if (random) hipLaunchKernelGGL((k_aggregate_phased<1, kPhasedMomentum>), grid, block, 0, ls.stream, a);
+      else hipLaunchKernelGGL((k_aggregate_phased<0, kPhasedMomentum>), grid, block, 0, ls.stream, a);
     } else {
-      if (random) hipLaunchKernelGGL((k_aggregate_phased<1, false>), grid, block, 0, ls.stream, a);
-      else hipLaunchKernelGGL((k_aggregate_phased<0, false>), grid, block, 0, ls.stream, a);
+      if (random) hipLaunchKernelGGL((k_aggregate_phased<1, kPhasedUpdate>), grid, block, 0, ls.stream, a);
+      else hipLaunchKernelGGL((k_aggregate_phased<0, kPhasedUpdate>), grid, block, 0, ls.stream, a);
     }
   }
   hipError_t e = after_launch();
   if (e != hipSuccess) return e;
   return finish(ls.stream, fin, true, true);
+}
+
+hipError_t launch_compress_sum_phased(const PhasedShape& ps, const LaunchShape& ls, uint64_t d,
+                                      uint32_t n, const RoundSpec& rs, const WorkerPtrs& grads,
+                                      const float* alpha, int32_t* sum_out, const Finish& fin_in) {
+  Finish fin = fin_in;
+  fin.num_tiles = ps.grid;
+  fin.workgroups = ps.grid;
+  PhasedArgs a{rs, n, alpha, 0.0, nullptr, nullptr, 0.0, 0.0, sum_out, d, fin, grads};
+  const dim3 grid(ps.grid), block(kPhasedThreads);
+  {
+    Tapped tap(ls);
+    if (rs.rounding == INTSGD_ROUND_STOCHASTIC)
+      hipLaunchKernelGGL((k_aggregate_phased<1, kPhasedSumOnly>), grid, block, 0, ls.stream, a);
+    else
+      hipLaunchKernelGGL((k_aggregate_phased<0, kPhasedSumOnly>), grid, block, 0, ls.stream, a);
+  }
+  hipError_t e = after_launch();
+  if (e != hipSuccess) return e;
+  return finish(ls.stream, fin, false, true);
 }
 
 hipError_t launch_diana_step(const TileMap& tm, const LaunchShape& ls, uint32_t n,

@@ -778,6 +778,30 @@ def test_two_phase_sweep_matches_oracle_and_tile_sweep(n, L, rounding):
     assert rel_err(res[1][1], res[2][1]) <= 1e-12
     if L <= 127:
         assert out["sat_count"].sum() > 0
+    # the unfused and two-pass entry points in both forms: a1-a3, a4, F1
+    wires = [P.WIRE_INT32] + ([P.WIRE_INT8] if L <= 127 else [])
+    q_ref = [oracle.compress(g[i], alpha, rounding=rounding, L=L, seed=5, step=3, worker=i)[0]
+             for i in range(n)]
+    for wire in wires:
+        wdesc = P.Desc(d, n, rounding=rounding, wire=wire, clip=L, seed=5, step=3)
+        qdt = torch.int8 if wire == P.WIRE_INT8 else torch.int32
+        for form in (2, 1):
+            P.intsgd_set_tuning(two_phase=form)
+            qs = [torch.full((d,), -99, dtype=qdt, device=DEV) for _ in range(n)]
+            d_a = dev(alpha)
+            d_cnt = torch.zeros(n, dtype=torch.int64, device=DEV)
+            P.intsgd_compress(wdesc, rows, d_a, qs, d_cnt, ws)
+            for i in range(n):
+                assert np.array_equal(host(qs[i]).astype(np.int32), q_ref[i]), (wire, form, i)
+            assert u64(d_cnt).tolist() == out["sat_count"].tolist()
+            d_S = torch.full((d,), -99, dtype=torch.int32, device=DEV)
+            P.intsgd_int_sum(wdesc, qs, d_S)
+            assert np.array_equal(host(d_S), out["S"]), (wire, form)
+            d_S2 = torch.full((d,), -99, dtype=torch.int32, device=DEV)
+            d_cnt2 = torch.zeros(n, dtype=torch.int64, device=DEV)
+            P.intsgd_compress_sum(wdesc, rows, d_a, d_S2, d_cnt2, ws)
+            assert np.array_equal(host(d_S2), out["S"]), (wire, form)
+            assert u64(d_cnt2).tolist() == out["sat_count"].tolist()
 
 
 @pytest.mark.parametrize("rounding", [P.ROUND_NEAREST_EVEN, P.ROUND_STOCHASTIC])
