@@ -441,13 +441,17 @@ def test_profiling_taps_bracket_the_sweep():
     hip.destroy(b)
 
 
-def test_coordinates_beyond_32_bit_quad_index():
-    """d = 2^34 + 4099 (68.7 GB per vector, n = 1): tile starts, quad indices and the Philox
-    counter's high word all exceed 32 bits; the oracle recomputes windows at both ends."""
+@pytest.mark.parametrize("rounding", [P.ROUND_STOCHASTIC, P.ROUND_NEAREST_EVEN],
+                         ids=["stochastic-tile-sweep", "nearest-two-phase-sweep"])
+def test_coordinates_beyond_32_bit_quad_index(rounding):
+    """d = 2^34 + 4099 (68.7 GB per vector, n = 1): tile starts, quad indices, round offsets
+    and the Philox counter's high word all exceed 32 bits; the oracle recomputes windows at
+    both ends.  Randomized rounding runs the tile sweep, nearest-even the two-phase sweep."""
     free, _ = torch.cuda.mem_get_info()
     assert free > 160e9, "needs the 288 GB MI355X"
     d, n = (1 << 34) + 4099, 1
-    desc = P.Desc(d, n, rounding=P.ROUND_STOCHASTIC, clip=P.default_clip(1), seed=(5 << 32) | 7, step=3)
+    desc = P.Desc(d, n, rounding=rounding, clip=P.default_clip(1), seed=(5 << 32) | 7, step=3)
+    assert P.intsgd_fused_step_form(desc) == (1 if rounding == P.ROUND_STOCHASTIC else 2)
     ws = P.new_workspace(desc, DEV)
     g = torch.empty(d, dtype=torch.float32, device=DEV)
     x = torch.empty(d, dtype=torch.float32, device=DEV)
@@ -466,14 +470,16 @@ def test_coordinates_beyond_32_bit_quad_index():
     torch.cuda.synchronize()
     assert u64(d_cnt)[0] == 0
     for s, xo in zip(starts, x_old):
-        out = oracle.step([host(g[s:s + ln])], alpha, xo, rounding=1, L=P.default_clip(1), eta=0.1,
-                          seed=(5 << 32) | 7, step=3, j0=s)
+        out = oracle.step([host(g[s:s + ln])], alpha, xo, rounding=rounding, L=P.default_clip(1),
+                          eta=0.1, seed=(5 << 32) | 7, step=3, j0=s)
         assert_within_ulp(host(x[s:s + ln]), out["x_new"], 1, "x[%d:+%d]" % (s, ln))
         changed = int((out["x_new"] != xo).sum())
         assert changed > ln // 4          # the update really happened there
-    # the norm against the rule of thumb E||dx||^2 = (eta/alpha)^2 d E[S^2], S = Int(alpha g)
+    # the norm against the rule of thumb E||dx||^2 = (eta/alpha)^2 d E[S^2], S = Int(alpha g):
+    # rounding error variance 1/6 (randomized, uniform fractional part) or 1/12 (nearest)
     t = float(alpha[0]) * 1e-3
-    expect = (0.1 / float(alpha[0])) ** 2 * d * (t * t + 1.0 / 6.0)
+    noise = 1.0 / 6.0 if rounding == P.ROUND_STOCHASTIC else 1.0 / 12.0
+    expect = (0.1 / float(alpha[0])) ** 2 * d * (t * t + noise)
     assert abs(host(d_ns)[0] / expect - 1.0) < 0.05
     del g, x
     torch.cuda.empty_cache()
