@@ -712,12 +712,14 @@ def test_single_worker_full_int32_range():
         assert out["sat_count"][0] == 40 * 9
 
 
-def test_graph_replay_of_a_whole_step():
+@pytest.mark.parametrize("d", [1_000_003, (1 << 22) + 1027], ids=["tile-sweep", "two-phase-sweep"])
+def test_graph_replay_of_a_whole_step(d):
     """A nearest-even step (sweep + final sums + alpha rule) captured in a HIP graph and
     replayed with fresh gradients: every replay equals the eager result (no memset nodes,
-    no allocation, nothing zeroed between launches)."""
-    w = W.config(2).scaled(1_000_003)
+    no allocation, nothing zeroed between launches).  Both forms of the sweep."""
+    w = W.config(2).scaled(d)
     desc = P.Desc(w.d, w.n, clip=w.clip)
+    assert P.intsgd_fused_step_form(desc) == (2 if d >= (1 << 22) else 1)
     P.intsgd_prepare(desc)
     st_g = Stepper(desc, eta=w.eta, device=DEV)
     st_e = Stepper(desc, eta=w.eta, device=DEV)
