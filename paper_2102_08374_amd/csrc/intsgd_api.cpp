@@ -271,9 +271,12 @@ uint32_t lds_reserve_for(uint32_t k) {
   return kLdsPerCu / (k + 1) + 1024u;
 }
 
-intsgd_status make_tiling(const intsgd_desc* desc, void* stream, Tiling* t) {
+intsgd_status make_tiling(const intsgd_desc* desc, void* stream, Tiling* t,
+                          uint32_t automatic_tile = 0) {
   const intsgd_tuning tune = effective_tuning(desc);
-  const uint32_t tile = tune.tile_coords;
+  // a kernel may have its own automatic tile; an explicit override still wins
+  const uint32_t tile =
+      (automatic_tile != 0 && g_tuning.tile_coords == 0) ? automatic_tile : tune.tile_coords;
   t->tm.d = desc->d;
   t->tm.tile = tile;
   if (desc->num_blocks == 1) {
@@ -432,8 +435,13 @@ intsgd_status intsgd_compress(const intsgd_desc* desc, const float* const* grads
   INTSGD_TRY(validate_worker_ptrs((const void* const*)q_out, desc->n));
   if (alpha == nullptr || sat_count == nullptr) return INTSGD_EINVAL;
   INTSGD_TRY(validate_workspace(desc, workspace, workspace_bytes));
+  // measured on MI355X (one worker, d = 108 M): the byte-wide wire wants more coordinates per
+  // workgroup (its stores are a quarter as wide), randomized rounding more again
+  const bool random = desc->rounding == INTSGD_ROUND_STOCHASTIC;
+  const uint32_t compress_tile = desc->wire == INTSGD_WIRE_INT8 ? (random ? 16384u : 8192u)
+                                                                : (random ? 8192u : 2048u);
   Tiling t;
-  INTSGD_TRY(make_tiling(desc, hip_stream, &t));
+  INTSGD_TRY(make_tiling(desc, hip_stream, &t, compress_tile));
   WorkerPtrs g;
   WorkerOutPtrs q;
   fill_ptrs(&g, (const void* const*)grads, desc->n);
