@@ -271,6 +271,15 @@ uint32_t lds_reserve_for(uint32_t k) {
   return kLdsPerCu / (k + 1) + 1024u;
 }
 
+// Automatic tile of the per-worker compress kernel.  Measured on MI355X (one worker,
+// d = 108 M): the byte-wide wire wants more coordinates per workgroup (its stores are a
+// quarter as wide), randomized rounding more again.
+uint32_t compress_tile(const intsgd_desc* desc) {
+  const bool random = desc->rounding == INTSGD_ROUND_STOCHASTIC;
+  if (desc->wire == INTSGD_WIRE_INT8) return random ? 16384u : 8192u;
+  return random ? 8192u : 2048u;
+}
+
 intsgd_status make_tiling(const intsgd_desc* desc, void* stream, Tiling* t,
                           uint32_t automatic_tile = 0) {
   const intsgd_tuning tune = effective_tuning(desc);
@@ -418,7 +427,11 @@ intsgd_status intsgd_prepare(const intsgd_desc* desc) {
   INTSGD_TRY(validate_desc(desc));
   if (desc->num_blocks == 1) return INTSGD_OK;
   const DevicePlan* plan = nullptr;
-  return get_plan(desc, effective_tuning(desc).tile_coords, &plan);
+  const uint32_t sweep_tile = effective_tuning(desc).tile_coords;
+  INTSGD_TRY(get_plan(desc, sweep_tile, &plan));
+  // the compress kernel picks its own tile unless the tuning fixes one
+  const uint32_t other = g_tuning.tile_coords == 0 ? compress_tile(desc) : sweep_tile;
+  return other == sweep_tile ? INTSGD_OK : get_plan(desc, other, &plan);
 }
 
 void intsgd_release(void) {
@@ -435,13 +448,8 @@ intsgd_status intsgd_compress(const intsgd_desc* desc, const float* const* grads
   INTSGD_TRY(validate_worker_ptrs((const void* const*)q_out, desc->n));
   if (alpha == nullptr || sat_count == nullptr) return INTSGD_EINVAL;
   INTSGD_TRY(validate_workspace(desc, workspace, workspace_bytes));
-  // measured on MI355X (one worker, d = 108 M): the byte-wide wire wants more coordinates per
-  // workgroup (its stores are a quarter as wide), randomized rounding more again
-  const bool random = desc->rounding == INTSGD_ROUND_STOCHASTIC;
-  const uint32_t compress_tile = desc->wire == INTSGD_WIRE_INT8 ? (random ? 16384u : 8192u)
-                                                                : (random ? 8192u : 2048u);
   Tiling t;
-  INTSGD_TRY(make_tiling(desc, hip_stream, &t, compress_tile));
+  INTSGD_TRY(make_tiling(desc, hip_stream, &t, compress_tile(desc)));
   WorkerPtrs g;
   WorkerOutPtrs q;
   fill_ptrs(&g, (const void* const*)grads, desc->n);
