@@ -853,3 +853,71 @@ def test_two_phase_needs_one_block_and_enough_coordinates():
     w = W.config(4).scaled(scaled_blocks(0)[-1], block_offsets=scaled_blocks(0))
     lockstep_run(w, steps=2)
     lockstep_run(W.config(2).scaled(100_003), steps=2)
+
+
+# --------------------------------------------------------------------------- random shapes
+def _random_partition(rng, d):
+    """Block offsets with a mix of tiny, unaligned and large blocks."""
+    cuts = set()
+    for _ in range(int(rng.integers(1, 12))):
+        cuts.add(int(rng.integers(1, d)))
+    if rng.random() < 0.5 and d > 40:                   # a run of tiny blocks
+        a = int(rng.integers(1, d - 20))
+        cuts.update(range(a, a + int(rng.integers(2, 12))))
+    return [0] + sorted(c for c in cuts if 0 < c < d) + [d]
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes_partitions_and_tunings(seed):
+    """Seeded random draws of (d, n, partition, rounding, wire, clip, tile, grid cap): the
+    fused step, the two-pass form and the unfused chain against the oracle.  Unaligned row
+    starts inside the gradient buffer are part of the draw."""
+    rng = np.random.default_rng(1000 + seed)
+    d = int(rng.choice([1, 3, 7, 1023, 1025, 4099, 20011, 65537, 150001, 262144 + 3]))
+    n = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 9, 13, 16, 17, 32]))
+    offsets = None if (d < 8 or rng.random() < 0.35) else _random_partition(rng, d)
+    rounding = int(rng.integers(0, 2))
+    wire = int(rng.choice([P.WIRE_INT8, P.WIRE_INT32]))
+    L = int(rng.choice([1, 15, 127])) if wire == P.WIRE_INT8 else int(rng.choice([1, 1000, P.default_clip(n)]))
+    tile = int(rng.choice([0, 1024, 2048, 4096, 8192]))
+    grid = int(rng.choice([0, 1, 3, 64]))
+    wgs = int(rng.choice([0, 2, 4, 8]))
+    P.intsgd_set_tuning(tile, grid, wgs)
+    alpha, g, x = make_case(d, n, offsets, seed=seed)
+    B = alpha.size
+    off_np = None if offsets is None else np.array(offsets, np.uint64)
+    eta, pseed, step = 0.05, (seed << 33) | 12345, seed + 1
+    out = oracle.step(list(g), alpha, x, rounding=rounding, L=L, eta=eta, seed=pseed, step=step,
+                      offsets=off_np)
+    desc = P.Desc(d, n, rounding=rounding, wire=wire, clip=L, seed=pseed, step=step,
+                  block_offsets=offsets)
+    ws = P.new_workspace(desc, DEV)
+    rows = rows_on_device(g)
+    d_a = dev(alpha)
+    # fused
+    d_x = dev(x)
+    d_ns = torch.zeros(B, dtype=torch.float64, device=DEV)
+    d_cnt = torch.zeros(n, dtype=torch.int64, device=DEV)
+    P.intsgd_step_fused(desc, rows, d_a, eta, d_x, d_ns, d_cnt, ws)
+    assert_within_ulp(host(d_x), out["x_new"], 1, "fused x")
+    assert u64(d_cnt).tolist() == out["sat_count"].tolist()
+    assert rel_err(host(d_ns), out["normsq"]) <= NORM_RTOL or float(np.max(out["normsq"])) == 0.0
+    # two-pass
+    d_S = torch.full((d,), -7, dtype=torch.int32, device=DEV)
+    d_cnt2 = torch.zeros(n, dtype=torch.int64, device=DEV)
+    P.intsgd_compress_sum(desc, rows, d_a, d_S, d_cnt2, ws)
+    assert np.array_equal(host(d_S), out["S"])
+    assert u64(d_cnt2).tolist() == out["sat_count"].tolist()
+    d_x2 = dev(x)
+    d_ns2 = torch.zeros(B, dtype=torch.float64, device=DEV)
+    P.intsgd_decode_update_norm(desc, d_S, d_a, eta, d_x2, d_ns2, ws)
+    assert torch.equal(d_x2, d_x)
+    # unfused
+    qdt = torch.int8 if wire == P.WIRE_INT8 else torch.int32
+    qs = [torch.full((d + 16,), -5, dtype=qdt, device=DEV)[:d] for _ in range(n)]
+    d_cnt3 = torch.zeros(n, dtype=torch.int64, device=DEV)
+    P.intsgd_compress(desc, rows, d_a, qs, d_cnt3, ws)
+    assert u64(d_cnt3).tolist() == out["sat_count"].tolist()
+    d_S3 = torch.full((d,), -7, dtype=torch.int32, device=DEV)
+    P.intsgd_int_sum(desc, qs, d_S3)
+    assert np.array_equal(host(d_S3), out["S"])
