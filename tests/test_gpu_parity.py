@@ -921,3 +921,49 @@ def test_random_shapes_partitions_and_tunings(seed):
     d_S3 = torch.full((d,), -7, dtype=torch.int32, device=DEV)
     P.intsgd_int_sum(desc, qs, d_S3)
     assert np.array_equal(host(d_S3), out["S"])
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_shapes_momentum_and_diana(seed):
+    """The widened forms on seeded random shapes, partitions and tunings."""
+    rng = np.random.default_rng(5000 + seed)
+    d = int(rng.choice([5, 1023, 4099, 20011, 65537, 150001]))
+    n = int(rng.choice([1, 2, 3, 5, 8, 9, 16, 20]))
+    offsets = None if (d < 8 or rng.random() < 0.35) else _random_partition(rng, d)
+    rounding = int(rng.integers(0, 2))
+    L = int(rng.choice([1, 1000, P.default_clip(n)]))
+    P.intsgd_set_tuning(int(rng.choice([0, 1024, 4096])), int(rng.choice([0, 2, 64])),
+                        int(rng.choice([0, 2, 8])))
+    alpha, g, x = make_case(d, n, offsets, seed=77 + seed)
+    B = alpha.size
+    off_np = None if offsets is None else np.array(offsets, np.uint64)
+    eta, mu, wd, pseed, step = 0.05, 0.9, 1e-4, 31 + seed, 3 + seed
+    m = rng.normal(0, 0.01, d).astype(F32)
+    desc = P.Desc(d, n, rounding=rounding, clip=L, seed=pseed, step=step, block_offsets=offsets)
+    ws = P.new_workspace(desc, DEV)
+    rows = rows_on_device(g)
+    # momentum form
+    out = oracle.step_momentum(list(g), alpha, x, m, rounding=rounding, L=L, eta=eta, mu=mu, wd=wd,
+                               seed=pseed, step=step, offsets=off_np)
+    d_x, d_m, d_a = dev(x), dev(m), dev(alpha)
+    d_ns = torch.zeros(B, dtype=torch.float64, device=DEV)
+    d_cnt = torch.zeros(n, dtype=torch.int64, device=DEV)
+    P.intsgd_step_momentum(desc, rows, d_a, eta, mu, wd, d_x, d_m, None, 0.0, 0.0, d_ns, d_cnt, ws)
+    assert_within_ulp(host(d_x), out["x_new"], 1, "x")
+    assert_within_ulp(host(d_m), out["m_new"], 1, "m")
+    assert u64(d_cnt).tolist() == out["sat_count"].tolist()
+    assert rel_err(host(d_ns), out["normsq"]) <= NORM_RTOL
+    # IntDIANA
+    hl = rng.normal(0, 0.01, (n, d)).astype(F32)
+    h = hl.astype(np.float64).mean(0).astype(F32)
+    out = oracle.diana_step(list(g), list(hl), alpha, x, h, rounding=rounding, L=L, eta=eta,
+                            seed=pseed, step=step, offsets=off_np)
+    d_hl = rows_on_device(hl)
+    d_x, d_h = dev(x), dev(h)
+    P.intsgd_diana_step(desc, rows, d_hl, d_a, eta, d_x, d_h, None, 0.0, 0.0, d_ns, d_cnt, ws)
+    assert u64(d_cnt).tolist() == out["sat_count"].tolist()
+    for i in range(n):
+        assert_within_ulp(host(d_hl[i]), out["h_local_new"][i], 1, "local shift %d" % i)
+    assert_within_ulp(host(d_h), out["h_new"], 1, "global shift")
+    assert_within_ulp(host(d_x), out["x_new"], 1, "x (diana)")
+    assert rel_err(host(d_ns), out["normsq"]) <= NORM_RTOL
