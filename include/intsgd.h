@@ -284,7 +284,8 @@ intsgd_status intsgd_heuristic_alpha(const intsgd_desc* desc, const float* const
  *                      intsgd_step_momentum, intsgd_compress_sum; one block, d >= 2^22):
  *                      1 = always the tile sweep, 2 = always the two-phase sweep (gradient
  *                      reads, then the write-back, with the integer sums held in registers
- *                      in between), 0 = automatic (two-phase for nearest-even rounding).
+ *                      in between), 0 = automatic (two-phase for nearest-even rounding
+ *                      with more than 8 or fewer than 3 workers).
  *                      intsgd_int_sum follows it too: automatic = two-phase for int8 */
 typedef struct intsgd_tuning {
   uint32_t tile_coords;

@@ -29,29 +29,32 @@ constexpr uint32_t kLdsPerCu = 160u * 1024u;    // gfx950
 // Process-wide overrides; a zero field means "automatic".
 intsgd_tuning g_tuning = {0, 0, 0, 0};
 
-// Automatic choices, measured on MI355X.  Nearest-even rounding is bound by HBM and
-// likes few, large bursts in flight: 8 KB per stream and workgroup, two resident
-// workgroups of 512 threads per CU.  Randomized rounding is co-bound by the integer
-// ALU (Philox) and needs more wavefronts to keep it busy: 16 KB tiles, four per CU.
+// Automatic choices of the tile sweeps, measured on MI355X.  Nearest-even rounding is bound by
+// HBM: 8 KB per stream and workgroup, and as few resident workgroups as keep enough loads in
+// flight: two of 512 threads per CU when a thread has two groups of eight worker loads to
+// issue (n > 8), four when it has at most one (at n = 8: 82 % of peak against 76 %).
+// Randomized rounding is co-bound by the integer ALU (Philox) and needs more wavefronts to
+// keep it busy: 16 KB tiles, four workgroups per CU.
 intsgd_tuning effective_tuning(const intsgd_desc* desc) {
   const bool random = desc->rounding == INTSGD_ROUND_STOCHASTIC;
   intsgd_tuning t = g_tuning;
   if (t.tile_coords == 0) t.tile_coords = random ? 4096 : 2048;
   if (t.max_workgroups == 0) t.max_workgroups = kMaxGrid;
-  if (t.workgroups_per_cu == 0) t.workgroups_per_cu = random ? 4 : 2;
+  if (t.workgroups_per_cu == 0) t.workgroups_per_cu = (random || desc->n <= 8) ? 4 : 2;
   return t;
 }
 
 // The two-phase sweep needs one block and enough coordinates to give every CU a chunk.
 // Automatic choice: nearest-even rounding only (randomized rounding is co-bound by the
-// integer ALU in its read phase and gains nothing from separating the phases).
+// integer ALU in its read phase and gains nothing from separating the phases), and not for
+// 3..8 workers, where a thread of the tile sweep has all its loads in one group and four
+// resident workgroups per CU stream as fast or faster (n = 8: 81-85 % against 78-82 %).
 constexpr uint64_t kMinPhasedD = 1ull << 22;
 bool use_two_phase(const intsgd_desc* desc, const intsgd_tuning& t) {
   if (desc->num_blocks != 1 || desc->d < kMinPhasedD || t.two_phase == 1) return false;
   if (t.two_phase == 2) return true;
-  return desc->rounding == INTSGD_ROUND_NEAREST_EVEN;
+  return desc->rounding == INTSGD_ROUND_NEAREST_EVEN && (desc->n > 8 || desc->n <= 2);
 }
-
 
 thread_local std::string t_hip_error;
 thread_local hipEvent_t t_tap_start = nullptr, t_tap_stop = nullptr;

@@ -260,6 +260,8 @@ def test_fused_step_form_policy():
         assert P.intsgd_fused_step_form(P.Desc(big, 8, rounding=P.ROUND_STOCHASTIC)) == 1
         blocks = P.Desc(big, 8, rounding=P.ROUND_NEAREST_EVEN, block_offsets=[0, 1000, big])
         assert P.intsgd_fused_step_form(blocks) == 1
+        for n, form in [(1, 2), (2, 2), (3, 1), (8, 1), (9, 2), (128, 2)]:
+            assert P.intsgd_fused_step_form(P.Desc(big, n, rounding=P.ROUND_NEAREST_EVEN)) == form
         P.intsgd_set_tuning(two_phase=2)
         assert P.intsgd_fused_step_form(P.Desc(big, 8, rounding=P.ROUND_STOCHASTIC)) == 2
         assert P.intsgd_fused_step_form(blocks) == 1
