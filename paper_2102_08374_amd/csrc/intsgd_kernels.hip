@@ -8,12 +8,17 @@
 //   * gradient streams are read non-temporally, up to 8 independent loads in flight
 //     per lane; x is written through (sc1) so that no dirty lines pile up in L2;
 //   * the integer aggregate stays in registers in the fused forms;
-//   * a workgroup is 512 threads and normally handles ONE tile of 2048 coordinates
-//     (8 KB per stream), and residency is capped (by an LDS reservation) at two
-//     workgroups per CU: with a write stream mixed into the reads, fewer, larger
-//     requests in flight measured faster than full occupancy;
-//   * the sweep writes one norm partial per tile and (only where something clipped) a
-//     row of clip counts per workgroup; a one-workgroup kernel right behind it on the
+//   * two forms of the fused sweep.  Tile sweep (any partition, both rounding modes): a
+//     workgroup is 512 threads and handles ONE tile of 2048 or 4096 coordinates, and
+//     residency is capped (by an LDS reservation) at two or four workgroups per CU:
+//     with a write stream mixed into the reads, fewer, larger requests in flight measured
+//     faster than full occupancy.  Two-phase sweep (one block): one persistent workgroup
+//     of 1024 threads per CU alternates between reading the gradient streams, with the
+//     sums of 12 quads per thread kept in registers, and updating x for the same quads,
+//     so that the chip as a whole alternates between a read-only stream and a short
+//     read-modify-write burst;
+//   * the sweep writes one norm partial per tile (or workgroup) and, only where something
+//     clipped, a row of clip counts per workgroup; a small kernel right behind it on the
 //     stream sums them in a fixed order and applies the alpha rule.  (Electing the
 //     sweep's last workgroup with a ticket instead was measured 3x slower: the
 //     device-scope release fence every workgroup then needs walks the L2.)
