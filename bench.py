@@ -254,7 +254,8 @@ def main():
     elif args.mode == "unfused":
         kernel_name = "k_compress<ROUND, WIRE>: a1-a3 for all n workers (first of the five calls)"
     elif args.mode != "fused":
-        kernel_name = "k_aggregate<ROUND, FUSED=false>: a1-a4 (first of the two sweeps)"
+        kernel_name = ("k_aggregate_phased<ROUND, sum only>" if P.intsgd_fused_step_form(desc) == 2
+                       else "k_aggregate<ROUND, FUSED=false>") + ": a1-a4 (first of the two sweeps)"
     elif P.intsgd_fused_step_form(desc) == 2:
         kernel_name = "k_aggregate_phased<ROUND, MOMENTUM>: a1-a7, gradient reads then x update per round"
     else:
