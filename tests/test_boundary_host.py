@@ -271,3 +271,26 @@ def test_fused_step_form_policy():
         assert lib.intsgd_fused_step_form(None) == 0
     finally:
         P.intsgd_set_tuning(*before)
+
+
+def test_traffic_table_keys_match_workload_names():
+    """bench.py looks HBM traffic up by "<workload name>/<sweep form>"; the committed table
+    must use names the workload recipes really have."""
+    import json
+    import os
+
+    from paper_2102_08374_amd import workloads as W
+    path = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "profiles",
+                        "traffic.json")
+    with open(path) as fh:
+        table = json.load(fh)
+    names = {W.config(i).name for i in range(1, 6)} | {W.config(4, per_bucket=False).name}
+    keys = [k for k in table if not k.startswith("_")]
+    assert keys, "empty traffic table"
+    for k in keys:
+        name, form = k.rsplit("/", 1)
+        assert name in names, k
+        assert form in ("tile", "two_phase"), k
+        assert table[k]["bytes_per_launch"] == table[k]["fetch_bytes"] + table[k]["write_bytes"]
+    # the headline workload has the entry bench.py reports by default
+    assert W.config(2).name + "/two_phase" in table
