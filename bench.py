@@ -55,7 +55,7 @@ def parse():
     return ap.parse_args()
 
 
-def cpu_baseline(w, rows, alpha_host, x_host, max_wc=420_000_000, steps=4, threads=1):
+def cpu_baseline(w, rows, alpha_host, x_host, max_wc=420_000_000, steps=6, threads=1):
     """The oracle as it stands on a bounded sample of the same workload: `steps`
     consecutive steps on the leading slice of at most max_wc worker-coordinates (the whole
     vector when it is small enough); reported in the metric's unit.  One thread by default;
