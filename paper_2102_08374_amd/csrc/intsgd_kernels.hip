@@ -1006,7 +1006,15 @@ __global__ __launch_bounds__(kThreads) void k_heuristic_alpha(const uint32_t* ti
   if (threadIdx.x == 0) lds_max = 0u;
   __syncthreads();
   uint32_t best = 0;
-  for (uint32_t t = t0 + threadIdx.x; t < t1; t += kThreads) best = max(best, tile_max[t]);
+  uint32_t t = t0 + threadIdx.x;
+  for (; t + 7u * kThreads < t1; t += 8u * kThreads) {          // eight loads in flight: pure latency
+    uint32_t v[8];
+#pragma unroll
+    for (uint32_t u = 0; u < 8; ++u) v[u] = tile_max[t + u * kThreads];
+#pragma unroll
+    for (uint32_t u = 0; u < 8; ++u) best = max(best, v[u]);
+  }
+  for (; t < t1; t += kThreads) best = max(best, tile_max[t]);
   if (best != 0u) atomicMax(&lds_max, best);
   __syncthreads();
   if (threadIdx.x != 0) return;
