@@ -100,10 +100,11 @@ typedef struct intsgd_desc {
  * workspace needs for this descriptor; 0 if the descriptor is invalid. */
 size_t intsgd_workspace_bytes(const intsgd_desc* desc);
 
-/* Profiling aid.  The next call of THIS thread that launches a streaming kernel
- * records `start_event` right before and `stop_event` right after that kernel (not
- * around the small final-sum kernel that follows it) on the call's stream, then
- * forgets both.  Pass hipEvent_t handles as void*; NULL clears a pending tap. */
+/* Profiling aid.  The next call of THIS thread that launches a streaming kernel attaches
+ * `start_event` and `stop_event` to that kernel's dispatch on the call's stream (not to
+ * the small final-sum kernel that follows it), so that hipEventElapsedTime(start, stop)
+ * is that kernel's duration; then it forgets both.  Pass hipEvent_t handles as void*:
+ * both non-NULL to arm a tap, both NULL to clear a pending one (one of each: EINVAL). */
 intsgd_status intsgd_tap_next_launch(void* start_event, void* stop_event);
 
 /* Validates the descriptor and builds the library's tile table for its partition

@@ -421,6 +421,7 @@ size_t intsgd_workspace_bytes(const intsgd_desc* desc) {
 }
 
 intsgd_status intsgd_tap_next_launch(void* start_event, void* stop_event) {
+  if ((start_event == nullptr) != (stop_event == nullptr)) return INTSGD_EINVAL;
   t_tap_start = static_cast<hipEvent_t>(start_event);
   t_tap_stop = static_cast<hipEvent_t>(stop_event);
   return INTSGD_OK;

@@ -29,6 +29,7 @@
 // everything in between moves as aligned quads.
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "intsgd_internal.h"
@@ -1365,15 +1366,17 @@ __global__ __launch_bounds__(256) void k_next_alpha(const double* norm_sq, Alpha
 inline hipError_t after_launch() { return hipGetLastError(); }
 
 // Records the optional profiling taps around the streaming kernel of a call.
-struct Tapped {
-  const LaunchShape& ls;
-  explicit Tapped(const LaunchShape& shape) : ls(shape) {
-    if (ls.tap_start) (void)hipEventRecord(ls.tap_start, ls.stream);
-  }
-  ~Tapped() {
-    if (ls.tap_stop) (void)hipEventRecord(ls.tap_stop, ls.stream);
-  }
-};
+// Launches a streaming kernel.  With profiling taps pending, the two events are attached to
+// the dispatch itself, so that their difference is the kernel's own duration (what a profiler
+// reports) and not kernel + dispatch latency.
+#define launch_sweep(ls, kernel, grid, block, lds, ...)                                          \
+  do {                                                                                           \
+    if ((ls).tap_start != nullptr && (ls).tap_stop != nullptr)                                   \
+      hipExtLaunchKernelGGL(kernel, grid, block, lds, (ls).stream, (ls).tap_start, (ls).tap_stop, \
+                            0u, __VA_ARGS__);                                                    \
+    else                                                                                         \
+      hipLaunchKernelGGL(kernel, grid, block, lds, (ls).stream, __VA_ARGS__);                    \
+  } while (0)
 
 constexpr uint32_t kChunk = 8192;            // partials per first-level workgroup
 constexpr uint32_t kTwoLevelFrom = 2 * kChunk;
@@ -1407,13 +1410,12 @@ hipError_t launch_compress(const TileMap& tm, const LaunchShape& ls, uint32_t n,
   const dim3 grid(ls.grid, n), block(kThreads);
   const bool random = rs.rounding == INTSGD_ROUND_STOCHASTIC;
   {
-    Tapped tap(ls);
     if (wire == INTSGD_WIRE_INT8) {
-      if (random) hipLaunchKernelGGL((k_compress<1, 8>), grid, block, ls.lds_reserve, ls.stream, a);
-      else hipLaunchKernelGGL((k_compress<0, 8>), grid, block, ls.lds_reserve, ls.stream, a);
+      if (random) launch_sweep(ls, (k_compress<1, 8>), grid, block, ls.lds_reserve, a);
+      else launch_sweep(ls, (k_compress<0, 8>), grid, block, ls.lds_reserve, a);
     } else {
-      if (random) hipLaunchKernelGGL((k_compress<1, 32>), grid, block, ls.lds_reserve, ls.stream, a);
-      else hipLaunchKernelGGL((k_compress<0, 32>), grid, block, ls.lds_reserve, ls.stream, a);
+      if (random) launch_sweep(ls, (k_compress<1, 32>), grid, block, ls.lds_reserve, a);
+      else launch_sweep(ls, (k_compress<0, 32>), grid, block, ls.lds_reserve, a);
     }
   }
   hipError_t e = after_launch();
@@ -1427,9 +1429,8 @@ hipError_t launch_int_sum_phased(const PhasedShape& ps, const LaunchShape& ls, u
                                  int32_t wire, const WorkerPtrs& q, int32_t* sum_out) {
   IntSumArgs a{d, n, sum_out, q};
   const dim3 grid(ps.grid), block(kPhasedThreads);
-  Tapped tap(ls);
-  if (wire == INTSGD_WIRE_INT8) hipLaunchKernelGGL((k_int_sum_phased<8>), grid, block, 0, ls.stream, a);
-  else hipLaunchKernelGGL((k_int_sum_phased<32>), grid, block, 0, ls.stream, a);
+  if (wire == INTSGD_WIRE_INT8) launch_sweep(ls, (k_int_sum_phased<8>), grid, block, 0, a);
+  else launch_sweep(ls, (k_int_sum_phased<32>), grid, block, 0, a);
   return after_launch();
 }
 
@@ -1437,9 +1438,8 @@ hipError_t launch_int_sum(uint64_t d, const LaunchShape& ls, uint32_t n, int32_t
                           const WorkerPtrs& q, int32_t* sum_out) {
   IntSumArgs a{d, n, sum_out, q};
   const dim3 grid(ls.grid), block(kThreads);
-  Tapped tap(ls);
-  if (wire == INTSGD_WIRE_INT8) hipLaunchKernelGGL((k_int_sum<8>), grid, block, 0, ls.stream, a);
-  else hipLaunchKernelGGL((k_int_sum<32>), grid, block, 0, ls.stream, a);
+  if (wire == INTSGD_WIRE_INT8) launch_sweep(ls, (k_int_sum<8>), grid, block, 0, a);
+  else launch_sweep(ls, (k_int_sum<32>), grid, block, 0, a);
   return after_launch();
 }
 
@@ -1448,9 +1448,8 @@ hipError_t launch_decode_update(const TileMap& tm, const LaunchShape& ls, uint32
                                 float* gtilde_out) {
   DecodeArgs a{tm, n, sum, alpha, eta, x, gtilde_out, nullptr, 0.0, 0.0, Finish{}};
   const dim3 grid(ls.grid), block(kThreads);
-  Tapped tap(ls);
-  if (gtilde_out) hipLaunchKernelGGL((k_decode<false, true, false>), grid, block, 0, ls.stream, a);
-  else hipLaunchKernelGGL((k_decode<false, false, false>), grid, block, 0, ls.stream, a);
+  if (gtilde_out) launch_sweep(ls, (k_decode<false, true, false>), grid, block, 0, a);
+  else launch_sweep(ls, (k_decode<false, false, false>), grid, block, 0, a);
   return after_launch();
 }
 
@@ -1458,8 +1457,7 @@ hipError_t launch_update_norm(const TileMap& tm, const LaunchShape& ls, const fl
                               const float* x_old, const Finish& fin) {
   NormArgs a{tm, x_new, x_old, fin};
   {
-    Tapped tap(ls);
-    hipLaunchKernelGGL(k_update_norm, dim3(ls.grid), dim3(kThreads), 0, ls.stream, a);
+    launch_sweep(ls, k_update_norm, dim3(ls.grid), dim3(kThreads), 0, a);
   }
   hipError_t e = after_launch();
   if (e != hipSuccess) return e;
@@ -1472,11 +1470,10 @@ hipError_t launch_compress_sum(const TileMap& tm, const LaunchShape& ls, uint32_
   AggregateArgs a{tm, rs, n, alpha, 0.0, nullptr, sum_out, nullptr, 0.0, 0.0, fin, grads};
   const dim3 grid(ls.grid), block(kThreads);
   {
-    Tapped tap(ls);
     if (rs.rounding == INTSGD_ROUND_STOCHASTIC)
-      hipLaunchKernelGGL((k_aggregate<1, false, false>), grid, block, ls.lds_reserve, ls.stream, a);
+      launch_sweep(ls, (k_aggregate<1, false, false>), grid, block, ls.lds_reserve, a);
     else
-      hipLaunchKernelGGL((k_aggregate<0, false, false>), grid, block, ls.lds_reserve, ls.stream, a);
+      launch_sweep(ls, (k_aggregate<0, false, false>), grid, block, ls.lds_reserve, a);
   }
   hipError_t e = after_launch();
   if (e != hipSuccess) return e;
@@ -1489,11 +1486,10 @@ hipError_t launch_decode_update_norm(const TileMap& tm, const LaunchShape& ls, u
   DecodeArgs a{tm, n, sum, alpha, eta, x, nullptr, mom ? mom->m : nullptr, mom ? mom->mu : 0.0,
                mom ? mom->wd : 0.0, fin};
   {
-    Tapped tap(ls);
     if (mom)
-      hipLaunchKernelGGL((k_decode<true, false, true>), dim3(ls.grid), dim3(kThreads), 0, ls.stream, a);
+      launch_sweep(ls, (k_decode<true, false, true>), dim3(ls.grid), dim3(kThreads), 0, a);
     else
-      hipLaunchKernelGGL((k_decode<true, false, false>), dim3(ls.grid), dim3(kThreads), 0, ls.stream, a);
+      launch_sweep(ls, (k_decode<true, false, false>), dim3(ls.grid), dim3(kThreads), 0, a);
   }
   hipError_t e = after_launch();
   if (e != hipSuccess) return e;
@@ -1508,13 +1504,12 @@ hipError_t launch_step_fused(const TileMap& tm, const LaunchShape& ls, uint32_t 
   const dim3 grid(ls.grid), block(kThreads);
   const bool random = rs.rounding == INTSGD_ROUND_STOCHASTIC;
   {
-    Tapped tap(ls);
     if (mom) {
-      if (random) hipLaunchKernelGGL((k_aggregate<1, true, true>), grid, block, ls.lds_reserve, ls.stream, a);
-      else hipLaunchKernelGGL((k_aggregate<0, true, true>), grid, block, ls.lds_reserve, ls.stream, a);
+      if (random) launch_sweep(ls, (k_aggregate<1, true, true>), grid, block, ls.lds_reserve, a);
+      else launch_sweep(ls, (k_aggregate<0, true, true>), grid, block, ls.lds_reserve, a);
     } else {
-      if (random) hipLaunchKernelGGL((k_aggregate<1, true, false>), grid, block, ls.lds_reserve, ls.stream, a);
-      else hipLaunchKernelGGL((k_aggregate<0, true, false>), grid, block, ls.lds_reserve, ls.stream, a);
+      if (random) launch_sweep(ls, (k_aggregate<1, true, false>), grid, block, ls.lds_reserve, a);
+      else launch_sweep(ls, (k_aggregate<0, true, false>), grid, block, ls.lds_reserve, a);
     }
   }
   hipError_t e = after_launch();
@@ -1534,13 +1529,12 @@ hipError_t launch_step_fused_phased(const PhasedShape& ps, const LaunchShape& ls
   const dim3 grid(ps.grid), block(kPhasedThreads);
   const bool random = rs.rounding == INTSGD_ROUND_STOCHASTIC;
   {
-    Tapped tap(ls);
     if (mom) {
-      if (random) hipLaunchKernelGGL((k_aggregate_phased<1, kPhasedMomentum>), grid, block, 0, ls.stream, a);
-      else hipLaunchKernelGGL((k_aggregate_phased<0, kPhasedMomentum>), grid, block, 0, ls.stream, a);
+      if (random) launch_sweep(ls, (k_aggregate_phased<1, kPhasedMomentum>), grid, block, 0, a);
+      else launch_sweep(ls, (k_aggregate_phased<0, kPhasedMomentum>), grid, block, 0, a);
     } else {
-      if (random) hipLaunchKernelGGL((k_aggregate_phased<1, kPhasedUpdate>), grid, block, 0, ls.stream, a);
-      else hipLaunchKernelGGL((k_aggregate_phased<0, kPhasedUpdate>), grid, block, 0, ls.stream, a);
+      if (random) launch_sweep(ls, (k_aggregate_phased<1, kPhasedUpdate>), grid, block, 0, a);
+      else launch_sweep(ls, (k_aggregate_phased<0, kPhasedUpdate>), grid, block, 0, a);
     }
   }
   hipError_t e = after_launch();
@@ -1557,11 +1551,10 @@ hipError_t launch_compress_sum_phased(const PhasedShape& ps, const LaunchShape& 
   PhasedArgs a{rs, n, alpha, 0.0, nullptr, nullptr, 0.0, 0.0, sum_out, d, fin, grads};
   const dim3 grid(ps.grid), block(kPhasedThreads);
   {
-    Tapped tap(ls);
     if (rs.rounding == INTSGD_ROUND_STOCHASTIC)
-      hipLaunchKernelGGL((k_aggregate_phased<1, kPhasedSumOnly>), grid, block, 0, ls.stream, a);
+      launch_sweep(ls, (k_aggregate_phased<1, kPhasedSumOnly>), grid, block, 0, a);
     else
-      hipLaunchKernelGGL((k_aggregate_phased<0, kPhasedSumOnly>), grid, block, 0, ls.stream, a);
+      launch_sweep(ls, (k_aggregate_phased<0, kPhasedSumOnly>), grid, block, 0, a);
   }
   hipError_t e = after_launch();
   if (e != hipSuccess) return e;
@@ -1575,11 +1568,10 @@ hipError_t launch_diana_step(const TileMap& tm, const LaunchShape& ls, uint32_t 
   DianaArgs a{tm, rs, n, alpha, eta, x, h, fin, grads, h_local};
   const dim3 grid(ls.grid), block(kThreads);
   {
-    Tapped tap(ls);
     if (rs.rounding == INTSGD_ROUND_STOCHASTIC)
-      hipLaunchKernelGGL((k_diana<1>), grid, block, ls.lds_reserve, ls.stream, a);
+      launch_sweep(ls, (k_diana<1>), grid, block, ls.lds_reserve, a);
     else
-      hipLaunchKernelGGL((k_diana<0>), grid, block, ls.lds_reserve, ls.stream, a);
+      launch_sweep(ls, (k_diana<0>), grid, block, ls.lds_reserve, a);
   }
   hipError_t e = after_launch();
   if (e != hipSuccess) return e;
@@ -1591,8 +1583,7 @@ hipError_t launch_heuristic_alpha(const TileMap& tm, const LaunchShape& ls, uint
                                   const uint32_t* tile_prefix, uint32_t B, float* alpha_out) {
   MaxAbsArgs a{tm, n, tile_max, grads};
   {
-    Tapped tap(ls);
-    hipLaunchKernelGGL(k_max_abs, dim3(ls.grid), dim3(kThreads), ls.lds_reserve, ls.stream, a);
+    launch_sweep(ls, k_max_abs, dim3(ls.grid), dim3(kThreads), ls.lds_reserve, a);
   }
   hipError_t e = after_launch();
   if (e != hipSuccess) return e;

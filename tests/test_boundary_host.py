@@ -294,3 +294,11 @@ def test_traffic_table_keys_match_workload_names():
         assert table[k]["bytes_per_launch"] == table[k]["fetch_bytes"] + table[k]["write_bytes"]
     # the headline workload has the entry bench.py reports by default
     assert W.config(2).name + "/two_phase" in table
+
+
+def test_tap_needs_both_events_or_none():
+    assert lib.intsgd_tap_next_launch(None, None) == 0
+    assert lib.intsgd_tap_next_launch(FAKE, None) == EINVAL
+    assert lib.intsgd_tap_next_launch(None, FAKE) == EINVAL
+    assert lib.intsgd_tap_next_launch(FAKE, FAKE) == 0
+    assert lib.intsgd_tap_next_launch(None, None) == 0      # clear it again
