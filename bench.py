@@ -235,11 +235,11 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
-    kernel_ms = sorted(hip.elapsed_ms(a, b) for a, b in ev) if not args.no_taps else [float("nan")]
+    kernel_ms = sorted(hip.elapsed_ms(a, b) for a, b in ev) if not args.no_taps else None
     for a, b in ev:
         hip.destroy(a)
         hip.destroy(b)
-    avg_kernel_ms = sum(kernel_ms) / len(kernel_ms)
+    avg_kernel_ms = sum(kernel_ms) / len(kernel_ms) if kernel_ms else None
     per_coord = (4 * w.n + 8) if args.mode == "fused" else (4 * w.n + 4)
     if args.mode == "unfused":
         per_coord = (4 + w.wire // 8) * w.n
@@ -248,7 +248,7 @@ def main():
     if args.diana:
         per_coord = 12 * w.n + 16
     algo_bytes = per_coord * w.d
-    achieved = algo_bytes / (avg_kernel_ms * 1e-3) / 1e9
+    achieved = algo_bytes / (avg_kernel_ms * 1e-3) / 1e9 if kernel_ms else None
     if args.diana:
         kernel_name = "k_diana<ROUND>: Algorithm 3 in one sweep"
     elif args.mode == "unfused":
@@ -289,13 +289,13 @@ def main():
         },
         "roofline": {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBS,
+            "frac": achieved / HBM_PEAK_GBS if kernel_ms else None,
             "traffic": None if (args.momentum or args.diana or args.mode != "fused")
                        else load_traffic(w.name, "two_phase" if P.intsgd_fused_step_form(desc) == 2 else "tile"),
             "kernel": kernel_name,
             "algorithmic_bytes_per_launch": algo_bytes,
-            "kernel_ms_avg": avg_kernel_ms, "kernel_ms_min": kernel_ms[0],
-            "kernel_ms_median": kernel_ms[len(kernel_ms) // 2],
+            "kernel_ms_avg": avg_kernel_ms, "kernel_ms_min": kernel_ms[0] if kernel_ms else None,
+            "kernel_ms_median": kernel_ms[len(kernel_ms) // 2] if kernel_ms else None,
         },
     }
     if not args.no_cpu_baseline and not args.momentum and not args.diana:
