@@ -967,3 +967,64 @@ def test_random_shapes_momentum_and_diana(seed):
     assert_within_ulp(host(d_h), out["h_new"], 1, "global shift")
     assert_within_ulp(host(d_x), out["x_new"], 1, "x (diana)")
     assert rel_err(host(d_ns), out["normsq"]) <= NORM_RTOL
+
+
+# --------------------------------------------------------------------------- state and random stream
+@pytest.mark.parametrize("rounding", [P.ROUND_STOCHASTIC, P.ROUND_NEAREST_EVEN])
+def test_resume_from_saved_state_is_bit_identical(rounding):
+    """The method's whole state is (x, r, alpha, k) plus the seed: 10 steps in a row equal
+    5 steps, a copy of the state to the host, a fresh Stepper loaded from it, 5 more steps."""
+    w = W.config(3).scaled(300_007)
+    desc_a = P.Desc(w.d, w.n, rounding=rounding, wire=w.wire, clip=w.clip, seed=77)
+    desc_b = P.Desc(w.d, w.n, rounding=rounding, wire=w.wire, clip=w.clip, seed=77)
+    st_a = Stepper(desc_a, eta=w.eta, beta=w.beta, eps=w.eps, device=DEV)
+    st_a.start(w.first_normsq)
+    x_a = W.make_params(w, DEV)
+    x_b0 = x_a.clone()
+    for k in range(1, 11):
+        _, rows = W.make_gradients(w, k, DEV)
+        st_a.step_fused(rows, x_a, k)
+    st_b = Stepper(desc_b, eta=w.eta, beta=w.beta, eps=w.eps, device=DEV)
+    st_b.start(w.first_normsq)
+    x_b = x_b0
+    for k in range(1, 6):
+        _, rows = W.make_gradients(w, k, DEV)
+        st_b.step_fused(rows, x_b, k)
+    saved = dict(x=host(x_b).copy(), r=host(st_b.r).copy(), alpha=host(st_b.alpha).copy())
+    del st_b, x_b
+    desc_c = P.Desc(w.d, w.n, rounding=rounding, wire=w.wire, clip=w.clip, seed=77)
+    st_c = Stepper(desc_c, eta=w.eta, beta=w.beta, eps=w.eps, device=DEV)
+    st_c.r.copy_(torch.from_numpy(saved["r"]))
+    st_c.alpha.copy_(torch.from_numpy(saved["alpha"]))
+    x_c = dev(saved["x"])
+    for k in range(6, 11):
+        _, rows = W.make_gradients(w, k, DEV)
+        st_c.step_fused(rows, x_c, k)
+    assert torch.equal(x_c, x_a)
+    assert torch.equal(st_c.alpha, st_a.alpha) and torch.equal(st_c.r, st_a.r)
+    assert torch.equal(st_c.norm_sq, st_a.norm_sq)
+
+
+def test_random_stream_word_by_word():
+    """Direct check of the random draws: with alpha = 1 and gradients t in [0, 1) on the
+    2^-24 grid, worker i's integer at coordinate j is 1 exactly when the top 24 bits of its
+    Philox word are below t 2^24.  Thresholds sweep all magnitudes; words come from the oracle
+    one by one."""
+    d, n, seed, step = 6007, 3, (9 << 32) | 3, 41
+    rng = np.random.default_rng(8)
+    shifts = rng.integers(1, 25, d)
+    thr = (rng.integers(0, 1 << 24, d) >> (24 - shifts)) << (24 - shifts)   # multiples of 2^-shift
+    t = (thr.astype(np.float64) / (1 << 24)).astype(F32)
+    assert np.array_equal((t.astype(np.float64) * (1 << 24)).astype(np.int64), thr)
+    g = np.tile(t, (n, 1))
+    desc = P.Desc(d, n, rounding=P.ROUND_STOCHASTIC, clip=P.default_clip(n), seed=seed, step=step)
+    ws = P.new_workspace(desc, DEV)
+    qs = [torch.empty(d, dtype=torch.int32, device=DEV) for _ in range(n)]
+    cnt = torch.zeros(n, dtype=torch.int64, device=DEV)
+    P.intsgd_compress(desc, rows_on_device(g), dev(np.ones(1, F32)), qs, cnt, ws)
+    for i in range(n):
+        got = host(qs[i])
+        want = np.array([1 if (oracle.random_word(seed, step, i, j) >> 8) < int(thr[j]) else 0
+                         for j in range(d)], np.int32)
+        assert np.array_equal(got, want), "worker %d" % i
+        assert 0 < want.sum() < d
