@@ -1172,12 +1172,14 @@ __global__ __launch_bounds__(kThreads) void k_int_sum(const IntSumArgs a) {
 
 // a4 in two phases: per round, read the n integer streams (the sums of Q units per thread stay
 // in registers), then write the sums.  A unit is 16 bytes of one worker's stream: one quad of
-// int32, or 16 coordinates of int8 (whose sums then go out as four 16-byte stores).
+// int32, or 16 coordinates of int8 (whose sums go out as four 16-byte stores, transposed
+// within the wavefront so that every store instruction is contiguous).
 template <int WIRE>
 __global__ __launch_bounds__(kPhasedThreads) void k_int_sum_phased(const IntSumArgs a) {
   constexpr uint32_t kUnitCoords = (WIRE == INTSGD_WIRE_INT8) ? 16u : 4u;
   constexpr uint32_t kUnitQuads = kUnitCoords / 4u;
   constexpr uint32_t Q = (WIRE == INTSGD_WIRE_INT8) ? 4u : 12u;      // units per thread and round
+  __shared__ vi4 transpose[(WIRE == INTSGD_WIRE_INT8) ? kPhasedThreads * kUnitQuads : 1u];
   const uint32_t tid = threadIdx.x;
   const uint64_t nunits = a.d / kUnitCoords;
   const uint32_t slab_row = gridDim.x * kPhasedThreads;
@@ -1214,9 +1216,29 @@ __global__ __launch_bounds__(kPhasedThreads) void k_int_sum_phased(const IntSumA
     for (uint32_t k = 0; k < Q; ++k) {
       if (k * slab_row < nu) {
         const uint32_t unit = (k * gridDim.x + blockIdx.x) * kPhasedThreads + tid;
+        if (WIRE == INTSGD_WIRE_INT8) {
+          // A lane holds the four quads of its 64 output bytes.  Written as they are, every store
+          // instruction would touch 64 cache lines a quarter each; a wavefront-local transpose
+          // through LDS makes each of the four stores one contiguous kilobyte instead.
+          const uint32_t lane = tid & 63u;
+          vi4* tr = transpose + (tid & ~63u) * kUnitQuads;           // this wavefront's 256 quads
 #pragma clang loop unroll(full)
-        for (uint32_t h = 0; h < kUnitQuads; ++h)
-          store128<kPlain>(out, (unit * kUnitQuads + h) * 16u, as_u(S[k][h]));
+          for (uint32_t h = 0; h < kUnitQuads; ++h) tr[lane * kUnitQuads + h] = S[k][h];
+          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+          __builtin_amdgcn_wave_barrier();
+          __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+          const uint32_t first_quad = (unit - lane) * kUnitQuads;    // of the wavefront's 64 units
+#pragma clang loop unroll(full)
+          for (uint32_t h = 0; h < kUnitQuads; ++h)
+            store128<kPlain>(out, (first_quad + h * 64u + lane) * 16u, as_u(tr[h * 64u + lane]));
+          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+          __builtin_amdgcn_wave_barrier();
+          __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        } else {
+#pragma clang loop unroll(full)
+          for (uint32_t h = 0; h < kUnitQuads; ++h)
+            store128<kPlain>(out, (unit * kUnitQuads + h) * 16u, as_u(S[k][h]));
+        }
       }
     }
     __syncthreads();
