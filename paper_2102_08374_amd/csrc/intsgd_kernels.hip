@@ -1145,17 +1145,41 @@ __device__ __forceinline__ void add_unit(vi4 (&S)[(WIRE == INTSGD_WIRE_INT8) ? 4
   }
 }
 
+// a4, tile form: workgroup b sums the 512 quads [512 b, 512 b + 512) of the n streams, eight
+// loads in flight per thread (int8: one dword = four coordinates per worker and thread).
 template <int WIRE>
 __global__ __launch_bounds__(kThreads) void k_int_sum(const IntSumArgs a) {
   const uint64_t nq = a.d >> 2;
-  const uint64_t stride = (uint64_t)gridDim.x * kThreads;
-  for (uint64_t quad = (uint64_t)blockIdx.x * kThreads + threadIdx.x; quad < nq; quad += stride) {
+  const uint64_t q0 = (uint64_t)blockIdx.x * kThreads;
+  if (q0 < nq) {
+    const uint64_t rest = nq - q0;
+    const uint32_t cnt = rest < kThreads ? (uint32_t)rest : kThreads;
+    const uint32_t ql = threadIdx.x;
     vi4 S = vi4{0, 0, 0, 0};
-    for (uint32_t i = 0; i < a.n; ++i) {
-      const vi4 v = load_q4<WIRE>(a.q.p[i], quad);
-      S.x += v.x; S.y += v.y; S.z += v.z; S.w += v.w;
+    if (WIRE == INTSGD_WIRE_INT8) {
+      if (ql < cnt)
+        for (uint32_t i = 0; i < a.n; ++i) {
+          const vi4 v = load_q4<WIRE>(a.q.p[i], q0 + ql);
+          S.x += v.x; S.y += v.y; S.z += v.z; S.w += v.w;
+        }
+    } else {
+      uint32_t i = 0;
+      for (; i + 8 <= a.n; i += 8) {
+        vu4 v[8];
+#pragma unroll
+        for (int w = 0; w < 8; ++w)
+          v[w] = load128<kNonTemporal>(make_stream((const vu4*)a.q.p[i + w] + q0, cnt * 16u), ql * 16u);
+#pragma unroll
+        for (int w = 0; w < 8; ++w) {
+          S.x += (int32_t)v[w].x; S.y += (int32_t)v[w].y; S.z += (int32_t)v[w].z; S.w += (int32_t)v[w].w;
+        }
+      }
+      for (; i < a.n; ++i) {
+        const vu4 v = load128<kNonTemporal>(make_stream((const vu4*)a.q.p[i] + q0, cnt * 16u), ql * 16u);
+        S.x += (int32_t)v.x; S.y += (int32_t)v.y; S.z += (int32_t)v.z; S.w += (int32_t)v.w;
+      }
     }
-    ((vi4*)a.sum_out)[quad] = S;
+    store128<INTSGD_X_STORE_POLICY>(make_stream((vi4*)a.sum_out + q0, cnt * 16u), ql * 16u, as_u(S));
   }
   // the d mod 4 last coordinates
   if (blockIdx.x == 0) {
