@@ -846,6 +846,41 @@ def test_two_phase_sweep_config3_full_size_randomized():
     assert sat > 0
 
 
+@pytest.mark.parametrize("fill", ["ones", "random", "zeros"])
+@pytest.mark.parametrize("form", [1, 2], ids=["tile-sweep", "two-phase-sweep"])
+def test_workspace_needs_no_initialisation(form, fill):
+    """The workspace may hold anything when a call starts (all-ones bytes, random bytes,
+    zeros): flags, the clip hint and the arrival ticket of the two-phase sweep are all
+    self-describing.  Three calls in a row on the same workspace, with and without clips,
+    so that each call also starts from what the previous one left."""
+    d, n = PHASED_D, 4
+    P.intsgd_set_tuning(two_phase=form)
+    desc0 = P.Desc(d, n, clip=P.default_clip(n))
+    ws = P.new_workspace(desc0, DEV)
+    if fill == "ones":
+        ws.fill_(255)
+    elif fill == "zeros":
+        ws.zero_()
+    else:
+        gen = torch.Generator(device=DEV)
+        gen.manual_seed(7)
+        ws.copy_(torch.randint(0, 256, ws.shape, dtype=torch.uint8, device=DEV, generator=gen))
+    alpha, g, x = make_case(d, n, None, seed=31)
+    rows = rows_on_device(g)
+    for call, L in enumerate([P.default_clip(n), 3, P.default_clip(n)]):
+        out = oracle.step(list(g), alpha, x, rounding=0, L=L, eta=0.1, seed=1, step=call)
+        desc = P.Desc(d, n, clip=L, seed=1, step=call)
+        d_x, d_a = dev(x), dev(alpha)
+        d_ns = torch.full((1,), -1.0, dtype=torch.float64, device=DEV)
+        d_cnt = torch.full((n,), -1, dtype=torch.int64, device=DEV)
+        P.intsgd_step_fused(desc, rows, d_a, 0.1, d_x, d_ns, d_cnt, ws)
+        assert_within_ulp(host(d_x), out["x_new"], 1, "x (call %d)" % call)
+        assert u64(d_cnt).tolist() == out["sat_count"].tolist(), call
+        assert rel_err(host(d_ns), out["normsq"]) <= NORM_RTOL
+        if L == 3:
+            assert out["sat_count"].sum() > 0
+
+
 def test_two_phase_needs_one_block_and_enough_coordinates():
     """Forced on, the library still takes the tile sweep where the two-phase one does not
     apply (several blocks, short vectors); results are the oracle's either way."""
