@@ -97,22 +97,58 @@ __device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
   return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
 }
 
+struct PhiloxState {
+  uint32_t c0, c1, c2, c3, k0, k1;
+};
+
+__device__ __forceinline__ void philox_bump_key(PhiloxState& s) {
+  s.k0 += 0x9E3779B9u;
+  s.k1 += 0xBB67AE85u;
+}
+
+// PRECONDITION: c2, c3 and the key are wave-uniform (worker, step and seed at every call
+// site); (c0, c1) is per lane.  In the first round two operands of each three-way xor are
+// then uniform, in the second round two operands of one of them; the uniform pair is
+// combined on the scalar unit (readfirstlane pins it there: the compiler otherwise
+// reassociates the xors back onto the vector unit), leaving one vector xor each.
 __device__ __forceinline__ vu4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
                                              uint32_t k0, uint32_t k1) {
-#pragma unroll
-  for (int round = 0; round < 10; ++round) {
-    const uint64_t p0 = (uint64_t)0xD2511F53u * (uint64_t)c0;
-    const uint64_t p1 = (uint64_t)0xCD9E8D57u * (uint64_t)c2;
-    const uint32_t n0 = xor3((uint32_t)(p1 >> 32), c1, k0);
-    const uint32_t n2 = xor3((uint32_t)(p0 >> 32), c3, k1);
-    c1 = (uint32_t)p1;
-    c3 = (uint32_t)p0;
-    c0 = n0;
-    c2 = n2;
-    k0 += 0x9E3779B9u;
-    k1 += 0xBB67AE85u;
+  PhiloxState s{c0, c1, c2, c3, k0, k1};
+  {
+    const uint64_t p0 = (uint64_t)0xD2511F53u * (uint64_t)s.c0;
+    const uint64_t p1 = (uint64_t)0xCD9E8D57u * (uint64_t)s.c2;
+    const uint32_t n0 = s.c1 ^ __builtin_amdgcn_readfirstlane((uint32_t)(p1 >> 32) ^ s.k0);
+    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ __builtin_amdgcn_readfirstlane(s.c3 ^ s.k1);
+    s.c1 = (uint32_t)p1;
+    s.c3 = (uint32_t)p0;
+    s.c0 = n0;
+    s.c2 = n2;
+    philox_bump_key(s);
   }
-  return vu4{c0, c1, c2, c3};
+  {
+    const uint64_t p0 = (uint64_t)0xD2511F53u * (uint64_t)s.c0;
+    const uint64_t p1 = (uint64_t)0xCD9E8D57u * (uint64_t)s.c2;
+    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ __builtin_amdgcn_readfirstlane(s.c1 ^ s.k0);
+    const uint32_t n2 = xor3((uint32_t)(p0 >> 32), s.c3, s.k1);
+    s.c1 = (uint32_t)p1;
+    s.c3 = (uint32_t)p0;
+    s.c0 = n0;
+    s.c2 = n2;
+    philox_bump_key(s);
+  }
+#pragma unroll
+  for (int round = 2; round < 10; ++round) {
+    const uint64_t p0 = (uint64_t)0xD2511F53u * (uint64_t)s.c0;
+    const uint64_t p1 = (uint64_t)0xCD9E8D57u * (uint64_t)s.c2;
+    const uint32_t n0 = xor3((uint32_t)(p1 >> 32), s.c1, s.k0);
+    const uint32_t n2 = xor3((uint32_t)(p0 >> 32), s.c3, s.k1);
+    s.c1 = (uint32_t)p1;
+    s.c3 = (uint32_t)p0;
+    s.c0 = n0;
+    s.c2 = n2;
+    philox_bump_key(s);
+  }
+  return vu4{s.c0, s.c1, s.c2, s.c3};
 }
 
 __device__ __forceinline__ uint32_t pick_word(const vu4& w, uint32_t c) {
