@@ -33,8 +33,9 @@ intsgd_tuning g_tuning = {0, 0, 0, 0};
 // HBM: 8 KB per stream and workgroup, and as few resident workgroups as keep enough loads in
 // flight: two of 512 threads per CU when a thread has two groups of eight worker loads to
 // issue (n > 8), four when it has at most one (at n = 8: 82 % of peak against 76 %).
-// Randomized rounding is co-bound by the integer ALU (Philox) and needs more wavefronts to
-// keep it busy: 16 KB tiles, four workgroups per CU.
+// Randomized rounding is co-bound by the integer ALU (Philox): 16 KB tiles and the
+// reservation for four, of which the kernel's 70 VGPRs let three be resident (two measured
+// 4 % slower on 8 x 25.6 M; a build squeezed into 64 VGPRs so that four fit, 3-5 % slower).
 intsgd_tuning effective_tuning(const intsgd_desc* desc) {
   const bool random = desc->rounding == INTSGD_ROUND_STOCHASTIC;
   intsgd_tuning t = g_tuning;
