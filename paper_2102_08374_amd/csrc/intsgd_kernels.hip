@@ -776,7 +776,7 @@ __global__ __launch_bounds__(kPhasedThreads) void k_aggregate_phased(const Phase
       if (k * slab_row < nq) {
         const uint32_t off = ((k * gridDim.x + blockIdx.x) * kPhasedThreads + tid) * 16u;
         if (MODE == kPhasedSumOnly) {
-          store128<kPlain>(out, off, as_u(S[k]));
+          store128<kWriteThrough>(out, off, as_u(S[k]));
         } else {
           const vf4 xv = as_f(load128<INTSGD_X_LOAD_POLICY>(out, off));
           if (MOMENTUM) {
@@ -1292,14 +1292,14 @@ __global__ __launch_bounds__(kPhasedThreads) void k_int_sum_phased(const IntSumA
           const uint32_t first_quad = (unit - lane) * kUnitQuads;    // of the wavefront's 64 units
 #pragma clang loop unroll(full)
           for (uint32_t h = 0; h < kUnitQuads; ++h)
-            store128<kPlain>(out, (first_quad + h * 64u + lane) * 16u, as_u(tr[h * 64u + lane]));
+            store128<kWriteThrough>(out, (first_quad + h * 64u + lane) * 16u, as_u(tr[h * 64u + lane]));
           __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
           __builtin_amdgcn_wave_barrier();
           __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         } else {
 #pragma clang loop unroll(full)
           for (uint32_t h = 0; h < kUnitQuads; ++h)
-            store128<kPlain>(out, (unit * kUnitQuads + h) * 16u, as_u(S[k][h]));
+            store128<kWriteThrough>(out, (unit * kUnitQuads + h) * 16u, as_u(S[k][h]));
         }
       }
     }
