@@ -475,10 +475,10 @@ intsgd_status intsgd_int_sum(const intsgd_desc* desc, const void* const* q, int3
   INTSGD_TRY(validate_vec(sum_out));
   WorkerPtrs qp;
   fill_ptrs(&qp, q, desc->n);
-  // int8 streams: 16 coordinates per 16-byte load and the two-phase form (53 us against 77 us
-  // on 8 x 25.6 M); int32 streams measured no better that way and keep the tile form
-  if ((desc->wire == INTSGD_WIRE_INT8 || effective_tuning(desc).two_phase == 2) &&
-      desc->d >= kMinPhasedD && effective_tuning(desc).two_phase != 1) {
+  // Long vectors take the two-phase form (int8: 16 coordinates per 16-byte load, 51 us against
+  // 77 us on 8 x 25.6 M; int32: 0.258 ms against 0.288 ms on 16 x 25.6 M behind intsgd_compress,
+  // 0.254 ms against 0.289 ms on its own), unless the tuning asks for the tile form.
+  if (desc->d >= kMinPhasedD && effective_tuning(desc).two_phase != 1) {
     PhasedShape ps{0};
     INTSGD_TRY(compute_units(&ps.grid));
     LaunchShape pls{ps.grid, 0, static_cast<hipStream_t>(hip_stream), nullptr, nullptr};
