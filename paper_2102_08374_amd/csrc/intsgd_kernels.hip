@@ -20,8 +20,9 @@
 //   * the sweep writes one norm partial per tile (or workgroup) and, only where something
 //     clipped, a row of clip counts per workgroup; a small kernel right behind it on the
 //     stream sums them in a fixed order and applies the alpha rule.  (Electing the
-//     sweep's last workgroup with a ticket instead was measured 3x slower: the
-//     device-scope release fence every workgroup then needs walks the L2.)
+//     sweep's last workgroup through a ticket instead was measured 3x slower with one
+//     workgroup per tile, and brings nothing with one workgroup per CU: consecutive
+//     launches on a stream already hide the small kernel's dispatch.)
 //
 // Work is cut into tiles that never straddle a block of Algorithm 2, so alpha is
 // wave-uniform inside a tile.  A tile whose ends are not multiples of four
@@ -710,7 +711,9 @@ __global__ __launch_bounds__(kThreads) void k_aggregate(const AggregateArgs a) {
 // registers; phase B reads, updates and writes x (and the momentum buffer) for the same
 // quads.  All CUs start together and move at about the same rate, so the chip alternates
 // between a read-only stream and a short read-modify-write burst instead of mixing the
-// two, which is what HBM rewards: 83-87 % of peak against 77-79 % for the tile sweep.
+// two.  While x fits the memory-side cache (d up to about 50 M) the burst never reaches
+// HBM and the sweep runs at 83-84 % of peak against 77-79 % for the tile sweep; beyond
+// that size the two forms are within 1-3 % of each other.
 struct PhasedArgs {
   RoundSpec rs;
   uint32_t n;
