@@ -302,3 +302,36 @@ def test_tap_needs_both_events_or_none():
     assert lib.intsgd_tap_next_launch(None, FAKE) == EINVAL
     assert lib.intsgd_tap_next_launch(FAKE, FAKE) == 0
     assert lib.intsgd_tap_next_launch(None, None) == 0      # clear it again
+
+
+def test_header_is_plain_c_and_links(tmp_path):
+    """include/intsgd.h compiles as C99 (-pedantic, warnings as errors) and a C program
+    linked against the built library can call the host-only entry points."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "abi.c"
+    src.write_text(
+        '#include "intsgd.h"\n#include <stdio.h>\n#include <string.h>\n'
+        "int main(void) {\n"
+        "  intsgd_desc d; double nsq = 1e-6, r = 0.0; float a = 0.0f; intsgd_status st;\n"
+        "  memset(&d, 0, sizeof d);\n"
+        "  if (intsgd_workspace_bytes(&d) != 0) return 2;\n"
+        "  d.d = 1048576; d.n = 4; d.num_blocks = 1; d.rounding = INTSGD_ROUND_STOCHASTIC;\n"
+        "  d.wire = INTSGD_WIRE_INT32; d.clip = 536870911;\n"
+        "  if (intsgd_workspace_bytes(&d) == 0) return 3;\n"
+        "  st = intsgd_next_alpha_host(&d, &nsq, &r, 0.9, 1e-8, 0.1, &a);\n"
+        '  printf("%d %.9g %s\\n", (int)st, (double)a, intsgd_status_string(INTSGD_EALIGN));\n'
+        "  return 0;\n}\n")
+    exe = tmp_path / "abi"
+    libdir = os.path.dirname(binding.library_path())
+    subprocess.check_call([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic",
+                           "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe),
+                           "-L", libdir, "-lintsgd", "-lm", "-Wl,-rpath," + libdir])
+    out = subprocess.check_output([str(exe)]).decode().split(None, 2)
+    assert out[0] == "0"
+    w = oracle.next_alpha(np.array([1e-6]), np.array([0.0]), n=4, d=1048576, beta=0.9, eps=1e-8, eta=0.1)
+    assert np.float32(float(out[1])) == np.float32(w[1][0])
+    assert out[2].strip() == "vector pointer not 16-byte aligned"
