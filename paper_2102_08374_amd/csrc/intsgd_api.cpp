@@ -26,8 +26,15 @@ constexpr uint64_t kMaxD = 1ull << 40;
 constexpr size_t kAlign = 256;
 constexpr uint32_t kLdsPerCu = 160u * 1024u;    // gfx950
 
-// Process-wide overrides; a zero field means "automatic".
+// Process-wide overrides; a zero field means "automatic".  Read and written under their
+// own lock, so that a call racing with intsgd_set_tuning sees the old or the new set whole.
+std::mutex g_tuning_mutex;
 intsgd_tuning g_tuning = {0, 0, 0, 0};
+
+intsgd_tuning current_tuning() {
+  std::lock_guard<std::mutex> lock(g_tuning_mutex);
+  return g_tuning;
+}
 
 // Automatic choices of the tile sweeps, measured on MI355X.  Nearest-even rounding is bound by
 // HBM: 8 KB per stream and workgroup, and as few resident workgroups as keep enough loads in
@@ -38,7 +45,7 @@ intsgd_tuning g_tuning = {0, 0, 0, 0};
 // 4 % slower on 8 x 25.6 M; a build squeezed into 64 VGPRs so that four fit, 3-5 % slower).
 intsgd_tuning effective_tuning(const intsgd_desc* desc) {
   const bool random = desc->rounding == INTSGD_ROUND_STOCHASTIC;
-  intsgd_tuning t = g_tuning;
+  intsgd_tuning t = current_tuning();
   if (t.tile_coords == 0) t.tile_coords = random ? 4096 : 2048;
   if (t.max_workgroups == 0) t.max_workgroups = kMaxGrid;
   if (t.workgroups_per_cu == 0) t.workgroups_per_cu = (random || desc->n <= 8) ? 4 : 2;
@@ -289,7 +296,7 @@ intsgd_status make_tiling(const intsgd_desc* desc, void* stream, Tiling* t,
   const intsgd_tuning tune = effective_tuning(desc);
   // a kernel may have its own automatic tile; an explicit override still wins
   const uint32_t tile =
-      (automatic_tile != 0 && g_tuning.tile_coords == 0) ? automatic_tile : tune.tile_coords;
+      (automatic_tile != 0 && current_tuning().tile_coords == 0) ? automatic_tile : tune.tile_coords;
   t->tm.d = desc->d;
   t->tm.tile = tile;
   if (desc->num_blocks == 1) {
@@ -435,7 +442,7 @@ intsgd_status intsgd_prepare(const intsgd_desc* desc) {
   const uint32_t sweep_tile = effective_tuning(desc).tile_coords;
   INTSGD_TRY(get_plan(desc, sweep_tile, &plan));
   // the compress kernel picks its own tile unless the tuning fixes one
-  const uint32_t other = g_tuning.tile_coords == 0 ? compress_tile(desc) : sweep_tile;
+  const uint32_t other = current_tuning().tile_coords == 0 ? compress_tile(desc) : sweep_tile;
   return other == sweep_tile ? INTSGD_OK : get_plan(desc, other, &plan);
 }
 
@@ -463,7 +470,7 @@ intsgd_status intsgd_compress(const intsgd_desc* desc, const float* const* grads
   const WorkspaceLayout w = workspace_layout(desc);
   // one read and one write stream per workgroup: a copy-like kernel, which wants every
   // wavefront slot filled (80 % of peak against 62 % under the sweeps' residency cap)
-  if (g_tuning.workgroups_per_cu == 0) t.ls.lds_reserve = 0;
+  if (current_tuning().workgroups_per_cu == 0) t.ls.lds_reserve = 0;
   return done(launch_compress(t.tm, t.ls, desc->n, desc->wire, round_spec(desc), g, alpha, q,
                               ws_at<uint64_t>(workspace, w.rows_off), sat_count));
 }
@@ -700,13 +707,13 @@ intsgd_status intsgd_set_tuning(const intsgd_tuning* tuning) {
   if (grid > kMaxGrid) return INTSGD_EINVAL;
   if (wgs != 0 && (wgs < 2 || wgs > 8)) return INTSGD_EINVAL;
   if (tuning->two_phase > 2) return INTSGD_EINVAL;
-  std::lock_guard<std::mutex> lock(g_mutex);
+  std::lock_guard<std::mutex> lock(g_tuning_mutex);
   g_tuning = *tuning;
   return INTSGD_OK;
 }
 
 void intsgd_get_tuning(intsgd_tuning* tuning) {
-  if (tuning) *tuning = g_tuning;
+  if (tuning) *tuning = current_tuning();
 }
 
 int intsgd_fused_step_form(const intsgd_desc* desc) {
