@@ -761,12 +761,16 @@ __global__ __launch_bounds__(kPhasedThreads) void k_aggregate_phased(const Phase
                                             alpha, a.rs, lds.sat, any);
     }
     if (any != 0ull) {            // rare: something clipped in this wavefront's quads
+      // Counted per worker here.  A lane past the round scales its zeros by 0 instead of
+      // alpha: with a non-finite alpha, 0 * alpha is a NaN and would be counted (in the pass
+      // above it can at most bring a wavefront here for nothing).
       LaneMask unused = 0ull;
 #pragma clang loop unroll(disable)
-      for (uint32_t k = 0; k * slab_row < nq; ++k)
-        (void)aggregate_quad<ROUND, true>(a.grads, a.n, r0, nq,
-                                          (k * gridDim.x + blockIdx.x) * kPhasedThreads + tid, alpha,
-                                          a.rs, lds.sat, unused);
+      for (uint32_t k = 0; k * slab_row < nq; ++k) {
+        const uint32_t ql = (k * gridDim.x + blockIdx.x) * kPhasedThreads + tid;
+        (void)aggregate_quad<ROUND, true>(a.grads, a.n, r0, nq, ql, ql < nq ? alpha : 0.f, a.rs,
+                                          lds.sat, unused);
+      }
     }
     __syncthreads();
     // phase B: stores past the round are dropped by the descriptor

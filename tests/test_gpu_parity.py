@@ -846,6 +846,37 @@ def test_two_phase_sweep_config3_full_size_randomized():
     assert sat > 0
 
 
+@pytest.mark.parametrize("rounding", [P.ROUND_NEAREST_EVEN, P.ROUND_STOCHASTIC])
+def test_two_phase_sweep_with_infinite_alpha(rounding):
+    """alpha = +Inf (the rule's zero denominator) in the two-phase form, whose last round is
+    partial: every real worker-coordinate is a clip event (0 * Inf = NaN included) and the
+    lanes past the end of the vector, which read zeros, are not."""
+    d, n = PHASED_D, 3
+    P.intsgd_set_tuning(two_phase=2)
+    rng = np.random.default_rng(5)
+    g = rng.normal(0, 1, (n, d)).astype(F32)
+    g[:, ::7] = 0.0
+    x = rng.normal(0, 1, d).astype(F32)
+    a_inf = np.array([np.inf], F32)
+    out = oracle.step(list(g), a_inf, x, rounding=rounding, L=100, eta=0.1, seed=1, step=1)
+    assert out["sat_count"].tolist() == [d] * n
+    desc = P.Desc(d, n, rounding=rounding, clip=100, seed=1, step=1)
+    assert P.intsgd_fused_step_form(desc) == 2
+    ws = P.new_workspace(desc, DEV)
+    rows = rows_on_device(g)
+    d_x = dev(x)
+    d_ns = torch.ones(1, dtype=torch.float64, device=DEV)
+    d_cnt = torch.ones(n, dtype=torch.int64, device=DEV)
+    P.intsgd_step_fused(desc, rows, dev(a_inf), 0.1, d_x, d_ns, d_cnt, ws)
+    assert u64(d_cnt).tolist() == [d] * n
+    assert_within_ulp(host(d_x), out["x_new"], 1, "x at alpha=inf")
+    d_S = torch.full((d,), -99, dtype=torch.int32, device=DEV)
+    d_cnt.fill_(1)
+    P.intsgd_compress_sum(desc, rows, dev(a_inf), d_S, d_cnt, ws)
+    assert u64(d_cnt).tolist() == [d] * n
+    assert np.array_equal(host(d_S), out["S"])
+
+
 @pytest.mark.parametrize("fill", ["ones", "random", "zeros"])
 @pytest.mark.parametrize("form", [1, 2], ids=["tile-sweep", "two-phase-sweep"])
 def test_workspace_needs_no_initialisation(form, fill):
