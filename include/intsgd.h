@@ -287,7 +287,8 @@ intsgd_status intsgd_heuristic_alpha(const intsgd_desc* desc, const float* const
  *                      reads, then the write-back, with the integer sums held in registers
  *                      in between), 0 = automatic (two-phase for nearest-even rounding
  *                      with more than 8 or fewer than 3 workers).
- *                      intsgd_int_sum follows it too: automatic = two-phase for int8 */
+ *                      intsgd_int_sum follows it too: automatic = two-phase for any wire
+ *                      (d >= 2^22), 1 = its tile form */
 typedef struct intsgd_tuning {
   uint32_t tile_coords;
   uint32_t max_workgroups;
