@@ -169,8 +169,11 @@ __device__ __forceinline__ int32_t cvt_i32_saturating(float r) {
 // form it from min/max because it cannot prove -L <= L.  Only one operand may be an
 // SGPR on this ISA, hence L in a VGPR.
 __device__ __forceinline__ int32_t clamp_sym(int32_t q, int32_t L) {
-  int32_t r;
-  asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(q), "s"(-L), "v"(L));
+  // The copy of L is an asm of its own so that it is made once and kept: a plain "v"(L)
+  // operand is re-created from the SGPR before every use (one v_mov per coordinate).
+  int32_t lv, r;
+  asm("v_mov_b32 %0, %1" : "=v"(lv) : "s"(L));
+  asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(q), "s"(-L), "v"(lv));
   return r;
 }
 
