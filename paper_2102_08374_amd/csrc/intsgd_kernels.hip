@@ -618,6 +618,7 @@ struct AggregateArgs {
   int32_t* sum_out;      // F1
   float* m;              // F3 with momentum
   double mu, wd;         // F3 with momentum
+  uint64_t keep_quads;   // F3, x beyond the last-level cache: quads [0, keep_quads) are kept in it
   Finish fin;
   WorkerPtrs grads;
 };
@@ -637,6 +638,7 @@ struct AggregateOp {
   __amdgpu_buffer_rsrc_t out;   // x (F3) or the aggregate (F1) of this tile body
   __amdgpu_buffer_rsrc_t mom;   // momentum buffer of this tile body
   MomentumRule rule;
+  bool keep;                    // this tile's part of x (and m) is to stay in the last-level cache
 
   __device__ __forceinline__ AggregateOp(const AggregateArgs& args, ReduceLds& l)
       : a(args), lds(l), alpha(0.f), c(0.0), acc(0.0), q0(0), nq(0), any(0ull) {}
@@ -664,21 +666,31 @@ struct AggregateOp {
     nq = quads;
     out = FUSED ? make_stream((vf4*)a.x + q0, nq * 16u) : make_stream((vi4*)a.sum_out + q0, nq * 16u);
     if (MOMENTUM) mom = make_stream((vf4*)a.m + q0, nq * 16u);
+    keep = q0 + nq <= a.keep_quads;
   }
-  __device__ __forceinline__ void quad(uint32_t ql) {
+  // XL / XS: cache policies of this tile's x (and m) loads and stores.
+  template <int XL, int XS>
+  __device__ __forceinline__ void quad_with(uint32_t ql) {
     vf4 xv = vf4{0.f, 0.f, 0.f, 0.f}, mv = vf4{0.f, 0.f, 0.f, 0.f};
-    if (FUSED) xv = as_f(load128<INTSGD_X_LOAD_POLICY>(out, ql * 16u));
-    if (MOMENTUM) mv = as_f(load128<INTSGD_X_LOAD_POLICY>(mom, ql * 16u));
+    if (FUSED) xv = as_f(load128<XL>(out, ql * 16u));
+    if (MOMENTUM) mv = as_f(load128<XL>(mom, ql * 16u));
     const vi4 S = aggregate_quad<ROUND, kCountInline>(a.grads, a.n, q0, nq, ql, alpha, a.rs, lds.sat, any);
     if (MOMENTUM) {
       const vf4 xn = momentum_quad(xv, mv, S, rule, acc);
-      store128<XSTORE>(mom, ql * 16u, as_u(mv));
-      store128<XSTORE>(out, ql * 16u, as_u(xn));
+      store128<XS>(mom, ql * 16u, as_u(mv));
+      store128<XS>(out, ql * 16u, as_u(xn));
     } else if (FUSED) {
-      store128<XSTORE>(out, ql * 16u, as_u(update_quad(xv, S, c, acc)));
+      store128<XS>(out, ql * 16u, as_u(update_quad(xv, S, c, acc)));
     } else {
-      store128<XSTORE>(out, ql * 16u, as_u(S));
+      store128<XS>(out, ql * 16u, as_u(S));
     }
+  }
+  // An x that fits the last-level cache stays there from step to step by itself.  Of a larger
+  // one a prefix is kept: its tiles use the allocating policies, all other tiles read and
+  // write x non-temporally so that they do not push the prefix out.
+  __device__ __forceinline__ void quad(uint32_t ql) {
+    if (XSTORE == kStreamOut && FUSED && !keep) quad_with<kNonTemporal, kStreamOut>(ql);
+    else quad_with<INTSGD_X_LOAD_POLICY, kWriteThrough>(ql);
   }
   __device__ __forceinline__ void end_tile(uint32_t t, uint32_t iter) {
     if (!kCountInline && any != 0ull) {   // rare: something clipped; count it per worker
@@ -1564,7 +1576,7 @@ hipError_t launch_update_norm(const TileMap& tm, const LaunchShape& ls, const fl
 hipError_t launch_compress_sum(const TileMap& tm, const LaunchShape& ls, uint32_t n,
                                const RoundSpec& rs, const WorkerPtrs& grads, const float* alpha,
                                int32_t* sum_out, const Finish& fin) {
-  AggregateArgs a{tm, rs, n, alpha, 0.0, nullptr, sum_out, nullptr, 0.0, 0.0, fin, grads};
+  AggregateArgs a{tm, rs, n, alpha, 0.0, nullptr, sum_out, nullptr, 0.0, 0.0, 0, fin, grads};
   const dim3 grid(ls.grid), block(kThreads);
   {
     if (rs.rounding == INTSGD_ROUND_STOCHASTIC)
@@ -1597,13 +1609,17 @@ hipError_t launch_step_fused(const TileMap& tm, const LaunchShape& ls, uint32_t 
                              const RoundSpec& rs, const WorkerPtrs& grads, const float* alpha,
                              double eta, float* x, const Momentum* mom, const Finish& fin) {
   AggregateArgs a{tm, rs, n, alpha, eta, x, nullptr, mom ? mom->m : nullptr, mom ? mom->mu : 0.0,
-                  mom ? mom->wd : 0.0, fin, grads};
+                  mom ? mom->wd : 0.0, 0, fin, grads};
   const dim3 grid(ls.grid), block(kThreads);
   const bool random = rs.rounding == INTSGD_ROUND_STOCHASTIC;
   // x (and m) no larger than the 256 MB last-level cache stay there from one step to the next
-  // when written through; beyond that they are real HBM traffic either way, and a store that is
-  // also marked non-temporal measured 2-3 % faster (workloads 4 and 5).
+  // when written through.  Of a larger x a prefix of kKeepBytes is treated that way and the
+  // rest is read and written non-temporally, which leaves the prefix in the cache: on
+  // workload 4 (434 MB of x) 0.741 -> 0.705 ms, and the streamed part by itself is 2-3 %
+  // faster with nt + sc1 stores than with plain write-through ones.
+  constexpr uint64_t kKeepBytes = 224ull << 20;
   const bool big = tm.d * sizeof(float) > (192ull << 20);
+  if (big) a.keep_quads = kKeepBytes / 16u / (mom ? 2u : 1u);
 #define INTSGD_LAUNCH_AGG(R, M)                                                                   \
   do {                                                                                            \
     if (big) launch_sweep(ls, (k_aggregate<R, true, M, kStreamOut>), grid, block, ls.lds_reserve, a); \
