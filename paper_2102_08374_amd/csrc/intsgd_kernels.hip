@@ -739,6 +739,7 @@ struct PhasedArgs {
   double mu, wd;
   int32_t* sum_out;      // kPhasedSumOnly
   uint64_t d;
+  uint64_t keep_quads;   // quads [0, keep_quads) of x (and m) are kept in the last-level cache
   Finish fin;
   WorkerPtrs grads;
 };
@@ -746,6 +747,22 @@ struct PhasedArgs {
 constexpr int kPhasedSumOnly = 0;    // F1: phase B writes the integer sums
 constexpr int kPhasedUpdate = 1;     // F3
 constexpr int kPhasedMomentum = 2;   // F3 with the momentum / weight-decay update
+
+// Phase B for one quad: read, update and write x (and m) with the given cache policies.
+template <bool MOMENTUM, int XL, int XS>
+__device__ __forceinline__ void update_in_place(__amdgpu_buffer_rsrc_t out, __amdgpu_buffer_rsrc_t mom,
+                                                uint32_t off, const vi4& S, double c,
+                                                const MomentumRule& rule, double& acc) {
+  const vf4 xv = as_f(load128<XL>(out, off));
+  if (MOMENTUM) {
+    vf4 mv = as_f(load128<XL>(mom, off));
+    const vf4 xn = momentum_quad(xv, mv, S, rule, acc);
+    store128<XS>(mom, off, as_u(mv));
+    store128<XS>(out, off, as_u(xn));
+  } else {
+    store128<XS>(out, off, as_u(update_quad(xv, S, c, acc)));
+  }
+}
 
 template <int ROUND, int MODE>
 __global__ __launch_bounds__(kPhasedThreads) void k_aggregate_phased(const PhasedArgs a) {
@@ -796,19 +813,15 @@ __global__ __launch_bounds__(kPhasedThreads) void k_aggregate_phased(const Phase
 #pragma clang loop unroll(full)
     for (uint32_t k = 0; k < kPhasedQuads; ++k) {
       if (k * slab_row < nq) {
-        const uint32_t off = ((k * gridDim.x + blockIdx.x) * kPhasedThreads + tid) * 16u;
+        const uint32_t slab = (k * gridDim.x + blockIdx.x) * kPhasedThreads;   // of this workgroup
+        const uint32_t off = (slab + tid) * 16u;
         if (MODE == kPhasedSumOnly) {
           store128<kWriteThrough>(out, off, as_u(S[k]));
-        } else {
-          const vf4 xv = as_f(load128<INTSGD_X_LOAD_POLICY>(out, off));
-          if (MOMENTUM) {
-            vf4 mv = as_f(load128<INTSGD_X_LOAD_POLICY>(mom, off));
-            const vf4 xn = momentum_quad(xv, mv, S[k], rule, acc);
-            store128<INTSGD_X_STORE_POLICY>(mom, off, as_u(mv));
-            store128<INTSGD_X_STORE_POLICY>(out, off, as_u(xn));
-          } else {
-            store128<INTSGD_X_STORE_POLICY>(out, off, as_u(update_quad(xv, S[k], c, acc)));
-          }
+        } else if (r0 + slab + kPhasedThreads <= a.keep_quads) {
+          update_in_place<MOMENTUM, INTSGD_X_LOAD_POLICY, INTSGD_X_STORE_POLICY>(out, mom, off, S[k], c,
+                                                                                 rule, acc);
+        } else {     // the part of a large x that is streamed past the cache-resident prefix
+          update_in_place<MOMENTUM, kNonTemporal, kStreamOut>(out, mom, off, S[k], c, rule, acc);
         }
       }
     }
@@ -1487,6 +1500,11 @@ inline hipError_t after_launch() { return hipGetLastError(); }
       hipLaunchKernelGGL(kernel, grid, block, lds, (ls).stream, __VA_ARGS__);                    \
   } while (0)
 
+// The 256 MB last-level (memory-side) cache: a state vector up to kResidentBytes is left to stay
+// in it as a whole; of a larger one the first kKeepBytes are kept and the rest is streamed.
+constexpr uint64_t kResidentBytes = 192ull << 20;
+constexpr uint64_t kKeepBytes = 224ull << 20;
+
 constexpr uint32_t kChunk = 8192;            // partials per first-level workgroup
 constexpr uint32_t kTwoLevelFrom = 2 * kChunk;
 
@@ -1617,8 +1635,7 @@ hipError_t launch_step_fused(const TileMap& tm, const LaunchShape& ls, uint32_t 
   // rest is read and written non-temporally, which leaves the prefix in the cache: on
   // workload 4 (434 MB of x) 0.741 -> 0.705 ms, and the streamed part by itself is 2-3 %
   // faster with nt + sc1 stores than with plain write-through ones.
-  constexpr uint64_t kKeepBytes = 224ull << 20;
-  const bool big = tm.d * sizeof(float) > (192ull << 20);
+  const bool big = tm.d * sizeof(float) > kResidentBytes;
   if (big) a.keep_quads = kKeepBytes / 16u / (mom ? 2u : 1u);
 #define INTSGD_LAUNCH_AGG(R, M)                                                                   \
   do {                                                                                            \
@@ -1645,8 +1662,11 @@ hipError_t launch_step_fused_phased(const PhasedShape& ps, const LaunchShape& ls
   Finish fin = fin_in;
   fin.num_tiles = ps.grid;      // one norm partial and one clip-table column per workgroup
   fin.workgroups = ps.grid;
+  // same rule as the tile sweep: an x beyond the last-level cache keeps a prefix in it
+  const uint64_t keep_quads =
+      d * sizeof(float) > kResidentBytes ? kKeepBytes / 16u / (mom ? 2u : 1u) : ~0ull;
   PhasedArgs a{rs, n, alpha, eta, x, mom ? mom->m : nullptr, mom ? mom->mu : 0.0,
-               mom ? mom->wd : 0.0, nullptr, d, fin, grads};
+               mom ? mom->wd : 0.0, nullptr, d, keep_quads, fin, grads};
   const dim3 grid(ps.grid), block(kPhasedThreads);
   const bool random = rs.rounding == INTSGD_ROUND_STOCHASTIC;
   {
@@ -1669,7 +1689,7 @@ hipError_t launch_compress_sum_phased(const PhasedShape& ps, const LaunchShape& 
   Finish fin = fin_in;
   fin.num_tiles = ps.grid;
   fin.workgroups = ps.grid;
-  PhasedArgs a{rs, n, alpha, 0.0, nullptr, nullptr, 0.0, 0.0, sum_out, d, fin, grads};
+  PhasedArgs a{rs, n, alpha, 0.0, nullptr, nullptr, 0.0, 0.0, sum_out, d, ~0ull, fin, grads};
   const dim3 grid(ps.grid), block(kPhasedThreads);
   {
     if (rs.rounding == INTSGD_ROUND_STOCHASTIC)
