@@ -366,6 +366,9 @@ def sampled_check(w: W.Workload, steps, slices_per_step=48, slice_len=8192):
             assert rel_err(host(st.norm_sq)[l], acc) <= NORM_RTOL
         starts = [0, max(0, w.d - slice_len), tile - 5, (w.d // tile) * tile - 3]
         starts += [o - 7 for o in off[1:-1:max(1, len(off) // 10)]]
+        # where the cache-resident prefix of a large x ends and the streamed part begins
+        # (224 MB of fp32; other code path, same arithmetic)
+        starts += [(224 << 20) // 4 - slice_len // 2]
         starts += list(rng.integers(0, w.d - slice_len, slices_per_step))
         for s in starts:
             s = int(max(0, min(s, w.d - slice_len)))
