@@ -397,6 +397,48 @@ def test_config5_full_size_sampled():
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("form,n,rounding", [(1, 4, P.ROUND_STOCHASTIC), (2, 2, P.ROUND_NEAREST_EVEN)],
+                         ids=["tile-sweep", "two-phase-sweep"])
+def test_momentum_step_on_a_state_beyond_the_last_level_cache(form, n, rounding):
+    """d = 60 M: x and m are 240 MB each, so both sweeps keep a prefix of them cache-resident
+    and stream the rest (different cache policies, same arithmetic).  Windows at the ends, at
+    the prefix boundaries (112 MB per vector with momentum, 224 MB without) and at random
+    places against the oracle; the norm against a float64 reduction."""
+    d = 60_000_003
+    eta, mu, wd, L = 0.1, 0.9, 1e-4, P.default_clip(n)
+    P.intsgd_set_tuning(two_phase=form)
+    desc = P.Desc(d, n, rounding=rounding, clip=L, seed=77, step=5)
+    assert P.intsgd_fused_step_form(desc) == form
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(99)
+    buf = torch.empty((n, W.row_stride(d)), dtype=torch.float32, device=DEV)
+    buf.normal_(0.0, 1e-3, generator=gen)
+    rows = [buf[i, :d] for i in range(n)]
+    x = torch.empty(d, dtype=torch.float32, device=DEV).normal_(0.0, 1.0, generator=gen)
+    m = torch.empty(d, dtype=torch.float32, device=DEV).normal_(0.0, 1e-2, generator=gen)
+    x_old, m_old = x.clone(), m.clone()
+    alpha = np.array([733.25], F32)
+    ws = P.new_workspace(desc, DEV)
+    d_ns = torch.zeros(1, dtype=torch.float64, device=DEV)
+    d_cnt = torch.zeros(n, dtype=torch.int64, device=DEV)
+    P.intsgd_step_momentum(desc, rows, dev(alpha), eta, mu, wd, x, m, None, 0.0, 0.0, d_ns, d_cnt, ws)
+    torch.cuda.synchronize()
+    assert u64(d_cnt).sum() == 0
+    ln = 8192
+    rng = np.random.default_rng(4)
+    starts = [0, d - ln, (112 << 20) // 4 - ln // 2, (224 << 20) // 4 - ln // 2]
+    starts += [int(v) for v in rng.integers(0, d - ln, 12)]
+    for s0 in starts:
+        e0 = s0 + ln
+        out = oracle.step_momentum([host(r_[s0:e0]) for r_ in rows], alpha, host(x_old[s0:e0]),
+                                   host(m_old[s0:e0]), rounding=rounding, L=L, eta=eta, mu=mu, wd=wd,
+                                   seed=77, step=5, j0=s0)
+        assert_within_ulp(host(x[s0:e0]), out["x_new"], 1, "x[%d:%d]" % (s0, e0))
+        assert_within_ulp(host(m[s0:e0]), out["m_new"], 1, "m[%d:%d]" % (s0, e0))
+    acc = float((x.double() - x_old.double()).pow(2).sum())
+    assert rel_err(host(d_ns)[0], acc) <= NORM_RTOL
+
+
 def test_whole_step_call_equals_step_then_rule():
     """intsgd_step_fused_next_alpha == intsgd_step_fused followed by intsgd_next_alpha,
     bit for bit, for one block and for several."""
