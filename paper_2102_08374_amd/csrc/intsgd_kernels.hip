@@ -689,7 +689,7 @@ struct AggregateOp {
   // one a prefix is kept: its tiles use the allocating policies, all other tiles read and
   // write x non-temporally so that they do not push the prefix out.
   __device__ __forceinline__ void quad(uint32_t ql) {
-    if (XSTORE == kStreamOut && FUSED && !keep) quad_with<kNonTemporal, kStreamOut>(ql);
+    if (XSTORE == kStreamOut && !(FUSED && keep)) quad_with<kNonTemporal, kStreamOut>(ql);
     else quad_with<INTSGD_X_LOAD_POLICY, kWriteThrough>(ql);
   }
   __device__ __forceinline__ void end_tile(uint32_t t, uint32_t iter) {
@@ -815,8 +815,9 @@ __global__ __launch_bounds__(kPhasedThreads) void k_aggregate_phased(const Phase
       if (k * slab_row < nq) {
         const uint32_t slab = (k * gridDim.x + blockIdx.x) * kPhasedThreads;   // of this workgroup
         const uint32_t off = (slab + tid) * 16u;
-        if (MODE == kPhasedSumOnly) {
-          store128<kWriteThrough>(out, off, as_u(S[k]));
+        if (MODE == kPhasedSumOnly) {       // sums that fit the cache are left there for F2
+          if (a.keep_quads != 0) store128<kWriteThrough>(out, off, as_u(S[k]));
+          else store128<kStreamOut>(out, off, as_u(S[k]));
         } else if (r0 + slab + kPhasedThreads <= a.keep_quads) {
           update_in_place<MOMENTUM, INTSGD_X_LOAD_POLICY, INTSGD_X_STORE_POLICY>(out, mom, off, S[k], c,
                                                                                  rule, acc);
@@ -1187,6 +1188,7 @@ __global__ __launch_bounds__(kThreads) void k_compress(const CompressArgs a) {
 struct IntSumArgs {
   uint64_t d;
   uint32_t n;
+  uint32_t stream_out;   // the sums are too long to wait in the last-level cache for a5-a6
   int32_t* sum_out;
   WorkerPtrs q;
 };
@@ -1255,7 +1257,9 @@ __global__ __launch_bounds__(kThreads) void k_int_sum(const IntSumArgs a) {
         S.x += (int32_t)v.x; S.y += (int32_t)v.y; S.z += (int32_t)v.z; S.w += (int32_t)v.w;
       }
     }
-    store128<INTSGD_X_STORE_POLICY>(make_stream((vi4*)a.sum_out + q0, cnt * 16u), ql * 16u, as_u(S));
+    const __amdgpu_buffer_rsrc_t out = make_stream((vi4*)a.sum_out + q0, cnt * 16u);
+    if (a.stream_out) store128<kStreamOut>(out, ql * 16u, as_u(S));
+    else store128<kWriteThrough>(out, ql * 16u, as_u(S));
   }
   // the d mod 4 last coordinates
   if (blockIdx.x == 0) {
@@ -1329,15 +1333,20 @@ __global__ __launch_bounds__(kPhasedThreads) void k_int_sum_phased(const IntSumA
           __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
           const uint32_t first_quad = (unit - lane) * kUnitQuads;    // of the wavefront's 64 units
 #pragma clang loop unroll(full)
-          for (uint32_t h = 0; h < kUnitQuads; ++h)
-            store128<kWriteThrough>(out, (first_quad + h * 64u + lane) * 16u, as_u(tr[h * 64u + lane]));
+          for (uint32_t h = 0; h < kUnitQuads; ++h) {
+            const uint32_t off = (first_quad + h * 64u + lane) * 16u;
+            if (a.stream_out) store128<kStreamOut>(out, off, as_u(tr[h * 64u + lane]));
+            else store128<kWriteThrough>(out, off, as_u(tr[h * 64u + lane]));
+          }
           __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
           __builtin_amdgcn_wave_barrier();
           __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         } else {
 #pragma clang loop unroll(full)
-          for (uint32_t h = 0; h < kUnitQuads; ++h)
-            store128<kWriteThrough>(out, (unit * kUnitQuads + h) * 16u, as_u(S[k][h]));
+          for (uint32_t h = 0; h < kUnitQuads; ++h) {
+            if (a.stream_out) store128<kStreamOut>(out, (unit * kUnitQuads + h) * 16u, as_u(S[k][h]));
+            else store128<kWriteThrough>(out, (unit * kUnitQuads + h) * 16u, as_u(S[k][h]));
+          }
         }
       }
     }
@@ -1367,6 +1376,7 @@ struct DecodeArgs {
   float* gtilde;         // decode_update only, may be null
   float* m;              // momentum form only
   double mu, wd;         // momentum form only
+  uint64_t keep_quads;   // quads [0, keep_quads) of x (and m) are kept in the last-level cache
   Finish fin;            // F2 only
 };
 
@@ -1377,6 +1387,7 @@ struct DecodeOp {
   double c, na, acc;
   __amdgpu_buffer_rsrc_t sum_s, x_s, gt_s, m_s;
   MomentumRule rule;
+  bool keep;             // this tile's part of x (and m) stays in the last-level cache
 
   __device__ __forceinline__ DecodeOp(const DecodeArgs& args, ReduceLds& l)
       : a(args), lds(l), c(0.0), na(0.0), acc(0.0) {}
@@ -1404,18 +1415,16 @@ struct DecodeOp {
     x_s = make_stream((vf4*)a.x + q0, quads * 16u);
     if (WITH_GTILDE) gt_s = make_stream((vf4*)a.gtilde + q0, quads * 16u);
     if (MOMENTUM) m_s = make_stream((vf4*)a.m + q0, quads * 16u);
+    keep = q0 + quads <= a.keep_quads;
   }
   __device__ __forceinline__ void quad(uint32_t ql) {
     const vi4 S = as_i(load128<kNonTemporal>(sum_s, ql * 16u));
-    const vf4 xv = as_f(load128<INTSGD_X_LOAD_POLICY>(x_s, ql * 16u));
-    if (MOMENTUM) {
-      vf4 mv = as_f(load128<INTSGD_X_LOAD_POLICY>(m_s, ql * 16u));
-      const vf4 xn = momentum_quad(xv, mv, S, rule, acc);
-      store128<INTSGD_X_STORE_POLICY>(m_s, ql * 16u, as_u(mv));
-      store128<INTSGD_X_STORE_POLICY>(x_s, ql * 16u, as_u(xn));
-    } else {
-      store128<INTSGD_X_STORE_POLICY>(x_s, ql * 16u, as_u(update_quad(xv, S, c, acc)));
-    }
+    // the cache-resident prefix of a large x, or the streamed rest (as in the fused sweeps)
+    if (keep)
+      update_in_place<MOMENTUM, INTSGD_X_LOAD_POLICY, INTSGD_X_STORE_POLICY>(x_s, m_s, ql * 16u, S, c,
+                                                                             rule, acc);
+    else
+      update_in_place<MOMENTUM, kNonTemporal, kStreamOut>(x_s, m_s, ql * 16u, S, c, rule, acc);
     if (WITH_GTILDE) {
       const vf4 gt = vf4{gtilde_of(S.x), gtilde_of(S.y), gtilde_of(S.z), gtilde_of(S.w)};
       store128<kPlain>(gt_s, ql * 16u, as_u(gt));
@@ -1505,6 +1514,16 @@ inline hipError_t after_launch() { return hipGetLastError(); }
 constexpr uint64_t kResidentBytes = 192ull << 20;
 constexpr uint64_t kKeepBytes = 224ull << 20;
 
+// Quads of x (and of m) that a sweep over d coordinates keeps cache-resident.
+uint64_t state_keep_quads(uint64_t d, bool with_momentum) {
+  const uint64_t vectors = with_momentum ? 2u : 1u;
+  if (vectors * d * sizeof(float) <= kResidentBytes) return ~0ull;
+  return kKeepBytes / 16u / vectors;
+}
+
+// The integer sums between F1 and F2 stay in the cache only if x fits beside them.
+bool sums_stay_resident(uint64_t d) { return 2u * d * sizeof(int32_t) <= kKeepBytes; }
+
 constexpr uint32_t kChunk = 8192;            // partials per first-level workgroup
 constexpr uint32_t kTwoLevelFrom = 2 * kChunk;
 
@@ -1554,7 +1573,7 @@ hipError_t launch_compress(const TileMap& tm, const LaunchShape& ls, uint32_t n,
 
 hipError_t launch_int_sum_phased(const PhasedShape& ps, const LaunchShape& ls, uint64_t d, uint32_t n,
                                  int32_t wire, const WorkerPtrs& q, int32_t* sum_out) {
-  IntSumArgs a{d, n, sum_out, q};
+  IntSumArgs a{d, n, sums_stay_resident(d) ? 0u : 1u, sum_out, q};
   const dim3 grid(ps.grid), block(kPhasedThreads);
   if (wire == INTSGD_WIRE_INT8) launch_sweep(ls, (k_int_sum_phased<8>), grid, block, 0, a);
   else launch_sweep(ls, (k_int_sum_phased<32>), grid, block, 0, a);
@@ -1563,7 +1582,7 @@ hipError_t launch_int_sum_phased(const PhasedShape& ps, const LaunchShape& ls, u
 
 hipError_t launch_int_sum(uint64_t d, const LaunchShape& ls, uint32_t n, int32_t wire,
                           const WorkerPtrs& q, int32_t* sum_out) {
-  IntSumArgs a{d, n, sum_out, q};
+  IntSumArgs a{d, n, sums_stay_resident(d) ? 0u : 1u, sum_out, q};
   const dim3 grid(ls.grid), block(kThreads);
   if (wire == INTSGD_WIRE_INT8) launch_sweep(ls, (k_int_sum<8>), grid, block, 0, a);
   else launch_sweep(ls, (k_int_sum<32>), grid, block, 0, a);
@@ -1573,7 +1592,8 @@ hipError_t launch_int_sum(uint64_t d, const LaunchShape& ls, uint32_t n, int32_t
 hipError_t launch_decode_update(const TileMap& tm, const LaunchShape& ls, uint32_t n,
                                 const int32_t* sum, const float* alpha, double eta, float* x,
                                 float* gtilde_out) {
-  DecodeArgs a{tm, n, sum, alpha, eta, x, gtilde_out, nullptr, 0.0, 0.0, Finish{}};
+  DecodeArgs a{tm, n, sum, alpha, eta, x, gtilde_out, nullptr, 0.0, 0.0, state_keep_quads(tm.d, false),
+               Finish{}};
   const dim3 grid(ls.grid), block(kThreads);
   if (gtilde_out) launch_sweep(ls, (k_decode<false, true, false>), grid, block, 0, a);
   else launch_sweep(ls, (k_decode<false, false, false>), grid, block, 0, a);
@@ -1596,11 +1616,13 @@ hipError_t launch_compress_sum(const TileMap& tm, const LaunchShape& ls, uint32_
                                int32_t* sum_out, const Finish& fin) {
   AggregateArgs a{tm, rs, n, alpha, 0.0, nullptr, sum_out, nullptr, 0.0, 0.0, 0, fin, grads};
   const dim3 grid(ls.grid), block(kThreads);
-  {
-    if (rs.rounding == INTSGD_ROUND_STOCHASTIC)
-      launch_sweep(ls, (k_aggregate<1, false, false, kWriteThrough>), grid, block, ls.lds_reserve, a);
-    else
-      launch_sweep(ls, (k_aggregate<0, false, false, kWriteThrough>), grid, block, ls.lds_reserve, a);
+  const bool random = rs.rounding == INTSGD_ROUND_STOCHASTIC;
+  if (sums_stay_resident(tm.d)) {
+    if (random) launch_sweep(ls, (k_aggregate<1, false, false, kWriteThrough>), grid, block, ls.lds_reserve, a);
+    else launch_sweep(ls, (k_aggregate<0, false, false, kWriteThrough>), grid, block, ls.lds_reserve, a);
+  } else {      // streamed: the sums would only push x out of the cache
+    if (random) launch_sweep(ls, (k_aggregate<1, false, false, kStreamOut>), grid, block, ls.lds_reserve, a);
+    else launch_sweep(ls, (k_aggregate<0, false, false, kStreamOut>), grid, block, ls.lds_reserve, a);
   }
   hipError_t e = after_launch();
   if (e != hipSuccess) return e;
@@ -1611,7 +1633,7 @@ hipError_t launch_decode_update_norm(const TileMap& tm, const LaunchShape& ls, u
                                      const int32_t* sum, const float* alpha, double eta, float* x,
                                      const Momentum* mom, const Finish& fin) {
   DecodeArgs a{tm, n, sum, alpha, eta, x, nullptr, mom ? mom->m : nullptr, mom ? mom->mu : 0.0,
-               mom ? mom->wd : 0.0, fin};
+               mom ? mom->wd : 0.0, state_keep_quads(tm.d, mom != nullptr), fin};
   {
     if (mom)
       launch_sweep(ls, (k_decode<true, false, true>), dim3(ls.grid), dim3(kThreads), 0, a);
@@ -1635,8 +1657,8 @@ hipError_t launch_step_fused(const TileMap& tm, const LaunchShape& ls, uint32_t 
   // rest is read and written non-temporally, which leaves the prefix in the cache: on
   // workload 4 (434 MB of x) 0.741 -> 0.705 ms, and the streamed part by itself is 2-3 %
   // faster with nt + sc1 stores than with plain write-through ones.
-  const bool big = tm.d * sizeof(float) > kResidentBytes;
-  if (big) a.keep_quads = kKeepBytes / 16u / (mom ? 2u : 1u);
+  a.keep_quads = state_keep_quads(tm.d, mom != nullptr);
+  const bool big = a.keep_quads != ~0ull;
 #define INTSGD_LAUNCH_AGG(R, M)                                                                   \
   do {                                                                                            \
     if (big) launch_sweep(ls, (k_aggregate<R, true, M, kStreamOut>), grid, block, ls.lds_reserve, a); \
@@ -1663,8 +1685,7 @@ hipError_t launch_step_fused_phased(const PhasedShape& ps, const LaunchShape& ls
   fin.num_tiles = ps.grid;      // one norm partial and one clip-table column per workgroup
   fin.workgroups = ps.grid;
   // same rule as the tile sweep: an x beyond the last-level cache keeps a prefix in it
-  const uint64_t keep_quads =
-      d * sizeof(float) > kResidentBytes ? kKeepBytes / 16u / (mom ? 2u : 1u) : ~0ull;
+  const uint64_t keep_quads = state_keep_quads(d, mom != nullptr);
   PhasedArgs a{rs, n, alpha, eta, x, mom ? mom->m : nullptr, mom ? mom->mu : 0.0,
                mom ? mom->wd : 0.0, nullptr, d, keep_quads, fin, grads};
   const dim3 grid(ps.grid), block(kPhasedThreads);
@@ -1689,7 +1710,8 @@ hipError_t launch_compress_sum_phased(const PhasedShape& ps, const LaunchShape& 
   Finish fin = fin_in;
   fin.num_tiles = ps.grid;
   fin.workgroups = ps.grid;
-  PhasedArgs a{rs, n, alpha, 0.0, nullptr, nullptr, 0.0, 0.0, sum_out, d, ~0ull, fin, grads};
+  PhasedArgs a{rs, n, alpha, 0.0, nullptr, nullptr, 0.0, 0.0, sum_out, d,
+               sums_stay_resident(d) ? ~0ull : 0ull, fin, grads};
   const dim3 grid(ps.grid), block(kPhasedThreads);
   {
     if (rs.rounding == INTSGD_ROUND_STOCHASTIC)
