@@ -439,6 +439,61 @@ def test_momentum_step_on_a_state_beyond_the_last_level_cache(form, n, rounding)
     assert rel_err(host(d_ns)[0], acc) <= NORM_RTOL
 
 
+@pytest.mark.parametrize("form", [1, 2], ids=["tile-forms", "two-phase-forms"])
+@pytest.mark.parametrize("wire,L", [(P.WIRE_INT32, None), (P.WIRE_INT8, 127)], ids=["int32", "int8"])
+def test_two_pass_and_unfused_chains_on_a_long_vector(form, wire, L):
+    """d = 60 M (240 MB per vector): the integer sums are streamed past the last-level cache
+    and x keeps only a prefix in it, in F1, a4, F2 and a5-a6 alike.  Windows of S and x at
+    the ends, at the prefix boundary and at random places against the oracle."""
+    d, n, eta = 60_000_003, 2, 0.1
+    L = P.default_clip(n) if L is None else L
+    P.intsgd_set_tuning(two_phase=form)
+    desc = P.Desc(d, n, rounding=P.ROUND_NEAREST_EVEN, wire=wire, clip=L, seed=3, step=2)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(5)
+    buf = torch.empty((n, W.row_stride(d)), dtype=torch.float32, device=DEV)
+    buf.normal_(0.0, 1e-3, generator=gen)
+    rows = [buf[i, :d] for i in range(n)]
+    x0 = torch.empty(d, dtype=torch.float32, device=DEV).normal_(0.0, 1.0, generator=gen)
+    alpha = np.array([611.5], F32)
+    d_a = dev(alpha)
+    ws = P.new_workspace(desc, DEV)
+    ln = 8192
+    rng = np.random.default_rng(6)
+    starts = [0, d - ln, (224 << 20) // 4 - ln // 2] + [int(v) for v in rng.integers(0, d - ln, 8)]
+    ref = {}
+    for s0 in starts:
+        ref[s0] = oracle.step([host(r_[s0:s0 + ln]) for r_ in rows], alpha, host(x0[s0:s0 + ln]),
+                              rounding=0, L=L, eta=eta, seed=3, step=2, j0=s0)
+
+    def check(S, x, what):
+        for s0 in starts:
+            assert np.array_equal(host(S[s0:s0 + ln]), ref[s0]["S"]), (what, s0)
+            assert_within_ulp(host(x[s0:s0 + ln]), ref[s0]["x_new"], 1, "%s x[%d:+%d]" % (what, s0, ln))
+
+    # two-pass: F1, F2
+    S = torch.full((d,), -99, dtype=torch.int32, device=DEV)
+    cnt = torch.zeros(n, dtype=torch.int64, device=DEV)
+    ns = torch.zeros(1, dtype=torch.float64, device=DEV)
+    P.intsgd_compress_sum(desc, rows, d_a, S, cnt, ws)
+    x = x0.clone()
+    P.intsgd_decode_update_norm(desc, S, d_a, eta, x, ns, ws)
+    check(S, x, "two-pass")
+    acc = float((x.double() - x0.double()).pow(2).sum())
+    assert rel_err(host(ns)[0], acc) <= NORM_RTOL
+    # unfused: a1-a3, a4, a5-a6
+    qdt = torch.int8 if wire == P.WIRE_INT8 else torch.int32
+    qbuf = torch.empty((n, W.row_stride(d)), dtype=qdt, device=DEV)
+    qs = [qbuf[i, :d] for i in range(n)]
+    P.intsgd_compress(desc, rows, d_a, qs, cnt, ws)
+    S2 = torch.full((d,), -99, dtype=torch.int32, device=DEV)
+    P.intsgd_int_sum(desc, qs, S2)
+    x2 = x0.clone()
+    P.intsgd_decode_update(desc, S2, d_a, eta, x2, None)
+    check(S2, x2, "unfused")
+    assert torch.equal(S, S2) and torch.equal(x, x2)
+
+
 def test_whole_step_call_equals_step_then_rule():
     """intsgd_step_fused_next_alpha == intsgd_step_fused followed by intsgd_next_alpha,
     bit for bit, for one block and for several."""
