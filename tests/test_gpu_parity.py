@@ -1171,6 +1171,69 @@ def test_resume_from_saved_state_is_bit_identical(rounding):
     assert torch.equal(st_c.norm_sq, st_a.norm_sq)
 
 
+@pytest.mark.parametrize("case", range(16))
+def test_random_long_shapes_two_phase_forms_equal_tile_forms(case):
+    """Seeded random long vectors (ragged last round, a few beyond the cache-resident size),
+    worker counts, rounding, wire, clip, with or without momentum, non-finite and huge
+    gradients sprinkled in: the two-phase forms of the fused step, F1 and a4 give the same
+    bits as the tile forms, which the other tests hold against the oracle."""
+    rng = np.random.default_rng(7000 + case)
+    d = int(rng.integers(1 << 22, (1 << 22) + 7_000_000))
+    n = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 9, 12, 16, 17, 20]))
+    if case % 5 == 0:
+        d, n = int(rng.integers(52_000_000, 66_000_000)), min(n, 3)
+    rounding = int(rng.integers(0, 2))
+    wire = int(rng.choice([P.WIRE_INT8, P.WIRE_INT32]))
+    L = int(rng.choice([1, 15, 127])) if wire == P.WIRE_INT8 else int(rng.choice([1, 1000, P.default_clip(n)]))
+    momentum = bool(rng.integers(0, 2))
+    alpha_v = float(rng.uniform(50, 2000))
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(case)
+    buf = torch.empty((n, W.row_stride(d)), dtype=torch.float32, device=DEV).normal_(0.0, 0.01, generator=gen)
+    idx = torch.randint(0, d, (64,), device=DEV, generator=gen)
+    buf[0, idx[:16]] = float("inf")
+    buf[n - 1, idx[16:32]] = float("nan")
+    buf[0, idx[32:48]] = -3.0e38
+    buf[n // 2, idx[48:]] = 0.5 / alpha_v
+    rows = [buf[i, :d] for i in range(n)]
+    x0 = torch.empty(d, dtype=torch.float32, device=DEV).normal_(0.0, 1.0, generator=gen)
+    m0 = torch.empty(d, dtype=torch.float32, device=DEV).normal_(0.0, 0.01, generator=gen)
+    alpha = torch.tensor([alpha_v], device=DEV)
+    desc = P.Desc(d, n, rounding=rounding, wire=wire, clip=L, seed=case * 7919, step=case)
+    ws = P.new_workspace(desc, DEV)
+    res = {}
+    for form in (1, 2):
+        P.intsgd_set_tuning(two_phase=form)
+        x, m = x0.clone(), m0.clone()
+        ns = torch.zeros(1, dtype=torch.float64, device=DEV)
+        cnt = torch.zeros(n, dtype=torch.int64, device=DEV)
+        if momentum:
+            P.intsgd_step_momentum(desc, rows, alpha, 0.1, 0.9, 1e-4, x, m, None, 0.0, 0.0, ns, cnt, ws)
+        else:
+            P.intsgd_step_fused(desc, rows, alpha, 0.1, x, ns, cnt, ws)
+        S = torch.empty(d, dtype=torch.int32, device=DEV)
+        cnt1 = torch.zeros(n, dtype=torch.int64, device=DEV)
+        P.intsgd_compress_sum(desc, rows, alpha, S, cnt1, ws)
+        qdt = torch.int8 if wire == P.WIRE_INT8 else torch.int32
+        qbuf = torch.empty((n, W.row_stride(d)), dtype=qdt, device=DEV)
+        qs = [qbuf[i, :d] for i in range(n)]
+        cnt2 = torch.zeros(n, dtype=torch.int64, device=DEV)
+        P.intsgd_compress(desc, rows, alpha, qs, cnt2, ws)
+        S2 = torch.empty(d, dtype=torch.int32, device=DEV)
+        P.intsgd_int_sum(desc, qs, S2)
+        torch.cuda.synchronize()
+        res[form] = (x.view(torch.int32), m.view(torch.int32), float(ns.cpu()[0]), cnt.cpu(), S, cnt1.cpu(),
+                     S2, cnt2.cpu())
+        del qbuf, qs
+    a, b = res[1], res[2]
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1]), "x or m differ between the forms"
+    assert torch.equal(a[4], b[4]) and torch.equal(a[6], b[6]) and torch.equal(a[4], a[6]), "sums differ"
+    for k in (3, 5, 7):
+        assert torch.equal(a[k], b[k]) and torch.equal(a[3], a[k]), "clip counts differ"
+    assert a[3].sum() >= 32                     # the non-finite entries were counted
+    assert (np.isnan(a[2]) and np.isnan(b[2])) or abs(a[2] - b[2]) <= 1e-9 * abs(a[2])
+
+
 def test_random_stream_word_by_word():
     """Direct check of the random draws: with alpha = 1 and gradients t in [0, 1) on the
     2^-24 grid, worker i's integer at coordinate j is 1 exactly when the top 24 bits of its
