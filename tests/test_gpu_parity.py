@@ -49,6 +49,8 @@ SHAPES = [
     (2, 1, None, 1024),
     (4096 * 3, 8, None, 2048),
     (33333, 7, [0, 33333], 1024),
+    (5003, 128, None, 2048),                       # the largest worker count the ABI takes
+    (4099, 127, [0, 1, 2050, 4099], 1024),         # every group size (8, 4, 2, 1) in one pass
 ]
 
 
@@ -1182,6 +1184,8 @@ def test_random_long_shapes_two_phase_forms_equal_tile_forms(case):
     n = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 9, 12, 16, 17, 20]))
     if case % 5 == 0:
         d, n = int(rng.integers(52_000_000, 66_000_000)), min(n, 3)
+    if case in (7, 13):
+        n = 128 - (case == 13)                 # the largest worker count, and an odd one next to it
     rounding = int(rng.integers(0, 2))
     wire = int(rng.choice([P.WIRE_INT8, P.WIRE_INT32]))
     L = int(rng.choice([1, 15, 127])) if wire == P.WIRE_INT8 else int(rng.choice([1, 1000, P.default_clip(n)]))
