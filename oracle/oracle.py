@@ -22,7 +22,10 @@ __all__ = [
 ROUND_NEAREST_EVEN = 0
 ROUND_STOCHASTIC = 1
 
-_lib = C.CDLL(_build.build())
+import os as _os
+
+# INTSGD_ORACLE_LIBRARY names another build of the same source (a sanitizer build in the tests)
+_lib = C.CDLL(_os.environ.get("INTSGD_ORACLE_LIBRARY") or _build.build())
 
 _u32p = C.POINTER(C.c_uint32)
 _u64p = C.POINTER(C.c_uint64)
