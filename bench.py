@@ -8,7 +8,12 @@ a single library call.  Gradients, parameters and all state are resident in HBM
 before the timed region; nothing is copied to the host inside it.  Prints ONE JSON
 line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--mode fused]
+  python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+With no --config the headline is the largest workload (5: d = 1.3e9, n = 8, randomized
+rounding) and the line also carries `per_config`, one entry for each of the five
+workloads.  With --config C only that workload runs (what the profiling commands use).
+--copy-probe MiB runs a plain copy of known size instead (counter calibration).
 """
 import argparse
 import json
@@ -21,14 +26,25 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
+HEADLINE_CONFIG = 5
+# State that the sweeps leave in the 256 MB memory-side cache from one step to the next (the
+# library's policy: a state vector up to 192 MB whole, of a larger one the first 224 MB).
+RESIDENT_BYTES = 192 << 20
+KEEP_BYTES = 224 << 20
+# default steps per timed region and workload (about 10-200 ms of GPU time each)
+DEFAULT_STEPS = {1: 200, 2: 100, 3: 100, 4: 50, 5: 20}
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = headline)")
+    ap.add_argument("--steps", type=int, default=0, help="steps per timed region (0 = per workload)")
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--repeats", type=int, default=5,
+                    help="timed regions per workload: the first is the reported one (with per-kernel "
+                         "events), all of them give the median / min")
+    ap.add_argument("--config", type=int, default=0,
+                    help="workload 1..5 alone (0 = headline workload 5 plus per_config for all five)")
     ap.add_argument("--mode", default="fused", choices=["fused", "two_pass", "unfused"],
                     help="fused: one call; two_pass: F1, F2, a8; unfused: a1-a3, a4, a5-a6, a7, a8")
     ap.add_argument("--pool", type=int, default=0,
@@ -39,8 +55,8 @@ def parse():
     ap.add_argument("--two-phase", type=int, default=0, choices=[0, 1, 2],
                     help="form of the fused sweep: 0 automatic, 1 tile sweep, 2 two-phase sweep")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-threads", type=int, default=1,
-                    help="threads for the oracle baseline (each runs the unchanged oracle on a slice)")
+    ap.add_argument("--cpu-threads", type=int, default=0,
+                    help="threads of the all-cores oracle leg (0 = the box's CPU share)")
     ap.add_argument("--no-taps", action="store_true",
                     help="do not record per-kernel events (roofline numbers are then null)")
     ap.add_argument("--global-alpha", action="store_true", help="config 4 with one alpha")
@@ -52,26 +68,37 @@ def parse():
                     help="IntDIANA step (Algorithm 3): n local shifts + a global shift in HBM")
     ap.add_argument("--momentum", action="store_true",
                     help="momentum 0.9 / weight decay 1e-4 form of the update (fused mode)")
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
+                    help="run five plain copies of this size and exit (calibrates FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
 
 
-def cpu_baseline(w, rows, alpha_host, x_host, max_wc=420_000_000, steps=6, threads=1):
-    """The oracle as it stands on a bounded sample of the same workload: `steps`
-    consecutive steps on the leading slice of at most max_wc worker-coordinates (the whole
-    vector when it is small enough); reported in the metric's unit.  One thread by default;
-    with threads > 1 the coordinate range is cut into that many slices and each thread
-    calls the unchanged oracle on its slice (coordinates are independent, norms add)."""
+def host_threads():
+    """Threads for the all-cores oracle leg: the CPUs this process may run on, at most 16
+    (a one-GPU machine's share of its host)."""
+    try:
+        return max(1, min(16, len(os.sched_getaffinity(0))))
+    except AttributeError:
+        return max(1, min(16, os.cpu_count() or 1))
+
+
+def cpu_baseline(w, rows, alpha_host, x_dev, *, threads, coords_per_thread, steps=1):
+    """The oracle as it stands on a bounded sample of the same workload: `steps` consecutive
+    steps on the leading `threads * coords_per_thread` coordinates (the whole vector when it is
+    shorter), copied device -> host beforehand; reported in the metric's unit.  With
+    threads > 1 the coordinate range is cut into that many slices and each thread calls the
+    unchanged oracle on its slice (coordinates are independent, norms add)."""
     from concurrent.futures import ThreadPoolExecutor
 
     import numpy as np
 
     import oracle
-    ln = min(w.d, max(4096, max_wc // w.n))
+    ln = min(w.d, max(4096, threads * coords_per_thread))
     off = None
     if w.block_offsets is not None:
         off = np.array(w.block_offsets, np.uint64)
     g = [r[:ln].cpu().numpy() for r in rows]
-    x = x_host[:ln].copy()
+    x = x_dev[:ln].cpu().numpy()
     alpha = alpha_host
     r = np.zeros(w.num_blocks)
     threads = max(1, min(int(threads), ln // 4096))
@@ -98,13 +125,14 @@ def cpu_baseline(w, rows, alpha_host, x_host, max_wc=420_000_000, steps=6, threa
         pool.shutdown()
     return {"value": 4.0 * w.n * ln * steps / dt / 1e9, "unit": "GB/s", "cores": threads,
             "kind": "oracle",
-            "sample": "%d steps on the first %d of %d coordinates x %d workers (%.1f s)" % (
-                steps, ln, w.d, w.n, dt)}
+            "sample": "%d step(s) on the first %d of %d coordinates x %d workers, one chunk streamed "
+                      "device -> host, %d slice(s) of %d coordinates (%.1f s)" % (
+                          steps, ln, w.d, w.n, threads, ln // threads, dt)}
 
 
 class HipEvents:
     """Raw HIP events from the runtime this process already has loaded (the library's
-    profiling taps take hipEvent_t handles)."""
+    launch options take hipEvent_t handles; the loop timer records on the launch stream)."""
 
     def __init__(self):
         import ctypes as C
@@ -118,6 +146,7 @@ class HipEvents:
         self.C = C
         self.hip = C.CDLL(path)
         self.hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.hip.hipEventRecord.argtypes = [C.c_void_p, C.c_void_p]
         self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
         self.hip.hipEventDestroy.argtypes = [C.c_void_p]
 
@@ -125,6 +154,10 @@ class HipEvents:
         ev = self.C.c_void_p()
         assert self.hip.hipEventCreate(self.C.byref(ev)) == 0
         return ev.value
+
+    def record(self, ev, stream):
+        rc = self.hip.hipEventRecord(ev, stream)
+        assert rc == 0, "hipEventRecord -> %d" % rc
 
     def elapsed_ms(self, a, b):
         ms = self.C.c_float()
@@ -136,50 +169,58 @@ class HipEvents:
         self.hip.hipEventDestroy(ev)
 
 
-def load_traffic(name, form):
-    """HBM bytes per launch of the dominant kernel (fused step, `form` = "tile" or
-    "two_phase") from committed rocprofv3 counter summaries (profiles/traffic.json), or None."""
+def load_counters(name, form):
+    """Committed rocprofv3 --pmc summary of the fused step's sweep kernel for this workload and
+    form ("tile" or "two_phase"), from profiles/traffic.json: HBM bytes per launch and, where
+    recorded, VALUBusy.  NOT measured in this run."""
     path = os.path.join(ROOT, "profiles", "traffic.json")
     try:
         with open(path) as fh:
             table = json.load(fh)
-        return table.get("%s/%s" % (name, form), {}).get("bytes_per_launch")
+        return table.get("%s/%s" % (name, form), {})
     except (OSError, ValueError):
-        return None
+        return {}
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (the n workers are "
-              "n gradient buffers in one HBM); run with --gpus 1", file=sys.stderr)
-        sys.exit(2)
+def copy_probe(mib):
+    import torch
+    n = mib * 1024 * 1024 // 4
+    src = torch.ones(n, dtype=torch.float32, device="cuda:0")
+    dst = torch.empty_like(src)
+    for _ in range(5):
+        torch.mul(src, 1.0, out=dst)      # one elementwise kernel: reads n*4 B, writes n*4 B
+    torch.cuda.synchronize()
+    print(json.dumps({"copy_probe": {"launches": 5, "read_bytes_per_launch": n * 4,
+                                     "write_bytes_per_launch": n * 4}}))
+
+
+def median(v):
+    s = sorted(v)
+    return s[len(s) // 2] if len(s) % 2 else 0.5 * (s[len(s) // 2 - 1] + s[len(s) // 2])
+
+
+def run_workload(args, hip, cfg, *, cpu_legs):
+    """Times one workload; returns (top-level result dict, per_config entry)."""
     import torch
 
     import paper_2102_08374_amd as P
     from paper_2102_08374_amd import workloads as W
     from paper_2102_08374_amd.stepper import Stepper
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
-    torch.cuda.set_device(0)
     rounding = {"config": None, "nearest": 0, "stochastic": 1}[args.rounding]
-    w = W.config(args.config, per_bucket=not args.global_alpha, rounding=rounding)
-    P.intsgd_set_tuning(args.tile, args.grid, args.wgs_per_cu, args.two_phase)
-    tile, grid, wgs_per_cu, two_phase = P.intsgd_get_tuning()
-
+    w = W.config(cfg, per_bucket=not args.global_alpha, rounding=rounding)
+    steps = args.steps or DEFAULT_STEPS[cfg]
+    opts = P.LaunchOpts(args.tile, args.grid, args.wgs_per_cu, args.two_phase)
     desc = P.Desc(w.d, w.n, rounding=w.rounding, wire=w.wire, clip=w.clip, seed=w.philox_seed,
-                  block_offsets=w.block_offsets)
+                  block_offsets=w.block_offsets, opts=opts)
     st = Stepper(desc, eta=w.eta, beta=w.beta, eps=w.eps, device=dev)
     x = W.make_params(w, dev)
 
     grad_bytes = 4 * w.n * w.d
     free, _ = torch.cuda.mem_get_info()
-    pool = args.pool or max(1, min(args.steps + args.warmup, 16, int(0.6 * free // grad_bytes)))
-    sets = []
-    for s in range(pool):
-        buf, rows = W.make_gradients(w, s + 1, dev)
-        sets.append((buf, rows))
+    pool = args.pool or max(1, min(steps + args.warmup, 16, int(0.45 * free // grad_bytes)))
+    sets = [W.make_gradients(w, s + 1, dev) for s in range(pool)]
     sum_buf = torch.empty(w.d, dtype=torch.int32, device=dev) if args.mode != "fused" else None
     q_bufs = x_old_buf = None
     if args.mode == "unfused":
@@ -193,84 +234,135 @@ def main():
         h_local = [hbuf[i, :w.d] for i in range(w.n)]
         h_global = torch.zeros_like(x)
     torch.cuda.synchronize()
+    stream = torch.cuda.current_stream().cuda_stream     # every library call below launches here
 
     def one_step(k, tap=None):
+        """One step; `tap` = a pair of events to attach to the step's (first) sweep kernel."""
         rows = sets[(k - 1) % pool][1]
+        opts.set_events(None, None)
         if args.heuristic:
             nb = 7 if w.wire == 8 else 31
             P.intsgd_heuristic_alpha(desc, rows, nb, st.alpha, st.workspace)   # extra sweep
         if tap is not None:
-            P.intsgd_tap_next_launch(tap[0], tap[1])     # events right around the next sweep
+            opts.set_events(*tap)
+        desc.step = k
         if args.heuristic:
             st.step_fused(rows, x, k, chain_alpha=False)
         elif args.diana:
-            desc.step = k
             P.intsgd_diana_step(desc, rows, h_local, st.alpha, st.eta, x, h_global, st.r, st.beta,
                                 st.eps, st.norm_sq, st.sat_count, st.workspace)
         elif args.momentum:
             st.step_momentum(rows, x, mom, k, 0.9, 1e-4)  # a1-a8 with the momentum update
         elif args.mode == "fused":
             st.step_fused(rows, x, k)                    # a1-a8, one call
-        elif args.mode == "two_pass":
-            st.step_two_pass(rows, x, k, sum_buf)        # F1, F2, a8
-        else:
-            st.step_unfused(rows, x, k, q_bufs, sum_buf, x_old_buf)   # five calls + a copy of x
+        elif args.mode == "two_pass":                    # F1, F2, a8 (Stepper.step_two_pass)
+            P.intsgd_compress_sum(desc, rows, st.alpha, sum_buf, st.sat_count, st.workspace)
+            opts.set_events(None, None)
+            P.intsgd_decode_update_norm(desc, sum_buf, st.alpha, st.eta, x, st.norm_sq, st.workspace)
+            st.next_alpha()
+        else:                                            # five calls + a copy of x (Stepper.step_unfused)
+            P.intsgd_compress(desc, rows, st.alpha, q_bufs, st.sat_count, st.workspace)
+            opts.set_events(None, None)
+            P.intsgd_int_sum(desc, q_bufs, sum_buf)
+            x_old_buf.copy_(x)
+            P.intsgd_decode_update(desc, sum_buf, st.alpha, st.eta, x, None)
+            P.intsgd_update_norm(desc, x, x_old_buf, st.norm_sq, st.workspace)
+            st.next_alpha()
 
     st.start(w.first_normsq)
     alpha0 = st.alpha.cpu().numpy().copy()
-    x0 = None if args.no_cpu_baseline else x.cpu().numpy().copy()
+    x0 = x.clone() if cpu_legs else None
 
-    for k in range(1, args.warmup + 1):
+    k = 0
+    for _ in range(args.warmup):
+        k += 1
         one_step(k)
     torch.cuda.synchronize()
 
-    # timed region: exactly K steps.  In every step the library records a pair of HIP
-    # events right around the sweep kernel, on the stream it launches it on.
-    hip = HipEvents()
-    ev = [(hip.create(), hip.create()) for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        one_step(args.warmup + 1 + i, None if args.no_taps else ev[i])
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    # Timed regions: exactly `steps` steps each, bracketed by a device synchronisation on both
+    # sides (host clock) and by a pair of HIP events recorded on the launch stream.  In the
+    # first region the library also attaches a pair of events to every sweep kernel's dispatch.
+    taps = [] if args.no_taps else [(hip.create(), hip.create()) for _ in range(steps)]
+    loop_ev = [(hip.create(), hip.create()) for _ in range(max(1, args.repeats))]
+    host_ms, event_ms = [], []
+    for rep, (e0, e1) in enumerate(loop_ev):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        hip.record(e0, stream)
+        for i in range(steps):
+            k += 1
+            one_step(k, taps[i] if (rep == 0 and taps) else None)
+        hip.record(e1, stream)
+        torch.cuda.synchronize()
+        host_ms.append((time.perf_counter() - t0) * 1e3 / steps)
+        event_ms.append(hip.elapsed_ms(e0, e1) / steps)
+    opts.set_events(None, None)
 
-    kernel_ms = sorted(hip.elapsed_ms(a, b) for a, b in ev) if not args.no_taps else None
-    for a, b in ev:
+    kernel_ms = sorted(hip.elapsed_ms(a, b) for a, b in taps) if taps else None
+    for a, b in taps + loop_ev:
         hip.destroy(a)
         hip.destroy(b)
     avg_kernel_ms = sum(kernel_ms) / len(kernel_ms) if kernel_ms else None
     per_coord = (4 * w.n + 8) if args.mode == "fused" else (4 * w.n + 4)
+    state_vectors = 1
     if args.mode == "unfused":
         per_coord = (4 + w.wire // 8) * w.n
     if args.momentum:
-        per_coord = 4 * w.n + 16
+        per_coord, state_vectors = 4 * w.n + 16, 2
     if args.diana:
         per_coord = 12 * w.n + 16
     algo_bytes = per_coord * w.d
     achieved = algo_bytes / (avg_kernel_ms * 1e-3) / 1e9 if kernel_ms else None
+    form = P.intsgd_fused_step_form(desc)
     if args.diana:
         kernel_name = "k_diana<ROUND>: Algorithm 3 in one sweep"
     elif args.mode == "unfused":
         kernel_name = "k_compress<ROUND, WIRE>: a1-a3 for all n workers (first of the five calls)"
     elif args.mode != "fused":
-        kernel_name = ("k_aggregate_phased<ROUND, sum only>" if P.intsgd_fused_step_form(desc) == 2
+        kernel_name = ("k_aggregate_phased<ROUND, sum only>" if form == 2
                        else "k_aggregate<ROUND, FUSED=false>") + ": a1-a4 (first of the two sweeps)"
-    elif P.intsgd_fused_step_form(desc) == 2:
+    elif form == 2:
         kernel_name = "k_aggregate_phased<ROUND, MOMENTUM>: a1-a7, gradient reads then x update per round"
     else:
         kernel_name = "k_aggregate<ROUND, FUSED=true, MOMENTUM>: a1-a7 in one tile sweep"
     sat = int(st.sat_count.cpu().numpy().view("uint64").sum())
     alpha_last = float(st.alpha.cpu()[0])
 
+    # Bytes of the fused sweep that the memory-side cache absorbs (the resident part of the
+    # state is read and written there, not in DRAM): what is left is the DRAM-only figure.
+    dram_only_frac = None
+    if kernel_ms and args.mode == "fused" and not args.diana:
+        state_bytes = 4 * w.d * state_vectors
+        resident = state_bytes if state_bytes <= RESIDENT_BYTES else KEEP_BYTES
+        dram_bytes = algo_bytes - 2 * resident
+        dram_only_frac = dram_bytes / (avg_kernel_ms * 1e-3) / 1e9 / HBM_PEAK_GBS
+    counters = {}
+    if args.mode == "fused" and not (args.momentum or args.diana):
+        counters = load_counters(w.name, "two_phase" if form == 2 else "tile")
+
+    claim = cfg != 1        # workload 1 is 16 MB of gradients: cache-resident, launch-bound
+    roofline = {
+        "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": achieved / HBM_PEAK_GBS if kernel_ms else None,
+        "traffic": counters.get("bytes_per_launch"),
+        "traffic_source": "profiles/traffic.json: committed rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
+                          "summary of this kernel and workload, not measured in this run",
+        "dram_only_frac": dram_only_frac,
+        "valu_busy": counters.get("valu_busy"),
+        "kernel": kernel_name,
+        "algorithmic_bytes_per_launch": algo_bytes,
+        "kernel_ms_avg": avg_kernel_ms, "kernel_ms_min": kernel_ms[0] if kernel_ms else None,
+        "kernel_ms_median": median(kernel_ms) if kernel_ms else None,
+        "claim": claim,
+    }
     result = {
         "metric": "fp32 gradient GB/s per IntSGD step (n workers)",
-        "value": grad_bytes * args.steps / dt / 1e9,
+        "value": grad_bytes / (host_ms[0] * 1e-3) / 1e9,
         "unit": "GB/s",
         "n_gpus": 1,
-        "steps": args.steps,
+        "steps": steps,
         "warmup": args.warmup,
-        "ms_per_step": dt * 1e3 / args.steps,
+        "ms_per_step": host_ms[0],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -282,24 +374,78 @@ def main():
             "clip": w.clip, "grad_dist": w.grad_kind,
             "mode": "heuristic-alpha+fused" if args.heuristic else "diana" if args.diana else args.mode + ("+momentum" if args.momentum else ""),
             "gradient_sets": pool,
-            "tuning_overrides": {"tile_coords": tile, "max_workgroups": grid,
-                                 "workgroups_per_cu": wgs_per_cu, "two_phase": two_phase},
+            "launch_options": {"tile_coords": args.tile, "max_workgroups": args.grid,
+                               "workgroups_per_cu": args.wgs_per_cu, "two_phase": args.two_phase},
             "alpha_last": alpha_last,
             "clipped_last_step": sat,
         },
-        "roofline": {
-            "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBS if kernel_ms else None,
-            "traffic": None if (args.momentum or args.diana or args.mode != "fused")
-                       else load_traffic(w.name, "two_phase" if P.intsgd_fused_step_form(desc) == 2 else "tile"),
-            "kernel": kernel_name,
-            "algorithmic_bytes_per_launch": algo_bytes,
-            "kernel_ms_avg": avg_kernel_ms, "kernel_ms_min": kernel_ms[0] if kernel_ms else None,
-            "kernel_ms_median": kernel_ms[len(kernel_ms) // 2] if kernel_ms else None,
+        "timing": {
+            "regions": len(loop_ev), "steps_per_region": steps,
+            "clock": "HIP events on the launch stream around each region; ms per step",
+            "ms_per_step_median": median(event_ms), "ms_per_step_min": min(event_ms),
+            "ms_per_step_host_clock_first_region": host_ms[0],
         },
+        "roofline": roofline,
     }
-    if not args.no_cpu_baseline and not args.momentum and not args.diana:
-        result["cpu_baseline"] = cpu_baseline(w, sets[0][1], alpha0, x0, threads=args.cpu_threads)
+    if cpu_legs:
+        one = cpu_baseline(w, sets[0][1], alpha0, x0, threads=1,
+                           coords_per_thread=cpu_legs["one_core_wc"] // w.n)
+        result["cpu_baseline"] = one
+        if cpu_legs.get("all_cores_wc_per_thread"):
+            th = args.cpu_threads or host_threads()
+            result["cpu_baseline_all_cores"] = cpu_baseline(
+                w, sets[0][1], alpha0, x0, threads=th,
+                coords_per_thread=cpu_legs["all_cores_wc_per_thread"] // w.n)
+    entry = {
+        "workload": w.name, "d": w.d, "n_workers": w.n,
+        "rounding": "stochastic" if w.rounding else "nearest-even",
+        "steps_per_region": steps, "regions": len(loop_ev),
+        "ms_per_step_median": median(event_ms), "ms_per_step_min": min(event_ms),
+        "gradient_gbs": grad_bytes / (median(event_ms) * 1e-3) / 1e9,
+        "kernel": kernel_name.split(":")[0], "kernel_ms": avg_kernel_ms,
+        "algorithmic_bytes": algo_bytes,
+        "frac": roofline["frac"] if claim else None,
+        "dram_only_frac": dram_only_frac if claim else None,
+        "valu_busy": counters.get("valu_busy"),
+        "note": None if claim else "no roofline claim: 16 MB of gradients, cache-resident and launch-bound",
+    }
+    if "cpu_baseline" in result:
+        entry["cpu_baseline_gbs_1_core"] = result["cpu_baseline"]["value"]
+    del sets, x, st
+    torch.cuda.empty_cache()
+    return result, entry
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (the n workers are "
+              "n gradient buffers in one HBM); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    if args.copy_probe:
+        copy_probe(args.copy_probe)
+        return
+    torch.zeros(1, device="cuda:0")          # loads the HIP runtime before HipEvents looks for it
+    hip = HipEvents()
+    widened = args.heuristic or args.diana or args.momentum
+    cpu = not args.no_cpu_baseline and not widened
+    # CPU legs: about 5 s of single-core oracle work; the all-cores leg gives every thread as much
+    big_legs = {"one_core_wc": 1 << 27, "all_cores_wc_per_thread": 1 << 27}
+    if args.config:
+        result, _ = run_workload(args, hip, args.config, cpu_legs=big_legs if cpu else None)
+        print(json.dumps(result))
+        return
+    result, head_entry = run_workload(args, hip, HEADLINE_CONFIG, cpu_legs=big_legs if cpu else None)
+    per_config = []
+    for cfg in (1, 2, 3, 4):
+        _, entry = run_workload(args, hip, cfg, cpu_legs={"one_core_wc": 1 << 26} if cpu else None)
+        per_config.append(entry)
+    per_config.append(head_entry)
+    result["per_config"] = per_config
     print(json.dumps(result))
 
 
