@@ -35,6 +35,9 @@
  *     its own workspace.
  *   - For full bandwidth give every vector a 128-byte aligned start (only 16 is
  *     required).
+ *   - The library keeps no tuning or profiling state of its own: what a call launches
+ *     depends on its arguments only (the descriptor's optional `launch` options
+ *     included), so callers in one process cannot disturb each other.
  */
 #ifndef INTSGD_H_
 #define INTSGD_H_
@@ -45,6 +48,10 @@
 #ifdef __cplusplus
 extern "C" {
 #endif
+
+/* The library is built with hidden visibility: the functions marked INTSGD_API are its
+ * whole dynamic symbol table. */
+#define INTSGD_API __attribute__((visibility("default")))
 
 typedef enum {
   INTSGD_OK = 0,
@@ -68,6 +75,39 @@ typedef enum {
 #define INTSGD_MAX_WORKERS 128u
 
 /*
+ * Optional launch options of the calls made with a descriptor (intsgd_desc.launch; NULL or a
+ * zero field = automatic: the library picks per call what measured best on MI355X).  They
+ * are not part of the numerical contract: results do not depend on them except for the
+ * summation order of the norm.  Read during the call only.
+ *   tile_coords        coordinates per work tile, a multiple of 1024 in [1024, 65536]
+ *   max_workgroups     cap of the launch grid, in [1, 1048576]; tiles beyond it are
+ *                      taken by striding
+ *   workgroups_per_cu  residency cap of the streaming kernels, 2..8 (8 = no cap)
+ *   two_phase          form of the sweeps that have one (intsgd_step_fused, .._next_alpha,
+ *                      intsgd_step_momentum, intsgd_compress_sum; one block, d >= 2^22):
+ *                      1 = always the tile sweep, 2 = always the two-phase sweep (gradient
+ *                      reads, then the write-back, with the integer sums held in registers
+ *                      in between), 0 = automatic (two-phase for nearest-even rounding
+ *                      with more than 8 or fewer than 3 workers).
+ *                      intsgd_int_sum follows it too: automatic = two-phase for any wire
+ *                      (d >= 2^22), 1 = its tile form
+ *   start_event, stop_event   profiling aid: hipEvent_t handles passed as void*, both set or
+ *                      both NULL.  When set, the call attaches them to the dispatch of its
+ *                      streaming kernel on the call's stream (not to the small final-sum
+ *                      kernel behind it), so that hipEventElapsedTime(start, stop) is that
+ *                      kernel's duration.
+ * An out-of-range field makes every call with the descriptor return INTSGD_EINVAL.
+ */
+typedef struct intsgd_launch_opts {
+  uint32_t tile_coords;
+  uint32_t max_workgroups;
+  uint32_t workgroups_per_cu;
+  uint32_t two_phase;
+  void* start_event;
+  void* stop_event;
+} intsgd_launch_opts;
+
+/*
  * Problem statement shared by all calls.
  *   d, n        model dimension and number of workers (Section 1, eq. (1)); d > 0,
  *               1 <= n <= INTSGD_MAX_WORKERS.
@@ -83,6 +123,7 @@ typedef enum {
  *               word (j mod 4) of Philox4x32-10 at counter
  *               (lo32(j/4), hi32(j/4), i, step) with key (lo32(seed), hi32(seed));
  *               the top 24 bits u of the word decide: round up iff u 2^-24 < t - floor(t).
+ *   launch      HOST pointer to launch options, or NULL (automatic).
  */
 typedef struct intsgd_desc {
   uint64_t d;
@@ -94,27 +135,21 @@ typedef struct intsgd_desc {
   int32_t clip;
   uint32_t step;
   uint64_t seed;
+  const intsgd_launch_opts* launch;
 } intsgd_desc;
 
 /* Bytes of DEVICE scratch (256-byte aligned) that any entry point taking a
  * workspace needs for this descriptor; 0 if the descriptor is invalid. */
-size_t intsgd_workspace_bytes(const intsgd_desc* desc);
-
-/* Profiling aid.  The next call of THIS thread that launches a streaming kernel attaches
- * `start_event` and `stop_event` to that kernel's dispatch on the call's stream (not to
- * the small final-sum kernel that follows it), so that hipEventElapsedTime(start, stop)
- * is that kernel's duration; then it forgets both.  Pass hipEvent_t handles as void*:
- * both non-NULL to arm a tap, both NULL to clear a pending one (one of each: EINVAL). */
-intsgd_status intsgd_tap_next_launch(void* start_event, void* stop_event);
+INTSGD_API size_t intsgd_workspace_bytes(const intsgd_desc* desc);
 
 /* Validates the descriptor and builds the library's tile table for its partition
  * now (the only call that may allocate device memory), so that later calls on
  * this partition only enqueue kernels.  Optional. */
-intsgd_status intsgd_prepare(const intsgd_desc* desc);
+INTSGD_API intsgd_status intsgd_prepare(const intsgd_desc* desc);
 
 /* Frees every cached tile table on every device.  Must not run concurrently with
  * other calls. */
-void intsgd_release(void);
+INTSGD_API void intsgd_release(void);
 
 /*
  * a1-a3 (Algorithm 1 "scale and round the local gradient"; Algorithm 2 with B > 1).
@@ -123,7 +158,7 @@ void intsgd_release(void);
  *   q_out     HOST array of n DEVICE pointers, each d int8_t or int32_t per desc->wire.
  *   sat_count DEVICE uint64_t[n], overwritten: clipped or non-finite coordinates per worker.
  */
-intsgd_status intsgd_compress(const intsgd_desc* desc, const float* const* grads,
+INTSGD_API intsgd_status intsgd_compress(const intsgd_desc* desc, const float* const* grads,
                               const float* alpha, void* const* q_out, uint64_t* sat_count,
                               void* workspace, size_t workspace_bytes, void* hip_stream);
 
@@ -132,7 +167,7 @@ intsgd_status intsgd_compress(const intsgd_desc* desc, const float* const* grads
  *   q        HOST array of n DEVICE pointers to int8_t or int32_t vectors (desc->wire).
  *   sum_out  DEVICE int32_t[d].  Exact whenever |q| <= desc->clip.
  */
-intsgd_status intsgd_int_sum(const intsgd_desc* desc, const void* const* q, int32_t* sum_out,
+INTSGD_API intsgd_status intsgd_int_sum(const intsgd_desc* desc, const void* const* q, int32_t* sum_out,
                              void* hip_stream);
 
 /*
@@ -142,7 +177,7 @@ intsgd_status intsgd_int_sum(const intsgd_desc* desc, const void* const* q, int3
  *   x           DEVICE float[d], updated in place.
  *   gtilde_out  DEVICE float[d] or NULL: g~ = fl32(S / (n alpha)).
  */
-intsgd_status intsgd_decode_update(const intsgd_desc* desc, const int32_t* sum,
+INTSGD_API intsgd_status intsgd_decode_update(const intsgd_desc* desc, const int32_t* sum,
                                    const float* alpha, double eta, float* x, float* gtilde_out,
                                    void* hip_stream);
 
@@ -151,7 +186,7 @@ intsgd_status intsgd_decode_update(const intsgd_desc* desc, const int32_t* sum,
  * sum over block l of (x_new[j] - x_old[j])^2, fp64 accumulation of the stored
  * fp32 iterates.  norm_sq_out: DEVICE double[B], overwritten.
  */
-intsgd_status intsgd_update_norm(const intsgd_desc* desc, const float* x_new, const float* x_old,
+INTSGD_API intsgd_status intsgd_update_norm(const intsgd_desc* desc, const float* x_new, const float* x_old,
                                  double* norm_sq_out, void* workspace, size_t workspace_bytes,
                                  void* hip_stream);
 
@@ -164,20 +199,20 @@ intsgd_status intsgd_update_norm(const intsgd_desc* desc, const float* x_new, co
  *   0 <= beta < 1, eps >= 0, eta > 0.  A zero denominator (r = 0 and eps = 0)
  *   yields alpha = +Inf on the device: every coordinate then saturates and is counted.
  */
-intsgd_status intsgd_next_alpha(const intsgd_desc* desc, const double* norm_sq, double* r,
+INTSGD_API intsgd_status intsgd_next_alpha(const intsgd_desc* desc, const double* norm_sq, double* r,
                                 double beta, double eps, double eta, float* alpha_out,
                                 void* hip_stream);
 
 /* Host twin of intsgd_next_alpha: same arithmetic on HOST arrays, no device
  * involved.  Returns INTSGD_ERANGE (and still writes +Inf) on a zero denominator. */
-intsgd_status intsgd_next_alpha_host(const intsgd_desc* desc, const double* norm_sq, double* r,
+INTSGD_API intsgd_status intsgd_next_alpha_host(const intsgd_desc* desc, const double* norm_sq, double* r,
                                      double beta, double eps, double eta, float* alpha_out);
 
 /*
  * F1 = a1-a4 in one pass over the n gradient streams: sum_out DEVICE int32_t[d],
  * sat_count DEVICE uint64_t[n].  Bit-identical to intsgd_compress + intsgd_int_sum.
  */
-intsgd_status intsgd_compress_sum(const intsgd_desc* desc, const float* const* grads,
+INTSGD_API intsgd_status intsgd_compress_sum(const intsgd_desc* desc, const float* const* grads,
                                   const float* alpha, int32_t* sum_out, uint64_t* sat_count,
                                   void* workspace, size_t workspace_bytes, void* hip_stream);
 
@@ -185,7 +220,7 @@ intsgd_status intsgd_compress_sum(const intsgd_desc* desc, const float* const* g
  * F2 = a5-a7 in one pass over S and x: x updated in place, norm_sq_out DEVICE
  * double[B] = ||x_new - x_old||^2 per block.  Same x as intsgd_decode_update.
  */
-intsgd_status intsgd_decode_update_norm(const intsgd_desc* desc, const int32_t* sum,
+INTSGD_API intsgd_status intsgd_decode_update_norm(const intsgd_desc* desc, const int32_t* sum,
                                         const float* alpha, double eta, float* x,
                                         double* norm_sq_out, void* workspace,
                                         size_t workspace_bytes, void* hip_stream);
@@ -195,7 +230,7 @@ intsgd_status intsgd_decode_update_norm(const intsgd_desc* desc, const int32_t* 
  * device because no real all-reduce separates a4 from a5).  Same x, norms and
  * counts as F1 followed by F2.
  */
-intsgd_status intsgd_step_fused(const intsgd_desc* desc, const float* const* grads,
+INTSGD_API intsgd_status intsgd_step_fused(const intsgd_desc* desc, const float* const* grads,
                                 const float* alpha, double eta, float* x, double* norm_sq_out,
                                 uint64_t* sat_count, void* workspace, size_t workspace_bytes,
                                 void* hip_stream);
@@ -204,14 +239,18 @@ intsgd_status intsgd_step_fused(const intsgd_desc* desc, const float* const* gra
  * The whole step in one call: F3, whose small final-sum kernel also applies a8
  * (Section 4.1 / Algorithm 2).  alpha: DEVICE float[B], read as alpha_k during the
  * sweep and overwritten with alpha_{k+1} afterwards; r: DEVICE double[B] in/out;
- * norm_sq_out, sat_count as in intsgd_step_fused.  eta is eta_k for both the update
- * and the rule.  Same results as intsgd_step_fused followed by intsgd_next_alpha.
+ * norm_sq_out, sat_count as in intsgd_step_fused.  eta is eta_k, the stepsize of this
+ * step's update; eta_next is eta_{k+1}, the stepsize that Algorithm 1's scaling-factor
+ * line pairs with alpha_{k+1} (equal to eta under a constant stepsize).  Same results as
+ * intsgd_step_fused(eta) followed by intsgd_next_alpha(eta_next).
  */
-intsgd_status intsgd_step_fused_next_alpha(const intsgd_desc* desc, const float* const* grads,
-                                           float* alpha, double eta, float* x, double* r,
-                                           double beta, double eps, double* norm_sq_out,
-                                           uint64_t* sat_count, void* workspace,
-                                           size_t workspace_bytes, void* hip_stream);
+INTSGD_API intsgd_status intsgd_step_fused_next_alpha(const intsgd_desc* desc,
+                                                      const float* const* grads, float* alpha,
+                                                      double eta, double eta_next, float* x,
+                                                      double* r, double beta, double eps,
+                                                      double* norm_sq_out, uint64_t* sat_count,
+                                                      void* workspace, size_t workspace_bytes,
+                                                      void* hip_stream);
 
 /*
  * Momentum / weight-decay form of the update (the optimizer of the paper's experiments,
@@ -224,18 +263,20 @@ intsgd_status intsgd_step_fused_next_alpha(const intsgd_desc* desc, const float*
  *
  * intsgd_decode_update_momentum: F2 with this update (a5-a7 on a given aggregate).
  * intsgd_step_momentum: F3 with this update in one sweep; if r is not NULL, a8 is applied
- * as in intsgd_step_fused_next_alpha (alpha in/out), otherwise alpha is only read.
+ * as in intsgd_step_fused_next_alpha (alpha in/out, with eta_next), otherwise alpha is only
+ * read and eta_next is ignored.
  */
-intsgd_status intsgd_decode_update_momentum(const intsgd_desc* desc, const int32_t* sum,
+INTSGD_API intsgd_status intsgd_decode_update_momentum(const intsgd_desc* desc, const int32_t* sum,
                                             const float* alpha, double eta, double mu,
                                             double weight_decay, float* x, float* m,
                                             double* norm_sq_out, void* workspace,
                                             size_t workspace_bytes, void* hip_stream);
-intsgd_status intsgd_step_momentum(const intsgd_desc* desc, const float* const* grads,
-                                   float* alpha, double eta, double mu, double weight_decay,
-                                   float* x, float* m, double* r, double beta, double eps,
-                                   double* norm_sq_out, uint64_t* sat_count, void* workspace,
-                                   size_t workspace_bytes, void* hip_stream);
+INTSGD_API intsgd_status intsgd_step_momentum(const intsgd_desc* desc, const float* const* grads,
+                                              float* alpha, double eta, double eta_next, double mu,
+                                              double weight_decay, float* x, float* m, double* r,
+                                              double beta, double eps, double* norm_sq_out,
+                                              uint64_t* sat_count, void* workspace,
+                                              size_t workspace_bytes, void* hip_stream);
 
 /*
  * IntDIANA (Appendix A.2, Algorithm 3) in one sweep, for heterogeneous workers: every
@@ -251,13 +292,15 @@ intsgd_status intsgd_step_momentum(const intsgd_desc* desc, const float* const* 
  *   h_local  HOST array of n DEVICE pointers (d floats each, in/out), 16-byte aligned
  *   h        DEVICE float[d], global shift, in/out;  x DEVICE float[d], in/out
  *   r        DEVICE double[B] or NULL.  Not NULL: a8 is applied afterwards (alpha in/out) with
- *            the given beta, eps; Algorithm 3's own rule is beta = 0, eps = 0.
+ *            eta_next (the next step's stepsize, which Algorithm 3's scaling-factor line
+ *            uses) and the given beta, eps; Algorithm 3's own rule is beta = 0, eps = 0.
  */
-intsgd_status intsgd_diana_step(const intsgd_desc* desc, const float* const* grads,
-                                float* const* h_local, float* alpha, double eta, float* x,
-                                float* h, double* r, double beta, double eps, double* norm_sq_out,
-                                uint64_t* sat_count, void* workspace, size_t workspace_bytes,
-                                void* hip_stream);
+INTSGD_API intsgd_status intsgd_diana_step(const intsgd_desc* desc, const float* const* grads,
+                                           float* const* h_local, float* alpha, double eta,
+                                           double eta_next, float* x, float* h, double* r,
+                                           double beta, double eps, double* norm_sq_out,
+                                           uint64_t* sat_count, void* workspace,
+                                           size_t workspace_bytes, void* hip_stream);
 
 /*
  * Heuristic IntSGD scaling (Section 5.2: the SwitchML rule the paper compares with), which
@@ -269,43 +312,20 @@ intsgd_status intsgd_diana_step(const intsgd_desc* desc, const float* const* gra
  * the largest finite fp32.  alpha_out: DEVICE float[B].  The result can be passed to any
  * of the compress / step calls in place of the adaptive alpha.
  */
-intsgd_status intsgd_heuristic_alpha(const intsgd_desc* desc, const float* const* grads,
+INTSGD_API intsgd_status intsgd_heuristic_alpha(const intsgd_desc* desc, const float* const* grads,
                                      uint32_t nb, float* alpha_out, void* workspace,
                                      size_t workspace_bytes, void* hip_stream);
 
-/* Tuning overrides (process-wide; not part of the numerical contract: results do not
- * depend on them except for the summation order of the norm).  A field that is 0
- * means "automatic": the library picks per call (by rounding mode) what measured best
- * on MI355X.  intsgd_set_tuning replaces all fields.
- *   tile_coords        coordinates per work tile, a multiple of 1024 in [1024, 65536]
- *   max_workgroups     cap of the launch grid, in [1, 1048576]; tiles beyond it are
- *                      taken by striding
- *   workgroups_per_cu  residency cap of the streaming kernels, 2..8 (8 = no cap)
- *   two_phase          form of the sweeps that have one (intsgd_step_fused, .._next_alpha,
- *                      intsgd_step_momentum, intsgd_compress_sum; one block, d >= 2^22):
- *                      1 = always the tile sweep, 2 = always the two-phase sweep (gradient
- *                      reads, then the write-back, with the integer sums held in registers
- *                      in between), 0 = automatic (two-phase for nearest-even rounding
- *                      with more than 8 or fewer than 3 workers).
- *                      intsgd_int_sum follows it too: automatic = two-phase for any wire
- *                      (d >= 2^22), 1 = its tile form */
-typedef struct intsgd_tuning {
-  uint32_t tile_coords;
-  uint32_t max_workgroups;
-  uint32_t workgroups_per_cu;
-  uint32_t two_phase;
-} intsgd_tuning;
-intsgd_status intsgd_set_tuning(const intsgd_tuning* tuning);
-void intsgd_get_tuning(intsgd_tuning* tuning);
 /* Which form the fused step (intsgd_step_fused, .._next_alpha, intsgd_step_momentum) and
- * intsgd_compress_sum take for this descriptor under the current tuning: 1 = tile sweep,
- * 2 = two-phase sweep;
- * 0 if the descriptor is invalid.  Host-only, launches nothing. */
-int intsgd_fused_step_form(const intsgd_desc* desc);
+ * intsgd_compress_sum take for this descriptor (its launch options included): 1 = tile
+ * sweep, 2 = two-phase sweep; 0 if the descriptor is invalid.  Host-only, launches nothing. */
+INTSGD_API int intsgd_fused_step_form(const intsgd_desc* desc);
 
-const char* intsgd_status_string(intsgd_status status);
+/* Text of a status code; takes a plain int so that any value is a defined argument
+ * ("unknown status" for codes that are not an intsgd_status). */
+INTSGD_API const char* intsgd_status_string(int status);
 /* Text of the last HIP error seen by this thread's calls ("" if none). */
-const char* intsgd_last_hip_error(void);
+INTSGD_API const char* intsgd_last_hip_error(void);
 
 #ifdef __cplusplus
 }

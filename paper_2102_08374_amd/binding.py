@@ -17,8 +17,8 @@ __all__ = [
     "intsgd_update_norm", "intsgd_next_alpha", "intsgd_next_alpha_host", "intsgd_compress_sum",
     "intsgd_decode_update_norm", "intsgd_step_fused", "intsgd_step_fused_next_alpha",
     "intsgd_decode_update_momentum", "intsgd_step_momentum", "intsgd_diana_step",
-    "intsgd_heuristic_alpha", "intsgd_tap_next_launch", "intsgd_set_tuning", "intsgd_get_tuning",
-    "intsgd_fused_step_form", "intsgd_status_string", "new_workspace", "EXPORTED_SYMBOLS",
+    "intsgd_heuristic_alpha", "intsgd_fused_step_form", "intsgd_status_string", "new_workspace",
+    "EXPORTED_SYMBOLS", "LaunchOpts",
 ]
 
 ROUND_NEAREST_EVEN = 0
@@ -28,17 +28,21 @@ WIRE_INT32 = 32
 MAX_WORKERS = 128
 
 EXPORTED_SYMBOLS = [
-    "intsgd_workspace_bytes", "intsgd_tap_next_launch", "intsgd_prepare", "intsgd_release",
+    "intsgd_workspace_bytes", "intsgd_prepare", "intsgd_release",
     "intsgd_compress", "intsgd_step_fused_next_alpha", "intsgd_decode_update_momentum",
     "intsgd_step_momentum", "intsgd_diana_step", "intsgd_heuristic_alpha",
     "intsgd_int_sum", "intsgd_decode_update", "intsgd_update_norm", "intsgd_next_alpha",
     "intsgd_next_alpha_host", "intsgd_compress_sum", "intsgd_decode_update_norm",
-    "intsgd_step_fused", "intsgd_set_tuning", "intsgd_get_tuning", "intsgd_fused_step_form",
-    "intsgd_status_string", "intsgd_last_hip_error",
+    "intsgd_step_fused", "intsgd_fused_step_form", "intsgd_status_string", "intsgd_last_hip_error",
 ]
 
 
 def library_path() -> str:
+    """The in-tree build; INTSGD_LIBRARY names another build of the same sources (e.g. one
+    whose host code is compiled with sanitizers)."""
+    override = os.environ.get("INTSGD_LIBRARY")
+    if override:
+        return override
     return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libintsgd.so")
 
 
@@ -54,16 +58,17 @@ def _load():
 _lib = _load()
 
 
+class _CLaunchOpts(C.Structure):
+    _fields_ = [("tile_coords", C.c_uint32), ("max_workgroups", C.c_uint32),
+                ("workgroups_per_cu", C.c_uint32), ("two_phase", C.c_uint32),
+                ("start_event", C.c_void_p), ("stop_event", C.c_void_p)]
+
+
 class _CDesc(C.Structure):
     _fields_ = [("d", C.c_uint64), ("n", C.c_uint32), ("num_blocks", C.c_uint32),
                 ("block_offsets", C.POINTER(C.c_uint64)), ("rounding", C.c_int32),
                 ("wire", C.c_int32), ("clip", C.c_int32), ("step", C.c_uint32),
-                ("seed", C.c_uint64)]
-
-
-class _CTuning(C.Structure):
-    _fields_ = [("tile_coords", C.c_uint32), ("max_workgroups", C.c_uint32),
-                ("workgroups_per_cu", C.c_uint32), ("two_phase", C.c_uint32)]
+                ("seed", C.c_uint64), ("launch", C.POINTER(_CLaunchOpts))]
 
 
 _P = C.c_void_p
@@ -84,19 +89,15 @@ _lib.intsgd_next_alpha_host.argtypes = [_DP, C.POINTER(C.c_double), C.POINTER(C.
 _lib.intsgd_compress_sum.argtypes = [_DP, _PP, _P, _P, _P, _P, C.c_size_t, _P]
 _lib.intsgd_decode_update_norm.argtypes = [_DP, _P, _P, C.c_double, _P, _P, _P, C.c_size_t, _P]
 _lib.intsgd_step_fused.argtypes = [_DP, _PP, _P, C.c_double, _P, _P, _P, _P, C.c_size_t, _P]
-_lib.intsgd_step_fused_next_alpha.argtypes = [_DP, _PP, _P, C.c_double, _P, _P, C.c_double,
-                                              C.c_double, _P, _P, _P, C.c_size_t, _P]
-_lib.intsgd_tap_next_launch.argtypes = [_P, _P]
+_lib.intsgd_step_fused_next_alpha.argtypes = [_DP, _PP, _P, C.c_double, C.c_double, _P, _P,
+                                              C.c_double, C.c_double, _P, _P, _P, C.c_size_t, _P]
 _lib.intsgd_decode_update_momentum.argtypes = [_DP, _P, _P, C.c_double, C.c_double, C.c_double, _P,
                                                _P, _P, _P, C.c_size_t, _P]
-_lib.intsgd_diana_step.argtypes = [_DP, _PP, _PP, _P, C.c_double, _P, _P, _P, C.c_double, C.c_double,
-                                   _P, _P, _P, C.c_size_t, _P]
+_lib.intsgd_diana_step.argtypes = [_DP, _PP, _PP, _P, C.c_double, C.c_double, _P, _P, _P, C.c_double,
+                                   C.c_double, _P, _P, _P, C.c_size_t, _P]
 _lib.intsgd_heuristic_alpha.argtypes = [_DP, _PP, C.c_uint32, _P, _P, C.c_size_t, _P]
-_lib.intsgd_step_momentum.argtypes = [_DP, _PP, _P, C.c_double, C.c_double, C.c_double, _P, _P, _P,
-                                      C.c_double, C.c_double, _P, _P, _P, C.c_size_t, _P]
-_lib.intsgd_set_tuning.argtypes = [C.POINTER(_CTuning)]
-_lib.intsgd_get_tuning.argtypes = [C.POINTER(_CTuning)]
-_lib.intsgd_get_tuning.restype = None
+_lib.intsgd_step_momentum.argtypes = [_DP, _PP, _P, C.c_double, C.c_double, C.c_double, C.c_double,
+                                      _P, _P, _P, C.c_double, C.c_double, _P, _P, _P, C.c_size_t, _P]
 _lib.intsgd_fused_step_form.argtypes = [_DP]
 _lib.intsgd_fused_step_form.restype = C.c_int
 _lib.intsgd_status_string.argtypes = [C.c_int]
@@ -106,8 +107,7 @@ _lib.intsgd_last_hip_error.restype = C.c_char_p
 for _name in ("intsgd_prepare", "intsgd_compress", "intsgd_int_sum", "intsgd_decode_update",
               "intsgd_update_norm", "intsgd_next_alpha", "intsgd_next_alpha_host",
               "intsgd_compress_sum", "intsgd_decode_update_norm", "intsgd_step_fused",
-              "intsgd_step_fused_next_alpha", "intsgd_tap_next_launch", "intsgd_set_tuning",
-              "intsgd_decode_update_momentum", "intsgd_step_momentum", "intsgd_diana_step",
+              "intsgd_step_fused_next_alpha", "intsgd_decode_update_momentum", "intsgd_step_momentum", "intsgd_diana_step",
               "intsgd_heuristic_alpha"):
     getattr(_lib, _name).restype = C.c_int
 
@@ -131,11 +131,30 @@ def default_clip(n: int, wire: int = WIRE_INT32) -> int:
     return ((1 << (wire - 1)) - 1) // max(1, int(n))
 
 
+class LaunchOpts:
+    """include/intsgd.h's intsgd_launch_opts: per-descriptor launch options (0 = automatic)
+    and the optional pair of raw hipEvent_t handles that bracket a call's streaming kernel."""
+
+    def __init__(self, tile_coords=0, max_workgroups=0, workgroups_per_cu=0, two_phase=0,
+                 start_event=None, stop_event=None):
+        self.c = _CLaunchOpts(int(tile_coords), int(max_workgroups), int(workgroups_per_cu),
+                              int(two_phase), start_event or None, stop_event or None)
+
+    def set_events(self, start_event, stop_event):
+        """Raw hipEvent_t handles (ints), or None / None to detach."""
+        self.c.start_event = start_event or None
+        self.c.stop_event = stop_event or None
+
+    def as_tuple(self):
+        return (self.c.tile_coords, self.c.max_workgroups, self.c.workgroups_per_cu, self.c.two_phase)
+
+
 class Desc:
-    """Problem statement of include/intsgd.h's intsgd_desc (keeps the offsets alive)."""
+    """Problem statement of include/intsgd.h's intsgd_desc (keeps the offsets and the launch
+    options alive)."""
 
     def __init__(self, d, n, *, rounding=ROUND_NEAREST_EVEN, wire=WIRE_INT32, clip=None, seed=0,
-                 step=0, block_offsets=None):
+                 step=0, block_offsets=None, opts=None):
         self._offsets = None
         num_blocks = 1
         ptr = None
@@ -147,7 +166,8 @@ class Desc:
         if clip is None:
             clip = default_clip(n, WIRE_INT32)
         self.c = _CDesc(int(d), int(n), int(num_blocks), ptr, int(rounding), int(wire), int(clip),
-                        int(step) & 0xFFFFFFFF, int(seed) & 0xFFFFFFFFFFFFFFFF)
+                        int(step) & 0xFFFFFFFF, int(seed) & 0xFFFFFFFFFFFFFFFF, None)
+        self.opts = opts
 
     d = property(lambda self: self.c.d)
     n = property(lambda self: self.c.n)
@@ -161,6 +181,16 @@ class Desc:
     @step.setter
     def step(self, k):
         self.c.step = int(k) & 0xFFFFFFFF
+
+    @property
+    def opts(self):
+        return self._opts
+
+    @opts.setter
+    def opts(self, opts):
+        """A LaunchOpts (kept alive by this object) or None = automatic."""
+        self._opts = opts
+        self.c.launch = C.pointer(opts.c) if opts is not None else None
 
     def ref(self):
         return C.byref(self.c)
@@ -219,12 +249,6 @@ def _ws(workspace):
 
 def intsgd_workspace_bytes(desc: Desc) -> int:
     return int(_lib.intsgd_workspace_bytes(desc.ref()))
-
-
-def intsgd_tap_next_launch(start_event, stop_event):
-    """Raw hipEvent_t handles (ints) or None; see include/intsgd.h."""
-    _check(_lib.intsgd_tap_next_launch(C.c_void_p(start_event or 0), C.c_void_p(stop_event or 0)),
-           "intsgd_tap_next_launch")
 
 
 def new_workspace(desc: Desc, device="cuda") -> torch.Tensor:
@@ -331,7 +355,8 @@ def intsgd_step_fused(desc, grads, alpha, eta, x, norm_sq_out, sat_count, worksp
 
 
 def intsgd_step_fused_next_alpha(desc, grads, alpha, eta, x, r, beta, eps, norm_sq_out, sat_count,
-                                 workspace, stream=None):
+                                 workspace, stream=None, eta_next=None):
+    """eta_next: the next step's stepsize (None = the same eta)."""
     _need_rows(desc, grads, torch.float32, "grads")
     _need(alpha, desc.num_blocks, torch.float32, "alpha")
     _need(x, desc.d, torch.float32, "x")
@@ -340,6 +365,7 @@ def intsgd_step_fused_next_alpha(desc, grads, alpha, eta, x, r, beta, eps, norm_
     _need(sat_count, desc.n, torch.int64, "sat_count")
     w, wb = _ws(workspace)
     _check(_lib.intsgd_step_fused_next_alpha(desc.ref(), _ptr_array(grads), _ptr(alpha), float(eta),
+                                             float(eta if eta_next is None else eta_next),
                                              _ptr(x), _ptr(r), float(beta), float(eps),
                                              _ptr(norm_sq_out), _ptr(sat_count), w, wb,
                                              _stream(stream)), "intsgd_step_fused_next_alpha")
@@ -360,8 +386,8 @@ def intsgd_decode_update_momentum(desc, sum_, alpha, eta, mu, weight_decay, x, m
 
 
 def intsgd_step_momentum(desc, grads, alpha, eta, mu, weight_decay, x, m, r, beta, eps, norm_sq_out,
-                         sat_count, workspace, stream=None):
-    """r may be None: alpha is then only read (no a8)."""
+                         sat_count, workspace, stream=None, eta_next=None):
+    """r may be None: alpha is then only read (no a8).  eta_next: the next step's stepsize."""
     _need_rows(desc, grads, torch.float32, "grads")
     _need(alpha, desc.num_blocks, torch.float32, "alpha")
     _need(x, desc.d, torch.float32, "x")
@@ -371,14 +397,15 @@ def intsgd_step_momentum(desc, grads, alpha, eta, mu, weight_decay, x, m, r, bet
     _need(sat_count, desc.n, torch.int64, "sat_count")
     w, wb = _ws(workspace)
     _check(_lib.intsgd_step_momentum(desc.ref(), _ptr_array(grads), _ptr(alpha), float(eta),
+                                     float(eta if eta_next is None else eta_next),
                                      float(mu), float(weight_decay), _ptr(x), _ptr(m), _ptr(r),
                                      float(beta), float(eps), _ptr(norm_sq_out), _ptr(sat_count),
                                      w, wb, _stream(stream)), "intsgd_step_momentum")
 
 
 def intsgd_diana_step(desc, grads, h_local, alpha, eta, x, h, r, beta, eps, norm_sq_out, sat_count,
-                      workspace, stream=None):
-    """IntDIANA step; r may be None (alpha only read)."""
+                      workspace, stream=None, eta_next=None):
+    """IntDIANA step; r may be None (alpha only read).  eta_next: the next step's stepsize."""
     _need_rows(desc, grads, torch.float32, "grads")
     _need_rows(desc, h_local, torch.float32, "h_local")
     _need(alpha, desc.num_blocks, torch.float32, "alpha")
@@ -389,7 +416,7 @@ def intsgd_diana_step(desc, grads, h_local, alpha, eta, x, h, r, beta, eps, norm
     _need(sat_count, desc.n, torch.int64, "sat_count")
     w, wb = _ws(workspace)
     _check(_lib.intsgd_diana_step(desc.ref(), _ptr_array(grads), _ptr_array(h_local), _ptr(alpha),
-                                  float(eta), _ptr(x), _ptr(h), _ptr(r), float(beta), float(eps),
+                                  float(eta), float(eta if eta_next is None else eta_next), _ptr(x), _ptr(h), _ptr(r), float(beta), float(eps),
                                   _ptr(norm_sq_out), _ptr(sat_count), w, wb, _stream(stream)),
            "intsgd_diana_step")
 
@@ -400,18 +427,6 @@ def intsgd_heuristic_alpha(desc, grads, nb, alpha_out, workspace, stream=None):
     w, wb = _ws(workspace)
     _check(_lib.intsgd_heuristic_alpha(desc.ref(), _ptr_array(grads), int(nb), _ptr(alpha_out), w, wb,
                                        _stream(stream)), "intsgd_heuristic_alpha")
-
-
-def intsgd_set_tuning(tile_coords=0, max_workgroups=0, workgroups_per_cu=0, two_phase=0):
-    t = _CTuning(int(tile_coords), int(max_workgroups), int(workgroups_per_cu), int(two_phase))
-    _check(_lib.intsgd_set_tuning(C.byref(t)), "intsgd_set_tuning")
-
-
-def intsgd_get_tuning():
-    """-> (tile_coords, max_workgroups, workgroups_per_cu, two_phase)"""
-    t = _CTuning()
-    _lib.intsgd_get_tuning(C.byref(t))
-    return int(t.tile_coords), int(t.max_workgroups), int(t.workgroups_per_cu), int(t.two_phase)
 
 
 def intsgd_fused_step_form(desc: "Desc") -> int:

@@ -26,14 +26,16 @@ constexpr uint64_t kMaxD = 1ull << 40;
 constexpr size_t kAlign = 256;
 constexpr uint32_t kLdsPerCu = 160u * 1024u;    // gfx950
 
-// Process-wide overrides; a zero field means "automatic".  Read and written under their
-// own lock, so that a call racing with intsgd_set_tuning sees the old or the new set whole.
-std::mutex g_tuning_mutex;
-intsgd_tuning g_tuning = {0, 0, 0, 0};
+// The caller's launch options (a zero field means "automatic"), copied once per call so
+// that a call sees one consistent set even if the caller's struct changes under it.
+struct Tuning {
+  uint32_t tile_coords, max_workgroups, workgroups_per_cu, two_phase;
+};
 
-intsgd_tuning current_tuning() {
-  std::lock_guard<std::mutex> lock(g_tuning_mutex);
-  return g_tuning;
+Tuning requested_tuning(const intsgd_desc* desc) {
+  const intsgd_launch_opts* o = desc->launch;
+  if (o == nullptr) return Tuning{0, 0, 0, 0};
+  return Tuning{o->tile_coords, o->max_workgroups, o->workgroups_per_cu, o->two_phase};
 }
 
 // Automatic choices of the tile sweeps, measured on MI355X.  Nearest-even rounding is bound by
@@ -43,9 +45,9 @@ intsgd_tuning current_tuning() {
 // Randomized rounding is co-bound by the integer ALU (Philox): 16 KB tiles and the
 // reservation for four, of which the kernel's 70 VGPRs let three be resident (two measured
 // 4 % slower on 8 x 25.6 M; a build squeezed into 64 VGPRs so that four fit, 3-5 % slower).
-intsgd_tuning effective_tuning(const intsgd_desc* desc) {
+Tuning effective_tuning(const intsgd_desc* desc) {
   const bool random = desc->rounding == INTSGD_ROUND_STOCHASTIC;
-  intsgd_tuning t = current_tuning();
+  Tuning t = requested_tuning(desc);
   if (t.tile_coords == 0) t.tile_coords = random ? 4096 : 2048;
   if (t.max_workgroups == 0) t.max_workgroups = kMaxGrid;
   if (t.workgroups_per_cu == 0) t.workgroups_per_cu = (random || desc->n <= 8) ? 4 : 2;
@@ -58,20 +60,19 @@ intsgd_tuning effective_tuning(const intsgd_desc* desc) {
 // 3..8 workers, where a thread of the tile sweep has all its loads in one group and four
 // resident workgroups per CU stream as fast or faster (n = 8: 81-85 % against 78-82 %).
 constexpr uint64_t kMinPhasedD = 1ull << 22;
-bool use_two_phase(const intsgd_desc* desc, const intsgd_tuning& t) {
+bool use_two_phase(const intsgd_desc* desc, const Tuning& t) {
   if (desc->num_blocks != 1 || desc->d < kMinPhasedD || t.two_phase == 1) return false;
   if (t.two_phase == 2) return true;
   return desc->rounding == INTSGD_ROUND_NEAREST_EVEN && (desc->n > 8 || desc->n <= 2);
 }
 
 thread_local std::string t_hip_error;
-thread_local hipEvent_t t_tap_start = nullptr, t_tap_stop = nullptr;
 
-// Moves this thread's pending profiling taps (if any) into a launch.
-void take_taps(LaunchShape* ls) {
-  ls->tap_start = t_tap_start;
-  ls->tap_stop = t_tap_stop;
-  t_tap_start = t_tap_stop = nullptr;
+// The profiling events of the caller's launch options (if any) go to the call's streaming kernel.
+void take_taps(const intsgd_desc* desc, LaunchShape* ls) {
+  const intsgd_launch_opts* o = desc->launch;
+  ls->tap_start = o ? static_cast<hipEvent_t>(o->start_event) : nullptr;
+  ls->tap_stop = o ? static_cast<hipEvent_t>(o->stop_event) : nullptr;
 }
 
 intsgd_status hip_fail(hipError_t e) {
@@ -101,6 +102,17 @@ intsgd_status compute_units(uint32_t* out) {
 size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+intsgd_status validate_launch_opts(const intsgd_launch_opts* o) {
+  if (o == nullptr) return INTSGD_OK;
+  const uint32_t tile = o->tile_coords, grid = o->max_workgroups, wgs = o->workgroups_per_cu;
+  if (tile != 0 && (tile < kMinTile || tile > kMaxTile || tile % kMinTile != 0)) return INTSGD_EINVAL;
+  if (grid > kMaxGrid) return INTSGD_EINVAL;
+  if (wgs != 0 && (wgs < 2 || wgs > 8)) return INTSGD_EINVAL;
+  if (o->two_phase > 2) return INTSGD_EINVAL;
+  if ((o->start_event == nullptr) != (o->stop_event == nullptr)) return INTSGD_EINVAL;
+  return INTSGD_OK;
+}
+
 intsgd_status validate_desc(const intsgd_desc* desc) {
   if (desc == nullptr) return INTSGD_EINVAL;
   if (desc->d == 0 || desc->n == 0 || desc->num_blocks == 0) return INTSGD_EINVAL;
@@ -120,7 +132,7 @@ intsgd_status validate_desc(const intsgd_desc* desc) {
     for (uint32_t l = 0; l < desc->num_blocks; ++l)
       if (off[l + 1] <= off[l]) return INTSGD_EINVAL;
   }
-  return INTSGD_OK;
+  return validate_launch_opts(desc->launch);
 }
 
 intsgd_status validate_rule(double beta, double eps, double eta) {
@@ -293,10 +305,10 @@ uint32_t compress_tile(const intsgd_desc* desc) {
 
 intsgd_status make_tiling(const intsgd_desc* desc, void* stream, Tiling* t,
                           uint32_t automatic_tile = 0) {
-  const intsgd_tuning tune = effective_tuning(desc);
+  const Tuning tune = effective_tuning(desc);
   // a kernel may have its own automatic tile; an explicit override still wins
   const uint32_t tile =
-      (automatic_tile != 0 && current_tuning().tile_coords == 0) ? automatic_tile : tune.tile_coords;
+      (automatic_tile != 0 && requested_tuning(desc).tile_coords == 0) ? automatic_tile : tune.tile_coords;
   t->tm.d = desc->d;
   t->tm.tile = tile;
   if (desc->num_blocks == 1) {
@@ -316,7 +328,7 @@ intsgd_status make_tiling(const intsgd_desc* desc, void* stream, Tiling* t,
   t->ls.grid = t->tm.num_tiles < tune.max_workgroups ? t->tm.num_tiles : tune.max_workgroups;
   t->ls.lds_reserve = lds_reserve_for(tune.workgroups_per_cu);
   t->ls.stream = static_cast<hipStream_t>(stream);
-  take_taps(&t->ls);
+  take_taps(desc, &t->ls);
   return INTSGD_OK;
 }
 
@@ -396,23 +408,25 @@ intsgd_status step_fused_impl(const intsgd_desc* desc, const float* const* grads
                               const float* alpha, double eta, float* x, double* norm_sq_out,
                               uint64_t* sat_count, void* workspace, size_t workspace_bytes,
                               void* hip_stream, double* r, float* alpha_out, double beta,
-                              double eps, const Momentum* mom = nullptr) {
+                              double eps, double eta_next, const Momentum* mom = nullptr) {
   INTSGD_TRY(validate_desc(desc));
   INTSGD_TRY(validate_worker_ptrs((const void* const*)grads, desc->n));
   INTSGD_TRY(validate_vec(x));
   if (alpha == nullptr || norm_sq_out == nullptr || sat_count == nullptr) return INTSGD_EINVAL;
   INTSGD_TRY(validate_rule(beta, eps, eta));
+  if (r != nullptr) INTSGD_TRY(validate_rule(beta, eps, eta_next));
   INTSGD_TRY(validate_momentum(mom));
   INTSGD_TRY(validate_workspace(desc, workspace, workspace_bytes));
   Tiling t;
   INTSGD_TRY(make_tiling(desc, hip_stream, &t));
-  WorkerPtrs g;
-  fill_ptrs(&g, (const void* const*)grads, desc->n);
-  Finish fin = make_finish(desc, t, workspace, norm_sq_out, sat_count);
-  if (r != nullptr) fin.rule = AlphaRule{r, alpha_out, t.offsets_dev, beta, eps, eta};
   PhasedShape ps{0};
   bool phased = false;
   INTSGD_TRY(two_phase_shape(desc, &ps, &phased));
+  WorkerPtrs g;
+  fill_ptrs(&g, (const void* const*)grads, desc->n);
+  Finish fin = make_finish(desc, t, workspace, norm_sq_out, sat_count);
+  // Algorithm 1's scaling-factor line pairs alpha_{k+1} with eta_{k+1}
+  if (r != nullptr) fin.rule = AlphaRule{r, alpha_out, t.offsets_dev, beta, eps, eta_next};
   if (phased)
     return done(launch_step_fused_phased(ps, t.ls, desc->d, desc->n, round_spec(desc), g, alpha, eta,
                                          x, mom, fin));
@@ -428,13 +442,6 @@ size_t intsgd_workspace_bytes(const intsgd_desc* desc) {
   return workspace_layout(desc).total;
 }
 
-intsgd_status intsgd_tap_next_launch(void* start_event, void* stop_event) {
-  if ((start_event == nullptr) != (stop_event == nullptr)) return INTSGD_EINVAL;
-  t_tap_start = static_cast<hipEvent_t>(start_event);
-  t_tap_stop = static_cast<hipEvent_t>(stop_event);
-  return INTSGD_OK;
-}
-
 intsgd_status intsgd_prepare(const intsgd_desc* desc) {
   INTSGD_TRY(validate_desc(desc));
   if (desc->num_blocks == 1) return INTSGD_OK;
@@ -442,7 +449,7 @@ intsgd_status intsgd_prepare(const intsgd_desc* desc) {
   const uint32_t sweep_tile = effective_tuning(desc).tile_coords;
   INTSGD_TRY(get_plan(desc, sweep_tile, &plan));
   // the compress kernel picks its own tile unless the tuning fixes one
-  const uint32_t other = current_tuning().tile_coords == 0 ? compress_tile(desc) : sweep_tile;
+  const uint32_t other = requested_tuning(desc).tile_coords == 0 ? compress_tile(desc) : sweep_tile;
   return other == sweep_tile ? INTSGD_OK : get_plan(desc, other, &plan);
 }
 
@@ -470,7 +477,7 @@ intsgd_status intsgd_compress(const intsgd_desc* desc, const float* const* grads
   const WorkspaceLayout w = workspace_layout(desc);
   // one read and one write stream per workgroup: a copy-like kernel, which wants every
   // wavefront slot filled (80 % of peak against 62 % under the sweeps' residency cap)
-  if (current_tuning().workgroups_per_cu == 0) t.ls.lds_reserve = 0;
+  if (requested_tuning(desc).workgroups_per_cu == 0) t.ls.lds_reserve = 0;
   return done(launch_compress(t.tm, t.ls, desc->n, desc->wire, round_spec(desc), g, alpha, q,
                               ws_at<uint64_t>(workspace, w.rows_off), sat_count));
 }
@@ -489,13 +496,13 @@ intsgd_status intsgd_int_sum(const intsgd_desc* desc, const void* const* q, int3
     PhasedShape ps{0};
     INTSGD_TRY(compute_units(&ps.grid));
     LaunchShape pls{ps.grid, 0, static_cast<hipStream_t>(hip_stream), nullptr, nullptr};
-    take_taps(&pls);
+    take_taps(desc, &pls);
     return done(launch_int_sum_phased(ps, pls, desc->d, desc->n, desc->wire, qp, sum_out));
   }
   // one workgroup per 512 quads (at least one, for the d mod 4 coordinates of a tiny vector)
   const uint64_t want = tiles_of((desc->d >> 2) + 1, INTSGD_THREADS_PER_WORKGROUP);
   LaunchShape ls{(uint32_t)want, 0, static_cast<hipStream_t>(hip_stream), nullptr, nullptr};
-  take_taps(&ls);
+  take_taps(desc, &ls);
   return done(launch_int_sum(desc->d, ls, desc->n, desc->wire, qp, sum_out));
 }
 
@@ -630,13 +637,14 @@ intsgd_status intsgd_decode_update_momentum(const intsgd_desc* desc, const int32
 }
 
 intsgd_status intsgd_step_momentum(const intsgd_desc* desc, const float* const* grads,
-                                   float* alpha, double eta, double mu, double weight_decay,
-                                   float* x, float* m, double* r, double beta, double eps,
-                                   double* norm_sq_out, uint64_t* sat_count, void* workspace,
-                                   size_t workspace_bytes, void* hip_stream) {
+                                   float* alpha, double eta, double eta_next, double mu,
+                                   double weight_decay, float* x, float* m, double* r, double beta,
+                                   double eps, double* norm_sq_out, uint64_t* sat_count,
+                                   void* workspace, size_t workspace_bytes, void* hip_stream) {
   const Momentum mom{m, mu, weight_decay};
   return step_fused_impl(desc, grads, alpha, eta, x, norm_sq_out, sat_count, workspace,
-                         workspace_bytes, hip_stream, r, alpha, r ? beta : 0.0, r ? eps : 0.0, &mom);
+                         workspace_bytes, hip_stream, r, alpha, r ? beta : 0.0, r ? eps : 0.0,
+                         r ? eta_next : eta, &mom);
 }
 
 intsgd_status intsgd_step_fused(const intsgd_desc* desc, const float* const* grads,
@@ -644,24 +652,24 @@ intsgd_status intsgd_step_fused(const intsgd_desc* desc, const float* const* gra
                                 uint64_t* sat_count, void* workspace, size_t workspace_bytes,
                                 void* hip_stream) {
   return step_fused_impl(desc, grads, alpha, eta, x, norm_sq_out, sat_count, workspace,
-                         workspace_bytes, hip_stream, nullptr, nullptr, 0.0, 0.0);
+                         workspace_bytes, hip_stream, nullptr, nullptr, 0.0, 0.0, eta);
 }
 
 intsgd_status intsgd_step_fused_next_alpha(const intsgd_desc* desc, const float* const* grads,
-                                           float* alpha, double eta, float* x, double* r,
-                                           double beta, double eps, double* norm_sq_out,
+                                           float* alpha, double eta, double eta_next, float* x,
+                                           double* r, double beta, double eps, double* norm_sq_out,
                                            uint64_t* sat_count, void* workspace,
                                            size_t workspace_bytes, void* hip_stream) {
   if (r == nullptr) return INTSGD_EINVAL;
   return step_fused_impl(desc, grads, alpha, eta, x, norm_sq_out, sat_count, workspace,
-                         workspace_bytes, hip_stream, r, alpha, beta, eps);
+                         workspace_bytes, hip_stream, r, alpha, beta, eps, eta_next);
 }
 
 intsgd_status intsgd_diana_step(const intsgd_desc* desc, const float* const* grads,
-                                float* const* h_local, float* alpha, double eta, float* x,
-                                float* h, double* r, double beta, double eps, double* norm_sq_out,
-                                uint64_t* sat_count, void* workspace, size_t workspace_bytes,
-                                void* hip_stream) {
+                                float* const* h_local, float* alpha, double eta, double eta_next,
+                                float* x, float* h, double* r, double beta, double eps,
+                                double* norm_sq_out, uint64_t* sat_count, void* workspace,
+                                size_t workspace_bytes, void* hip_stream) {
   INTSGD_TRY(validate_desc(desc));
   INTSGD_TRY(validate_worker_ptrs((const void* const*)grads, desc->n));
   INTSGD_TRY(validate_worker_ptrs((const void* const*)h_local, desc->n));
@@ -669,6 +677,7 @@ intsgd_status intsgd_diana_step(const intsgd_desc* desc, const float* const* gra
   INTSGD_TRY(validate_vec(h));
   if (alpha == nullptr || norm_sq_out == nullptr || sat_count == nullptr) return INTSGD_EINVAL;
   INTSGD_TRY(validate_rule(r ? beta : 0.0, r ? eps : 0.0, eta));
+  if (r != nullptr) INTSGD_TRY(validate_rule(beta, eps, eta_next));
   INTSGD_TRY(validate_workspace(desc, workspace, workspace_bytes));
   Tiling t;
   INTSGD_TRY(make_tiling(desc, hip_stream, &t));
@@ -678,7 +687,7 @@ intsgd_status intsgd_diana_step(const intsgd_desc* desc, const float* const* gra
   std::memset(&hl, 0, sizeof(hl));
   for (uint32_t i = 0; i < desc->n; ++i) hl.p[i] = h_local[i];
   Finish fin = make_finish(desc, t, workspace, norm_sq_out, sat_count);
-  if (r != nullptr) fin.rule = AlphaRule{r, alpha, t.offsets_dev, beta, eps, eta};
+  if (r != nullptr) fin.rule = AlphaRule{r, alpha, t.offsets_dev, beta, eps, eta_next};
   return done(launch_diana_step(t.tm, t.ls, desc->n, round_spec(desc), g, hl, alpha, eta, x, h, fin));
 }
 
@@ -699,29 +708,12 @@ intsgd_status intsgd_heuristic_alpha(const intsgd_desc* desc, const float* const
                                      t.tile_prefix, desc->num_blocks, alpha_out));
 }
 
-intsgd_status intsgd_set_tuning(const intsgd_tuning* tuning) {
-  if (tuning == nullptr) return INTSGD_EINVAL;
-  const uint32_t tile = tuning->tile_coords, grid = tuning->max_workgroups,
-                 wgs = tuning->workgroups_per_cu;
-  if (tile != 0 && (tile < kMinTile || tile > kMaxTile || tile % kMinTile != 0)) return INTSGD_EINVAL;
-  if (grid > kMaxGrid) return INTSGD_EINVAL;
-  if (wgs != 0 && (wgs < 2 || wgs > 8)) return INTSGD_EINVAL;
-  if (tuning->two_phase > 2) return INTSGD_EINVAL;
-  std::lock_guard<std::mutex> lock(g_tuning_mutex);
-  g_tuning = *tuning;
-  return INTSGD_OK;
-}
-
-void intsgd_get_tuning(intsgd_tuning* tuning) {
-  if (tuning) *tuning = current_tuning();
-}
-
 int intsgd_fused_step_form(const intsgd_desc* desc) {
   if (validate_desc(desc) != INTSGD_OK) return 0;
   return use_two_phase(desc, effective_tuning(desc)) ? 2 : 1;
 }
 
-const char* intsgd_status_string(intsgd_status status) {
+const char* intsgd_status_string(int status) {
   switch (status) {
     case INTSGD_OK: return "ok";
     case INTSGD_EINVAL: return "invalid argument";

@@ -129,29 +129,53 @@ def test_pointer_alignment_eta_and_workspace_validation():
     assert lib.intsgd_next_alpha(desc.ref(), None, FAKE, 0.9, 1e-8, 0.1, FAKE, None) == EINVAL
 
 
-def test_tuning_knobs_are_validated():
-    before = P.intsgd_get_tuning()
-    T = binding._CTuning
-    for bad in (T(1000, 0, 0), T(512, 0, 0), T(131072, 0, 0), T(4097, 0, 0), T(0, (1 << 20) + 1, 0),
-                T(0, 0, 1), T(0, 0, 9), T(0, 0, 0, 3)):
-        assert lib.intsgd_set_tuning(C.byref(bad)) == EINVAL
-    assert lib.intsgd_set_tuning(None) == EINVAL
-    assert P.intsgd_get_tuning() == before
-    assert before == (0, 0, 0, 0)                        # everything automatic by default
-    P.intsgd_set_tuning(4096, 100, 4)
-    assert P.intsgd_get_tuning() == (4096, 100, 4, 0)
-    P.intsgd_set_tuning(tile_coords=1024)                # zero fields go back to automatic
-    assert P.intsgd_get_tuning() == (1024, 0, 0, 0)
-    P.intsgd_set_tuning(two_phase=2)
-    assert P.intsgd_get_tuning() == (0, 0, 0, 2)
-    P.intsgd_set_tuning(*before)
-    # the workspace size does not depend on the tuning
+def test_launch_options_are_validated_per_descriptor():
+    """Launch options travel with the descriptor of each call; the library keeps none."""
+    ok = P.LaunchOpts(4096, 100, 4, 2)
+    assert call_step_fused(P.Desc(1000, 4, opts=ok), ws=None) == EWORKSPACE     # passed validation
+    for bad in ((1000, 0, 0), (512, 0, 0), (131072, 0, 0), (4097, 0, 0), (0, (1 << 20) + 1, 0),
+                (0, 0, 1), (0, 0, 9), (0, 0, 0, 3)):
+        desc = P.Desc(1000, 4, opts=P.LaunchOpts(*bad))
+        assert call_step_fused(desc) == EINVAL, bad
+        assert P.intsgd_workspace_bytes(desc) == 0
+        assert lib.intsgd_prepare(desc.ref()) == EINVAL
+    # profiling events: both or none
+    for a, b, want in ((FAKE, None, EINVAL), (None, FAKE, EINVAL), (FAKE, FAKE, EWORKSPACE),
+                       (None, None, EWORKSPACE)):
+        desc = P.Desc(1000, 4, opts=P.LaunchOpts(start_event=a, stop_event=b))
+        assert call_step_fused(desc, ws=None) == want
+    # the workspace size does not depend on the options
     desc = P.Desc(10**7, 8)
     a = P.intsgd_workspace_bytes(desc)
-    P.intsgd_set_tuning(1024, 1 << 20, 8)
+    desc.opts = P.LaunchOpts(1024, 1 << 20, 8)
     assert P.intsgd_workspace_bytes(desc) == a
-    P.intsgd_set_tuning(*before)
-    assert P.intsgd_get_tuning() == before
+    desc.opts = None
+    assert P.intsgd_workspace_bytes(desc) == a
+
+
+def test_two_callers_hold_different_options():
+    """No process-wide state: the same query answers per descriptor, in any interleaving."""
+    big = 1 << 22
+    auto = P.Desc(big, 16, rounding=P.ROUND_NEAREST_EVEN)
+    tile = P.Desc(big, 16, rounding=P.ROUND_NEAREST_EVEN, opts=P.LaunchOpts(two_phase=1))
+    phased = P.Desc(big, 8, rounding=P.ROUND_STOCHASTIC, opts=P.LaunchOpts(two_phase=2))
+    for _ in range(3):
+        assert P.intsgd_fused_step_form(auto) == 2
+        assert P.intsgd_fused_step_form(tile) == 1
+        assert P.intsgd_fused_step_form(phased) == 2
+    assert not hasattr(lib, "intsgd_set_tuning") and not hasattr(lib, "intsgd_tap_next_launch")
+
+
+def test_only_the_c_abi_is_exported():
+    """The dynamic symbol table is the extern "C" names of include/intsgd.h and nothing else."""
+    import shutil
+    import subprocess
+    nm = shutil.which("nm")
+    if nm is None:
+        pytest.skip("no nm")
+    out = subprocess.check_output([nm, "-D", "--defined-only", binding.library_path()]).decode()
+    names = sorted(line.split()[-1] for line in out.splitlines() if line.strip())
+    assert names == declared_functions()
 
 
 def test_whole_step_call_validation():
@@ -159,7 +183,8 @@ def test_whole_step_call_validation():
     need = P.intsgd_workspace_bytes(desc)
     f = lib.intsgd_step_fused_next_alpha
     ok_args = lambda **kw: [kw.get("desc", desc.ref()), kw.get("g", ptrs(4)), kw.get("alpha", FAKE),
-                            kw.get("eta", 0.1), kw.get("x", FAKE), kw.get("r", FAKE),
+                            kw.get("eta", 0.1), kw.get("eta_next", 0.05), kw.get("x", FAKE),
+                            kw.get("r", FAKE),
                             kw.get("beta", 0.9), kw.get("eps", 1e-8), kw.get("ns", FAKE),
                             kw.get("sat", FAKE), kw.get("ws", FAKE), kw.get("wb", need), None]
     assert f(*ok_args(r=None)) == EINVAL
@@ -167,6 +192,8 @@ def test_whole_step_call_validation():
     assert f(*ok_args(beta=1.0)) == EINVAL
     assert f(*ok_args(eps=-1.0)) == EINVAL
     assert f(*ok_args(eta=0.0)) == EINVAL
+    for eta_next in (0.0, -1.0, float("nan"), float("inf")):
+        assert f(*ok_args(eta_next=eta_next)) == EINVAL
     assert f(*ok_args(x=FAKE_ODD)) == EALIGN
     assert f(*ok_args(wb=need - 1)) == EWORKSPACE
     assert f(*ok_args(desc=None)) == EINVAL
@@ -176,9 +203,9 @@ def test_momentum_calls_validation():
     desc = P.Desc(1000, 4)
     need = P.intsgd_workspace_bytes(desc)
     f = lib.intsgd_step_momentum
-    args = lambda **kw: [desc.ref(), ptrs(4), FAKE, kw.get("eta", 0.1), kw.get("mu", 0.9),
-                         kw.get("wd", 1e-4), kw.get("x", FAKE), kw.get("m", FAKE), kw.get("r", None),
-                         0.9, 1e-8, FAKE, FAKE, FAKE, need, None]
+    args = lambda **kw: [desc.ref(), ptrs(4), FAKE, kw.get("eta", 0.1), kw.get("eta_next", 0.1),
+                         kw.get("mu", 0.9), kw.get("wd", 1e-4), kw.get("x", FAKE), kw.get("m", FAKE),
+                         kw.get("r", None), 0.9, 1e-8, FAKE, FAKE, FAKE, need, None]
     assert f(*args(m=None)) == EINVAL
     assert f(*args(m=FAKE_ODD)) == EALIGN
     for mu in (-0.1, 1.0, float("nan")):
@@ -186,6 +213,7 @@ def test_momentum_calls_validation():
     for wd in (-1e-4, float("inf"), float("nan")):
         assert f(*args(wd=wd)) == EINVAL
     assert f(*args(eta=0.0)) == EINVAL
+    assert f(*args(r=FAKE, eta_next=0.0)) == EINVAL
     g = lib.intsgd_decode_update_momentum
     assert g(desc.ref(), FAKE, FAKE, 0.1, 0.9, 1e-4, FAKE, None, FAKE, FAKE, need, None) == EINVAL
     assert g(desc.ref(), FAKE, FAKE, 0.1, 1.5, 1e-4, FAKE, FAKE, FAKE, FAKE, need, None) == EINVAL
@@ -197,8 +225,9 @@ def test_diana_call_validation():
     need = P.intsgd_workspace_bytes(desc)
     f = lib.intsgd_diana_step
     args = lambda **kw: [desc.ref(), kw.get("g", ptrs(4)), kw.get("hl", ptrs(4)), kw.get("alpha", FAKE),
-                         kw.get("eta", 0.1), kw.get("x", FAKE), kw.get("h", FAKE), kw.get("r", None),
-                         kw.get("beta", 0.0), 0.0, FAKE, FAKE, FAKE, kw.get("wb", need), None]
+                         kw.get("eta", 0.1), kw.get("eta_next", 0.1), kw.get("x", FAKE),
+                         kw.get("h", FAKE), kw.get("r", None), kw.get("beta", 0.0), 0.0, FAKE, FAKE,
+                         FAKE, kw.get("wb", need), None]
     assert f(*args(hl=None)) == EINVAL
     assert f(*args(hl=ptrs(4, FAKE_ODD))) == EALIGN
     assert f(*args(h=None)) == EINVAL
@@ -206,6 +235,7 @@ def test_diana_call_validation():
     assert f(*args(alpha=None)) == EINVAL
     assert f(*args(eta=-1.0)) == EINVAL
     assert f(*args(r=FAKE, beta=1.0)) == EINVAL
+    assert f(*args(r=FAKE, eta_next=-0.1)) == EINVAL
     assert f(*args(wb=16)) == EWORKSPACE
 
 
@@ -252,25 +282,22 @@ def test_host_alpha_rule_equals_the_oracle():
 
 def test_fused_step_form_policy():
     """Host-only query of which sweep the fused step would launch."""
-    before = P.intsgd_get_tuning()
     big, small = 1 << 22, (1 << 22) - 1
-    try:
-        assert P.intsgd_fused_step_form(P.Desc(big, 16, rounding=P.ROUND_NEAREST_EVEN)) == 2
-        assert P.intsgd_fused_step_form(P.Desc(small, 16, rounding=P.ROUND_NEAREST_EVEN)) == 1
-        assert P.intsgd_fused_step_form(P.Desc(big, 8, rounding=P.ROUND_STOCHASTIC)) == 1
-        blocks = P.Desc(big, 8, rounding=P.ROUND_NEAREST_EVEN, block_offsets=[0, 1000, big])
-        assert P.intsgd_fused_step_form(blocks) == 1
-        for n, form in [(1, 2), (2, 2), (3, 1), (8, 1), (9, 2), (128, 2)]:
-            assert P.intsgd_fused_step_form(P.Desc(big, n, rounding=P.ROUND_NEAREST_EVEN)) == form
-        P.intsgd_set_tuning(two_phase=2)
-        assert P.intsgd_fused_step_form(P.Desc(big, 8, rounding=P.ROUND_STOCHASTIC)) == 2
-        assert P.intsgd_fused_step_form(blocks) == 1
-        assert P.intsgd_fused_step_form(P.Desc(small, 8)) == 1
-        P.intsgd_set_tuning(two_phase=1)
-        assert P.intsgd_fused_step_form(P.Desc(big, 16, rounding=P.ROUND_NEAREST_EVEN)) == 1
-        assert lib.intsgd_fused_step_form(None) == 0
-    finally:
-        P.intsgd_set_tuning(*before)
+    assert P.intsgd_fused_step_form(P.Desc(big, 16, rounding=P.ROUND_NEAREST_EVEN)) == 2
+    assert P.intsgd_fused_step_form(P.Desc(small, 16, rounding=P.ROUND_NEAREST_EVEN)) == 1
+    assert P.intsgd_fused_step_form(P.Desc(big, 8, rounding=P.ROUND_STOCHASTIC)) == 1
+    blocks = P.Desc(big, 8, rounding=P.ROUND_NEAREST_EVEN, block_offsets=[0, 1000, big])
+    assert P.intsgd_fused_step_form(blocks) == 1
+    for n, form in [(1, 2), (2, 2), (3, 1), (8, 1), (9, 2), (128, 2)]:
+        assert P.intsgd_fused_step_form(P.Desc(big, n, rounding=P.ROUND_NEAREST_EVEN)) == form
+    two = P.LaunchOpts(two_phase=2)
+    assert P.intsgd_fused_step_form(P.Desc(big, 8, rounding=P.ROUND_STOCHASTIC, opts=two)) == 2
+    blocks.opts = two
+    assert P.intsgd_fused_step_form(blocks) == 1
+    assert P.intsgd_fused_step_form(P.Desc(small, 8, opts=two)) == 1
+    one = P.LaunchOpts(two_phase=1)
+    assert P.intsgd_fused_step_form(P.Desc(big, 16, rounding=P.ROUND_NEAREST_EVEN, opts=one)) == 1
+    assert lib.intsgd_fused_step_form(None) == 0
 
 
 def test_traffic_table_keys_match_workload_names():
@@ -293,15 +320,7 @@ def test_traffic_table_keys_match_workload_names():
         assert form in ("tile", "two_phase"), k
         assert table[k]["bytes_per_launch"] == table[k]["fetch_bytes"] + table[k]["write_bytes"]
     # the headline workload has the entry bench.py reports by default
-    assert W.config(2).name + "/two_phase" in table
-
-
-def test_tap_needs_both_events_or_none():
-    assert lib.intsgd_tap_next_launch(None, None) == 0
-    assert lib.intsgd_tap_next_launch(FAKE, None) == EINVAL
-    assert lib.intsgd_tap_next_launch(None, FAKE) == EINVAL
-    assert lib.intsgd_tap_next_launch(FAKE, FAKE) == 0
-    assert lib.intsgd_tap_next_launch(None, None) == 0      # clear it again
+    assert W.config(5).name + "/tile" in table
 
 
 def test_header_is_plain_c_and_links(tmp_path):

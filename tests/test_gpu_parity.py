@@ -21,14 +21,9 @@ NORM_RTOL = 1e-5
 ALPHA_RTOL = 1e-5
 
 
-DEFAULT_TUNING = P.intsgd_get_tuning()
-
-
-@pytest.fixture(autouse=True)
-def _default_tuning():
-    P.intsgd_set_tuning(*DEFAULT_TUNING)
-    yield
-    P.intsgd_set_tuning(*DEFAULT_TUNING)
+def opts(tile_coords=0, max_workgroups=0, workgroups_per_cu=0, two_phase=0):
+    """Launch options of a descriptor (the library itself keeps no tuning state)."""
+    return P.LaunchOpts(tile_coords, max_workgroups, workgroups_per_cu, two_phase)
 
 
 def dev(a):
@@ -70,13 +65,12 @@ def make_case(d, n, offsets, seed, alpha_scale=1.0):
 @pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "d%d-n%d" % (s[0], s[1]))
 def test_every_entry_point_matches_oracle(shape, wire, clip, rounding):
     d, n, offsets, tile = shape
-    P.intsgd_set_tuning(tile_coords=tile)
     L = P.default_clip(n) if clip is None else clip
     seed, step, eta = 0x1234ABCD5678EF01, 11, 0.1
     alpha, g, x = make_case(d, n, offsets, seed=d + n + rounding)
     B = alpha.size
     desc = P.Desc(d, n, rounding=rounding, wire=wire, clip=L, seed=seed, step=step,
-                  block_offsets=offsets)
+                  block_offsets=offsets, opts=opts(tile_coords=tile))
     ws = P.new_workspace(desc, DEV)
     off_np = None if offsets is None else np.array(offsets, np.uint64)
 
@@ -166,7 +160,7 @@ def test_results_do_not_depend_on_tuning(tile, grid, wgs):
     ws = P.new_workspace(desc, DEV)
     off_np = np.array(offsets, np.uint64)
     out = oracle.step(list(g), alpha, x, rounding=1, L=1000, eta=0.3, seed=9, step=2, offsets=off_np)
-    P.intsgd_set_tuning(tile, grid, wgs)
+    desc.opts = opts(tile, grid, wgs)
     d_x = dev(x)
     d_ns = torch.zeros(len(offsets) - 1, dtype=torch.float64, device=DEV)
     d_cnt = torch.zeros(n, dtype=torch.int64, device=DEV)
@@ -231,13 +225,13 @@ def test_next_alpha_matches_oracle_and_host_twin():
 
 
 # --------------------------------------------------------------------------- multi-step
-def lockstep_run(w: W.Workload, steps, mode="fused", free_running=True):
+def lockstep_run(w: W.Workload, steps, mode="fused", free_running=True, launch=None):
     """Runs `steps` IntSGD steps on the GPU and replays each one in the oracle WITH THE
     GPU's alpha (integers are only comparable under the same alpha).  Compares x (<= 1
     ulp), clip counts (exact), norm and next alpha (1e-5).  With free_running, a second
     oracle chain that never sees GPU values must also stay within 1e-5 on norm and alpha."""
     desc = P.Desc(w.d, w.n, rounding=w.rounding, wire=w.wire, clip=w.clip, seed=w.philox_seed,
-                  block_offsets=w.block_offsets)
+                  block_offsets=w.block_offsets, opts=launch)
     off_np = None if w.block_offsets is None else np.array(w.block_offsets, np.uint64)
     st = Stepper(desc, eta=w.eta, beta=w.beta, eps=w.eps, device=DEV)
     st.start(w.first_normsq)
@@ -270,6 +264,13 @@ def lockstep_run(w: W.Workload, steps, mode="fused", free_running=True):
                           seed=w.philox_seed, step=k, offsets=off_np)
         assert out["overflow"] == 0
         assert_within_ulp(host(x), out["x_new"], 1, "x at step %d" % k)
+        if sum_buf is not None:                 # the integers themselves, bit for bit
+            assert np.array_equal(host(sum_buf), out["S"]), "aggregate at step %d" % k
+        if q_bufs is not None:
+            for i in range(w.n):
+                q_i, _ = oracle.compress(g_host[i], a_gpu, rounding=w.rounding, L=w.clip,
+                                         seed=w.philox_seed, step=k, worker=i, offsets=off_np)
+                assert np.array_equal(host(q_bufs[i]).astype(np.int32), q_i), (k, i)
         assert u64(st.sat_count).tolist() == out["sat_count"].tolist(), "clip counts at step %d" % k
         assert rel_err(host(st.norm_sq), out["normsq"]) <= NORM_RTOL
         total_sat += int(out["sat_count"].sum())
@@ -338,64 +339,104 @@ def test_config3_full_size_two_steps():
     assert sat > 0
 
 
-def sampled_check(w: W.Workload, steps, slices_per_step=48, slice_len=8192):
-    """Full-size run; the oracle recomputes sampled coordinate windows (tile edges,
-    block edges, the vector's ends, random places) with the GPU's alpha; the norm is
-    checked against a float64 torch reduction of the stored iterates."""
+ORACLE_THREADS = 16          # a one-GPU machine's share of its host
+
+
+def oracle_step_sliced(pool, grads, alpha, x_old, *, j0, threads=ORACLE_THREADS, **kw):
+    """The unchanged oracle on `threads` disjoint coordinate slices of one chunk (coordinates
+    are independent; clip counts and per-block norms add).  -> (x_new, S, sat_count, normsq)."""
+    ln = x_old.size
+    B = np.atleast_1d(alpha).size
+    cuts = sorted(set([(ln * i // threads) & ~3 for i in range(threads)] + [ln]))
+
+    def one(i):
+        lo, hi = cuts[i], cuts[i + 1]
+        return oracle.step([g[lo:hi] for g in grads], alpha, x_old[lo:hi], j0=j0 + lo, **kw)
+
+    outs = list(pool.map(one, range(len(cuts) - 1)))
+    assert all(o["overflow"] == 0 for o in outs)
+    sat = np.sum([o["sat_count"] for o in outs], axis=0, dtype=np.uint64)
+    normsq = np.sum([o["normsq"] for o in outs], axis=0).reshape(B)
+    return (np.concatenate([o["x_new"] for o in outs]), np.concatenate([o["S"] for o in outs]), sat,
+            normsq)
+
+
+def whole_vector_check(w: W.Workload, steps, mode="fused", chunk=1 << 26, launch=None):
+    """Full-size lockstep run in the launch configuration the benchmark times.  After every
+    step the WHOLE vector is streamed device -> host in chunks of `chunk` coordinates and every
+    chunk is replayed by the oracle (threads over disjoint slices of the unchanged oracle) with
+    the GPU's alpha: x within 1 fp32 ulp on every coordinate (two_pass: the integer sums
+    bit-exact as well), clip counts exact, per-block norm against the ORACLE's accumulated sums
+    (1e-5), then r and the next alpha (1e-5)."""
+    from concurrent.futures import ThreadPoolExecutor
     desc = P.Desc(w.d, w.n, rounding=w.rounding, wire=w.wire, clip=w.clip, seed=w.philox_seed,
-                  block_offsets=w.block_offsets)
-    off = [0, w.d] if w.block_offsets is None else w.block_offsets
+                  block_offsets=w.block_offsets, opts=launch)
     off_np = None if w.block_offsets is None else np.array(w.block_offsets, np.uint64)
     st = Stepper(desc, eta=w.eta, beta=w.beta, eps=w.eps, device=DEV)
     st.start(w.first_normsq)
     x = W.make_params(w, DEV)
     buf = torch.empty((w.n, W.row_stride(w.d)), dtype=torch.float32, device=DEV)
-    rng = np.random.default_rng(w.config_id)
-    tile = P.intsgd_get_tuning()[0] or (4096 if w.rounding else 2048)
-    for k in range(1, steps + 1):
-        _, rows = W.make_gradients(w, k, DEV, out=buf)
-        a_gpu = host(st.alpha).copy()
-        x_old = x.clone()
-        st.step_fused(rows, x, k)
-        assert u64(st.sat_count).sum() == 0
-        # norm: property that holds at any size
-        for l in rng.choice(len(off) - 1, min(8, len(off) - 1), replace=False):
-            a, b = off[l], off[l + 1]
-            acc = 0.0
-            for c in range(a, b, 1 << 26):
-                e = min(b, c + (1 << 26))
-                acc += float((x[c:e].double() - x_old[c:e].double()).pow(2).sum())
-            assert rel_err(host(st.norm_sq)[l], acc) <= NORM_RTOL
-        starts = [0, max(0, w.d - slice_len), tile - 5, (w.d // tile) * tile - 3]
-        starts += [o - 7 for o in off[1:-1:max(1, len(off) // 10)]]
-        # where the cache-resident prefix of a large x ends and the streamed part begins
-        # (224 MB of fp32; other code path, same arithmetic)
-        starts += [(224 << 20) // 4 - slice_len // 2]
-        starts += list(rng.integers(0, w.d - slice_len, slices_per_step))
-        for s in starts:
-            s = int(max(0, min(s, w.d - slice_len)))
-            e = s + slice_len
-            out = oracle.step([host(r_[s:e]) for r_ in rows], a_gpu, host(x_old[s:e]),
-                              rounding=w.rounding, L=w.clip, eta=w.eta, seed=w.philox_seed, step=k,
-                              j0=s, offsets=off_np)
-            assert_within_ulp(host(x[s:e]), out["x_new"], 1, "x[%d:%d] at step %d" % (s, e, k))
-            assert out["sat_count"].sum() == 0
-        del x_old
+    sum_buf = torch.empty(w.d, dtype=torch.int32, device=DEV) if mode == "two_pass" else None
+    kw = dict(d=w.d, n=w.n, beta=w.beta, eps=w.eps, eta=w.eta, offsets=off_np)
+    r_lock, ad, _, _ = oracle.next_alpha(w.first_normsq, np.zeros(w.num_blocks), **kw)
+    assert rel_err(host(st.alpha), ad) <= ALPHA_RTOL
+    total_sat = 0
+    with ThreadPoolExecutor(ORACLE_THREADS) as pool:
+        for k in range(1, steps + 1):
+            _, rows = W.make_gradients(w, k, DEV, out=buf)
+            a_gpu = host(st.alpha).copy()
+            x_old = x.clone()
+            if mode == "fused":
+                st.step_fused(rows, x, k)
+            else:
+                st.step_two_pass(rows, x, k, sum_buf)
+            torch.cuda.synchronize()
+            sat = np.zeros(w.n, np.uint64)
+            normsq = np.zeros(w.num_blocks)
+            for c0 in range(0, w.d, chunk):
+                c1 = min(w.d, c0 + chunk)
+                xn, S, sat_c, ns_c = oracle_step_sliced(
+                    pool, [host(r_[c0:c1]) for r_ in rows], a_gpu, host(x_old[c0:c1]), j0=c0,
+                    rounding=w.rounding, L=w.clip, eta=w.eta, seed=w.philox_seed, step=k,
+                    offsets=off_np)
+                assert_within_ulp(host(x[c0:c1]), xn, 1, "x[%d:%d] at step %d" % (c0, c1, k))
+                if sum_buf is not None:
+                    assert np.array_equal(host(sum_buf[c0:c1]), S), "S[%d:%d] at step %d" % (c0, c1, k)
+                sat += sat_c
+                normsq += ns_c
+            del x_old
+            assert u64(st.sat_count).tolist() == sat.tolist(), "clip counts at step %d" % k
+            assert rel_err(host(st.norm_sq), normsq) <= NORM_RTOL, "norm at step %d" % k
+            total_sat += int(sat.sum())
+            r_lock, ad, _, _ = oracle.next_alpha(normsq, r_lock, **kw)
+            assert rel_err(host(st.r), r_lock) <= NORM_RTOL
+            assert rel_err(host(st.alpha), ad) <= ALPHA_RTOL
+    return total_sat
 
 
-def test_config4_full_size_sampled():
-    sampled_check(W.config(4), steps=2)
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("rounding", [P.ROUND_STOCHASTIC, P.ROUND_NEAREST_EVEN],
+                         ids=["stochastic", "nearest-even"])
+def test_config4_full_size_whole_vector(rounding):
+    """Workload 4 (Algorithm 2, 161 blocks, d = 108 M, n = 8), both rounding modes, 2 steps:
+    every coordinate, every block's norm and alpha against the oracle."""
+    whole_vector_check(W.config(4, rounding=rounding), steps=2)
 
 
-def test_config4_full_size_sampled_nearest_even():
-    sampled_check(W.config(4, rounding=0), steps=1)
+@pytest.mark.timeout(600)
+def test_config4_full_size_global_alpha_two_pass_integers():
+    """Workload 4 with one alpha, F1 + F2: the 108 M integer sums bit-exact against the oracle."""
+    whole_vector_check(W.config(4, per_bucket=False), steps=1, mode="two_pass")
 
 
-def test_config5_full_size_sampled():
-    """d = 1.3e9, n = 8: 41.6 GB of gradients + 5.2 GB of parameters resident."""
+@pytest.mark.timeout(1200)
+def test_config5_full_size_whole_vector():
+    """Workload 5 (d = 1.3e9, n = 8: 41.6 GB of gradients + 5.2 GB of parameters resident), one
+    step of the fused sweep: all 1.3e9 coordinates replayed by the oracle in 20 chunks."""
     free, _ = torch.cuda.mem_get_info()
-    assert free > 70e9, "needs the 288 GB MI355X"
-    sampled_check(W.config(5), steps=1, slices_per_step=64)
+    if free < 70e9:
+        pytest.skip("needs 70 GB of free device memory (the 288 GB MI355X)")
+    whole_vector_check(W.config(5), steps=1)
     torch.cuda.empty_cache()
 
 
@@ -408,8 +449,7 @@ def test_momentum_step_on_a_state_beyond_the_last_level_cache(form, n, rounding)
     places against the oracle; the norm against a float64 reduction."""
     d = 60_000_003
     eta, mu, wd, L = 0.1, 0.9, 1e-4, P.default_clip(n)
-    P.intsgd_set_tuning(two_phase=form)
-    desc = P.Desc(d, n, rounding=rounding, clip=L, seed=77, step=5)
+    desc = P.Desc(d, n, rounding=rounding, clip=L, seed=77, step=5, opts=opts(two_phase=form))
     assert P.intsgd_fused_step_form(desc) == form
     gen = torch.Generator(device=DEV)
     gen.manual_seed(99)
@@ -449,8 +489,8 @@ def test_two_pass_and_unfused_chains_on_a_long_vector(form, wire, L):
     the ends, at the prefix boundary and at random places against the oracle."""
     d, n, eta = 60_000_003, 2, 0.1
     L = P.default_clip(n) if L is None else L
-    P.intsgd_set_tuning(two_phase=form)
-    desc = P.Desc(d, n, rounding=P.ROUND_NEAREST_EVEN, wire=wire, clip=L, seed=3, step=2)
+    desc = P.Desc(d, n, rounding=P.ROUND_NEAREST_EVEN, wire=wire, clip=L, seed=3, step=2,
+                  opts=opts(two_phase=form))
     gen = torch.Generator(device=DEV)
     gen.manual_seed(5)
     buf = torch.empty((n, W.row_stride(d)), dtype=torch.float32, device=DEV)
@@ -522,6 +562,69 @@ def test_whole_step_call_equals_step_then_rule():
             assert np.array_equal(a.view(np.uint8), b.view(np.uint8))
 
 
+@pytest.mark.parametrize("form", ["fused", "momentum", "diana"])
+def test_stepsize_schedule_pairs_next_alpha_with_next_eta(form):
+    """Algorithm 1's scaling-factor line defines alpha_k with eta_k, the stepsize of the step
+    that uses it.  Under a warm-up / decay schedule the chained calls therefore take eta_k for
+    the update and eta_{k+1} for the rule; lockstep against oracle.next_alpha(eta=eta_{k+1})."""
+    d, n, steps = 150_001, 4, 6
+    etas = [0.02, 0.05, 0.1, 0.1, 0.05, 0.01, 0.001]          # eta_1 .. eta_7
+    beta, eps = (0.0, 0.0) if form == "diana" else (0.9, 1e-8)
+    w = W.config(2).scaled(d)
+    desc = P.Desc(d, n, rounding=P.ROUND_STOCHASTIC, clip=P.default_clip(n), seed=21)
+    ws = P.new_workspace(desc, DEV)
+    rng = np.random.default_rng(8)
+    x = dev(rng.normal(0, 1, d).astype(F32))
+    m = torch.zeros(d, dtype=torch.float32, device=DEV)
+    h = torch.zeros(d, dtype=torch.float32, device=DEV)
+    hl = [torch.zeros(d, dtype=torch.float32, device=DEV) for _ in range(n)]
+    r0 = np.zeros(1)
+    r_or, ad, af, _ = oracle.next_alpha([1e-3], r0, d=d, n=n, beta=beta, eps=eps, eta=etas[0])
+    d_a, d_r = dev(af), dev(r_or)
+    d_ns = torch.zeros(1, dtype=torch.float64, device=DEV)
+    d_cnt = torch.zeros(n, dtype=torch.int64, device=DEV)
+    for k in range(1, steps + 1):
+        eta, eta_next = etas[k - 1], etas[k]
+        g = rng.normal(0, 1e-2, (n, d)).astype(F32)
+        rows = rows_on_device(g)
+        a_gpu, x_old = host(d_a).copy(), host(x).copy()
+        desc.step = k
+        if form == "fused":
+            P.intsgd_step_fused_next_alpha(desc, rows, d_a, eta, x, d_r, beta, eps, d_ns, d_cnt, ws,
+                                           eta_next=eta_next)
+            out = oracle.step(list(g), a_gpu, x_old, rounding=1, L=P.default_clip(n), eta=eta, seed=21,
+                              step=k)
+        elif form == "momentum":
+            m_old = host(m).copy()
+            P.intsgd_step_momentum(desc, rows, d_a, eta, 0.9, 1e-4, x, m, d_r, beta, eps, d_ns, d_cnt,
+                                   ws, eta_next=eta_next)
+            out = oracle.step_momentum(list(g), a_gpu, x_old, m_old, rounding=1, L=P.default_clip(n),
+                                       eta=eta, mu=0.9, wd=1e-4, seed=21, step=k)
+        else:
+            hl_old, h_old = [host(t).copy() for t in hl], host(h).copy()
+            P.intsgd_diana_step(desc, rows, hl, d_a, eta, x, h, d_r, beta, eps, d_ns, d_cnt, ws,
+                                eta_next=eta_next)
+            out = oracle.diana_step(list(g), hl_old, a_gpu, x_old, h_old, rounding=1,
+                                    L=P.default_clip(n), eta=eta, seed=21, step=k)
+        assert_within_ulp(host(x), out["x_new"], 1, "x at step %d" % k)
+        assert rel_err(host(d_ns), out["normsq"]) <= NORM_RTOL
+        r_or, ad, af, _ = oracle.next_alpha(out["normsq"], r_or, d=d, n=n, beta=beta, eps=eps,
+                                            eta=eta_next)
+        assert rel_err(host(d_r), r_or) <= NORM_RTOL
+        assert rel_err(host(d_a), ad) <= ALPHA_RTOL, "alpha_%d must be built with eta_%d" % (k + 1, k + 1)
+        # and it is NOT what the current step's eta would give (the schedule really moves)
+        if eta != eta_next:
+            _, ad_wrong, _, _ = oracle.next_alpha(out["normsq"], r_lock_prev(r_or, out["normsq"], beta),
+                                                  d=d, n=n, beta=beta, eps=eps, eta=eta)
+            assert rel_err(host(d_a), ad_wrong) > 1e-3
+
+
+def r_lock_prev(r_new, normsq, beta):
+    """r_{k-1} from r_k = beta r_{k-1} + (1 - beta) ||.||^2 (beta = 0: any value does)."""
+    normsq = np.asarray(normsq, dtype=np.float64)
+    return (r_new - (1.0 - beta) * normsq) / beta if beta > 0 else np.zeros_like(r_new)
+
+
 def test_profiling_taps_bracket_the_sweep():
     import bench
     hip = bench.HipEvents()
@@ -533,9 +636,10 @@ def test_profiling_taps_bracket_the_sweep():
     _, rows = W.make_gradients(w, 1, DEV)
     st.step_fused(rows, x, 1)
     a, b = hip.create(), hip.create()
-    P.intsgd_tap_next_launch(a, b)
+    desc.opts = P.LaunchOpts(start_event=a, stop_event=b)
     st.step_fused(rows, x, 2)
-    st.step_fused(rows, x, 3)            # the tap is one-shot: this call must not touch the events
+    desc.opts = None                     # detached: this call must not touch the events
+    st.step_fused(rows, x, 3)
     torch.cuda.synchronize()
     ms = hip.elapsed_ms(a, b)
     assert 0.0 < ms < 50.0
@@ -550,7 +654,8 @@ def test_coordinates_beyond_32_bit_quad_index(rounding):
     and the Philox counter's high word all exceed 32 bits; the oracle recomputes windows at
     both ends.  Randomized rounding runs the tile sweep, nearest-even the two-phase sweep."""
     free, _ = torch.cuda.mem_get_info()
-    assert free > 160e9, "needs the 288 GB MI355X"
+    if free < 160e9:
+        pytest.skip("needs 160 GB of free device memory (the 288 GB MI355X)")
     d, n = (1 << 34) + 4099, 1
     desc = P.Desc(d, n, rounding=rounding, clip=P.default_clip(1), seed=(5 << 32) | 7, step=3)
     assert P.intsgd_fused_step_form(desc) == (1 if rounding == P.ROUND_STOCHASTIC else 2)
@@ -594,7 +699,6 @@ def test_momentum_update_matches_oracle(shape, rounding):
     """intsgd_step_momentum (one sweep) and intsgd_decode_update_momentum (on a given
     aggregate): x and m within 1 fp32 ulp of the oracle, norms within 1e-5, same integers."""
     d, n, offsets, tile = shape
-    P.intsgd_set_tuning(tile_coords=tile)
     alpha, g, x = make_case(d, n, offsets, seed=3 * d + rounding)
     B = alpha.size
     rng = np.random.default_rng(d)
@@ -603,7 +707,8 @@ def test_momentum_update_matches_oracle(shape, rounding):
     off_np = None if offsets is None else np.array(offsets, np.uint64)
     out = oracle.step_momentum(list(g), alpha, x, m, rounding=rounding, L=L, eta=eta, mu=mu, wd=wd,
                                seed=seed, step=step, offsets=off_np)
-    desc = P.Desc(d, n, rounding=rounding, clip=L, seed=seed, step=step, block_offsets=offsets)
+    desc = P.Desc(d, n, rounding=rounding, clip=L, seed=seed, step=step, block_offsets=offsets,
+                  opts=opts(tile_coords=tile))
     ws = P.new_workspace(desc, DEV)
     rows = rows_on_device(g)
     d_x, d_m, d_a = dev(x), dev(m), dev(alpha)
@@ -658,7 +763,6 @@ def test_diana_step_matches_oracle(shape, rounding):
     """Algorithm 3 in one sweep: integers via the clip counts and the shifts (bit-exact
     messages imply h_i within 1 ulp), x, h, h_i within 1 fp32 ulp, norm within 1e-5."""
     d, n, offsets, tile = shape
-    P.intsgd_set_tuning(tile_coords=tile)
     alpha, g, x = make_case(d, n, offsets, seed=7 * d + rounding)
     B = alpha.size
     rng = np.random.default_rng(d + 1)
@@ -668,7 +772,8 @@ def test_diana_step_matches_oracle(shape, rounding):
     off_np = None if offsets is None else np.array(offsets, np.uint64)
     out = oracle.diana_step(list(g), list(hl), alpha, x, h, rounding=rounding, L=L, eta=eta,
                             seed=seed, step=step, offsets=off_np)
-    desc = P.Desc(d, n, rounding=rounding, clip=L, seed=seed, step=step, block_offsets=offsets)
+    desc = P.Desc(d, n, rounding=rounding, clip=L, seed=seed, step=step, block_offsets=offsets,
+                  opts=opts(tile_coords=tile))
     ws = P.new_workspace(desc, DEV)
     d_g, d_hl = rows_on_device(g), rows_on_device(hl)
     d_x, d_h, d_a = dev(x), dev(h), dev(alpha)
@@ -728,7 +833,6 @@ def test_heuristic_alpha_matches_oracle(shape, nb):
     (maximum and power-of-two arithmetic are exact), incl. non-finite entries, an all-zero
     block, denormal and power-of-two maxima; then a step with that alpha still matches."""
     d, n, offsets, tile = shape
-    P.intsgd_set_tuning(tile_coords=tile)
     rng = np.random.default_rng(d * nb)
     g = rng.normal(0, 1e-3, (n, d)).astype(F32)
     g[rng.integers(0, n), rng.integers(0, d)] = np.inf
@@ -745,7 +849,7 @@ def test_heuristic_alpha_matches_oracle(shape, nb):
         oracle.max_abs(g[i], offsets=off_np, B=B, out=m)
     _, want = oracle.heuristic_alpha(m, n=n, nb=nb)
     desc = P.Desc(d, n, rounding=P.ROUND_STOCHASTIC, clip=min(P.default_clip(n), 2**nb - 1), seed=4,
-                  step=1, block_offsets=offsets)
+                  step=1, block_offsets=offsets, opts=opts(tile_coords=tile))
     ws = P.new_workspace(desc, DEV)
     rows = rows_on_device(g)
     d_a = torch.zeros(B, dtype=torch.float32, device=DEV)
@@ -875,7 +979,7 @@ def test_two_phase_sweep_matches_oracle_and_tile_sweep(n, L, rounding):
     rows = rows_on_device(g)
     res = {}
     for form in (2, 1):
-        P.intsgd_set_tuning(two_phase=form)
+        desc.opts = opts(two_phase=form)
         d_x, d_a = dev(x), dev(alpha)
         d_ns = torch.zeros(1, dtype=torch.float64, device=DEV)
         d_cnt = torch.zeros(n, dtype=torch.int64, device=DEV)
@@ -896,7 +1000,7 @@ def test_two_phase_sweep_matches_oracle_and_tile_sweep(n, L, rounding):
         wdesc = P.Desc(d, n, rounding=rounding, wire=wire, clip=L, seed=5, step=3)
         qdt = torch.int8 if wire == P.WIRE_INT8 else torch.int32
         for form in (2, 1):
-            P.intsgd_set_tuning(two_phase=form)
+            wdesc.opts = opts(two_phase=form)
             qs = [torch.full((d,), -99, dtype=qdt, device=DEV) for _ in range(n)]
             d_a = dev(alpha)
             d_cnt = torch.zeros(n, dtype=torch.int64, device=DEV)
@@ -922,10 +1026,9 @@ def test_two_phase_sweep_momentum_form(rounding):
     eta, mu, wd, L = 0.1, 0.9, 1e-4, P.default_clip(n)
     out = oracle.step_momentum(list(g), alpha, x, m, rounding=rounding, L=L, eta=eta, mu=mu, wd=wd,
                                seed=9, step=2)
-    desc = P.Desc(d, n, rounding=rounding, clip=L, seed=9, step=2)
+    desc = P.Desc(d, n, rounding=rounding, clip=L, seed=9, step=2, opts=opts(two_phase=2))
     ws = P.new_workspace(desc, DEV)
     rows = rows_on_device(g)
-    P.intsgd_set_tuning(two_phase=2)
     d_x, d_m, d_a = dev(x), dev(m), dev(alpha)
     d_ns = torch.zeros(1, dtype=torch.float64, device=DEV)
     d_cnt = torch.zeros(n, dtype=torch.int64, device=DEV)
@@ -938,13 +1041,11 @@ def test_two_phase_sweep_momentum_form(rounding):
 
 def test_two_phase_sweep_config2_full_size():
     """Workload 2 at full size: two rounds, the second one partial."""
-    P.intsgd_set_tuning(two_phase=2)
-    lockstep_run(W.config(2), steps=2, free_running=False)
+    lockstep_run(W.config(2), steps=2, free_running=False, launch=opts(two_phase=2))
 
 
 def test_two_phase_sweep_config3_full_size_randomized():
-    P.intsgd_set_tuning(two_phase=2)
-    sat = lockstep_run(W.config(3), steps=1, free_running=False)
+    sat = lockstep_run(W.config(3), steps=1, free_running=False, launch=opts(two_phase=2))
     assert sat > 0
 
 
@@ -954,7 +1055,6 @@ def test_two_phase_sweep_with_infinite_alpha(rounding):
     partial: every real worker-coordinate is a clip event (0 * Inf = NaN included) and the
     lanes past the end of the vector, which read zeros, are not."""
     d, n = PHASED_D, 3
-    P.intsgd_set_tuning(two_phase=2)
     rng = np.random.default_rng(5)
     g = rng.normal(0, 1, (n, d)).astype(F32)
     g[:, ::7] = 0.0
@@ -962,7 +1062,7 @@ def test_two_phase_sweep_with_infinite_alpha(rounding):
     a_inf = np.array([np.inf], F32)
     out = oracle.step(list(g), a_inf, x, rounding=rounding, L=100, eta=0.1, seed=1, step=1)
     assert out["sat_count"].tolist() == [d] * n
-    desc = P.Desc(d, n, rounding=rounding, clip=100, seed=1, step=1)
+    desc = P.Desc(d, n, rounding=rounding, clip=100, seed=1, step=1, opts=opts(two_phase=2))
     assert P.intsgd_fused_step_form(desc) == 2
     ws = P.new_workspace(desc, DEV)
     rows = rows_on_device(g)
@@ -987,7 +1087,6 @@ def test_workspace_needs_no_initialisation(form, fill):
     self-describing.  Three calls in a row on the same workspace, with and without clips,
     so that each call also starts from what the previous one left."""
     d, n = PHASED_D, 4
-    P.intsgd_set_tuning(two_phase=form)
     desc0 = P.Desc(d, n, clip=P.default_clip(n))
     ws = P.new_workspace(desc0, DEV)
     if fill == "ones":
@@ -1002,7 +1101,7 @@ def test_workspace_needs_no_initialisation(form, fill):
     rows = rows_on_device(g)
     for call, L in enumerate([P.default_clip(n), 3, P.default_clip(n)]):
         out = oracle.step(list(g), alpha, x, rounding=0, L=L, eta=0.1, seed=1, step=call)
-        desc = P.Desc(d, n, clip=L, seed=1, step=call)
+        desc = P.Desc(d, n, clip=L, seed=1, step=call, opts=opts(two_phase=form))
         d_x, d_a = dev(x), dev(alpha)
         d_ns = torch.full((1,), -1.0, dtype=torch.float64, device=DEV)
         d_cnt = torch.full((n,), -1, dtype=torch.int64, device=DEV)
@@ -1017,10 +1116,9 @@ def test_workspace_needs_no_initialisation(form, fill):
 def test_two_phase_needs_one_block_and_enough_coordinates():
     """Forced on, the library still takes the tile sweep where the two-phase one does not
     apply (several blocks, short vectors); results are the oracle's either way."""
-    P.intsgd_set_tuning(two_phase=2)
     w = W.config(4).scaled(scaled_blocks(0)[-1], block_offsets=scaled_blocks(0))
-    lockstep_run(w, steps=2)
-    lockstep_run(W.config(2).scaled(100_003), steps=2)
+    lockstep_run(w, steps=2, launch=opts(two_phase=2))
+    lockstep_run(W.config(2).scaled(100_003), steps=2, launch=opts(two_phase=2))
 
 
 # --------------------------------------------------------------------------- random shapes
@@ -1050,7 +1148,7 @@ def test_random_shapes_partitions_and_tunings(seed):
     tile = int(rng.choice([0, 1024, 2048, 4096, 8192]))
     grid = int(rng.choice([0, 1, 3, 64]))
     wgs = int(rng.choice([0, 2, 4, 8]))
-    P.intsgd_set_tuning(tile, grid, wgs)
+    launch = opts(tile, grid, wgs)
     alpha, g, x = make_case(d, n, offsets, seed=seed)
     B = alpha.size
     off_np = None if offsets is None else np.array(offsets, np.uint64)
@@ -1058,7 +1156,7 @@ def test_random_shapes_partitions_and_tunings(seed):
     out = oracle.step(list(g), alpha, x, rounding=rounding, L=L, eta=eta, seed=pseed, step=step,
                       offsets=off_np)
     desc = P.Desc(d, n, rounding=rounding, wire=wire, clip=L, seed=pseed, step=step,
-                  block_offsets=offsets)
+                  block_offsets=offsets, opts=launch)
     ws = P.new_workspace(desc, DEV)
     rows = rows_on_device(g)
     d_a = dev(alpha)
@@ -1100,14 +1198,15 @@ def test_random_shapes_momentum_and_diana(seed):
     offsets = None if (d < 8 or rng.random() < 0.35) else _random_partition(rng, d)
     rounding = int(rng.integers(0, 2))
     L = int(rng.choice([1, 1000, P.default_clip(n)]))
-    P.intsgd_set_tuning(int(rng.choice([0, 1024, 4096])), int(rng.choice([0, 2, 64])),
-                        int(rng.choice([0, 2, 8])))
+    launch = opts(int(rng.choice([0, 1024, 4096])), int(rng.choice([0, 2, 64])),
+                  int(rng.choice([0, 2, 8])))
     alpha, g, x = make_case(d, n, offsets, seed=77 + seed)
     B = alpha.size
     off_np = None if offsets is None else np.array(offsets, np.uint64)
     eta, mu, wd, pseed, step = 0.05, 0.9, 1e-4, 31 + seed, 3 + seed
     m = rng.normal(0, 0.01, d).astype(F32)
-    desc = P.Desc(d, n, rounding=rounding, clip=L, seed=pseed, step=step, block_offsets=offsets)
+    desc = P.Desc(d, n, rounding=rounding, clip=L, seed=pseed, step=step, block_offsets=offsets,
+                  opts=launch)
     ws = P.new_workspace(desc, DEV)
     rows = rows_on_device(g)
     # momentum form
@@ -1207,7 +1306,7 @@ def test_random_long_shapes_two_phase_forms_equal_tile_forms(case):
     ws = P.new_workspace(desc, DEV)
     res = {}
     for form in (1, 2):
-        P.intsgd_set_tuning(two_phase=form)
+        desc.opts = opts(two_phase=form)
         x, m = x0.clone(), m0.clone()
         ns = torch.zeros(1, dtype=torch.float64, device=DEV)
         cnt = torch.zeros(n, dtype=torch.int64, device=DEV)
