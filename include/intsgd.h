@@ -59,7 +59,9 @@ typedef enum {
   INTSGD_EALIGN = -2,     /* a vector pointer is not 16-byte aligned */
   INTSGD_ERANGE = -3,     /* clip bound or worker count outside what the wire / int32 sum can hold */
   INTSGD_EHIP = -4,       /* a HIP runtime call failed (see intsgd_last_hip_error) */
-  INTSGD_EWORKSPACE = -5  /* workspace missing, misaligned or smaller than intsgd_workspace_bytes */
+  INTSGD_EWORKSPACE = -5, /* workspace missing, misaligned or smaller than intsgd_workspace_bytes */
+  INTSGD_ENOPLAN = -6     /* a call that must not allocate met a partition (num_blocks > 1) whose
+                             tile table intsgd_prepare has not built on this device */
 } intsgd_status;
 
 typedef enum {
@@ -251,6 +253,31 @@ INTSGD_API intsgd_status intsgd_step_fused_next_alpha(const intsgd_desc* desc,
                                                       double* norm_sq_out, uint64_t* sat_count,
                                                       void* workspace, size_t workspace_bytes,
                                                       void* hip_stream);
+
+/*
+ * For callers that cannot allocate device memory or pass a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): intsgd_step_fused_next_alpha
+ * with its scratch in a static device array of INTSGD_STATIC_SCRATCH_BYTES that every GPU
+ * running the library holds until the process ends.  Same arguments (minus the workspace)
+ * and the same results.  It calls no hipMalloc / hipFree and no allocating routine.
+ *   - The scratch must hold 12 + 8 n bytes per work tile (4096 coordinates with randomized
+ *     rounding, 2048 with nearest-even, or desc->launch->tile_coords) plus 1 KiB; a larger
+ *     problem is refused with INTSGD_EWORKSPACE and nothing is launched (32 MiB covers
+ *     d = 1.3e9 at n = 8, or d = 2.5e8 at n = 128 nearest-even).
+ *   - num_blocks > 1 needs the partition's tile table, which only intsgd_prepare builds:
+ *     without it the call returns INTSGD_ENOPLAN.  Calling intsgd_prepare(desc) once per
+ *     device beforehand (with the launch options the later calls use) also resolves the
+ *     array's address, after which this call only enqueues kernels.
+ *   - The array keeps the previous call's contents; nothing in it needs clearing (flags and
+ *     the clip hint are tagged per launch).  All calls on one GPU share it: calls that
+ *     overlap in time on one GPU (different streams or threads) race; serialise them.
+ */
+#define INTSGD_STATIC_SCRATCH_BYTES (32u << 20)
+INTSGD_API intsgd_status intsgd_step_fused_static(const intsgd_desc* desc, const float* const* grads,
+                                                  float* alpha, double eta, double eta_next,
+                                                  float* x, double* r, double beta, double eps,
+                                                  double* norm_sq_out, uint64_t* sat_count,
+                                                  void* hip_stream);
 
 /*
  * Momentum / weight-decay form of the update (the optimizer of the paper's experiments,

@@ -16,6 +16,7 @@ __all__ = [
     "intsgd_release", "intsgd_compress", "intsgd_int_sum", "intsgd_decode_update",
     "intsgd_update_norm", "intsgd_next_alpha", "intsgd_next_alpha_host", "intsgd_compress_sum",
     "intsgd_decode_update_norm", "intsgd_step_fused", "intsgd_step_fused_next_alpha",
+    "intsgd_step_fused_static", "STATIC_SCRATCH_BYTES",
     "intsgd_decode_update_momentum", "intsgd_step_momentum", "intsgd_diana_step",
     "intsgd_heuristic_alpha", "intsgd_fused_step_form", "intsgd_status_string", "new_workspace",
     "EXPORTED_SYMBOLS", "LaunchOpts",
@@ -26,6 +27,7 @@ ROUND_STOCHASTIC = 1
 WIRE_INT8 = 8
 WIRE_INT32 = 32
 MAX_WORKERS = 128
+STATIC_SCRATCH_BYTES = 32 << 20
 
 EXPORTED_SYMBOLS = [
     "intsgd_workspace_bytes", "intsgd_prepare", "intsgd_release",
@@ -34,6 +36,7 @@ EXPORTED_SYMBOLS = [
     "intsgd_int_sum", "intsgd_decode_update", "intsgd_update_norm", "intsgd_next_alpha",
     "intsgd_next_alpha_host", "intsgd_compress_sum", "intsgd_decode_update_norm",
     "intsgd_step_fused", "intsgd_fused_step_form", "intsgd_status_string", "intsgd_last_hip_error",
+    "intsgd_step_fused_static",
 ]
 
 
@@ -91,6 +94,8 @@ _lib.intsgd_decode_update_norm.argtypes = [_DP, _P, _P, C.c_double, _P, _P, _P, 
 _lib.intsgd_step_fused.argtypes = [_DP, _PP, _P, C.c_double, _P, _P, _P, _P, C.c_size_t, _P]
 _lib.intsgd_step_fused_next_alpha.argtypes = [_DP, _PP, _P, C.c_double, C.c_double, _P, _P,
                                               C.c_double, C.c_double, _P, _P, _P, C.c_size_t, _P]
+_lib.intsgd_step_fused_static.argtypes = [_DP, _PP, _P, C.c_double, C.c_double, _P, _P, C.c_double,
+                                          C.c_double, _P, _P, _P]
 _lib.intsgd_decode_update_momentum.argtypes = [_DP, _P, _P, C.c_double, C.c_double, C.c_double, _P,
                                                _P, _P, _P, C.c_size_t, _P]
 _lib.intsgd_diana_step.argtypes = [_DP, _PP, _PP, _P, C.c_double, C.c_double, _P, _P, _P, C.c_double,
@@ -107,7 +112,8 @@ _lib.intsgd_last_hip_error.restype = C.c_char_p
 for _name in ("intsgd_prepare", "intsgd_compress", "intsgd_int_sum", "intsgd_decode_update",
               "intsgd_update_norm", "intsgd_next_alpha", "intsgd_next_alpha_host",
               "intsgd_compress_sum", "intsgd_decode_update_norm", "intsgd_step_fused",
-              "intsgd_step_fused_next_alpha", "intsgd_decode_update_momentum", "intsgd_step_momentum", "intsgd_diana_step",
+              "intsgd_step_fused_next_alpha", "intsgd_step_fused_static",
+              "intsgd_decode_update_momentum", "intsgd_step_momentum", "intsgd_diana_step",
               "intsgd_heuristic_alpha"):
     getattr(_lib, _name).restype = C.c_int
 
@@ -369,6 +375,22 @@ def intsgd_step_fused_next_alpha(desc, grads, alpha, eta, x, r, beta, eps, norm_
                                              _ptr(x), _ptr(r), float(beta), float(eps),
                                              _ptr(norm_sq_out), _ptr(sat_count), w, wb,
                                              _stream(stream)), "intsgd_step_fused_next_alpha")
+
+
+def intsgd_step_fused_static(desc, grads, alpha, eta, x, r, beta, eps, norm_sq_out, sat_count,
+                             stream=None, eta_next=None):
+    """intsgd_step_fused_next_alpha on the library's static scratch: no workspace, no allocation."""
+    _need_rows(desc, grads, torch.float32, "grads")
+    _need(alpha, desc.num_blocks, torch.float32, "alpha")
+    _need(x, desc.d, torch.float32, "x")
+    _need(r, desc.num_blocks, torch.float64, "r")
+    _need(norm_sq_out, desc.num_blocks, torch.float64, "norm_sq_out")
+    _need(sat_count, desc.n, torch.int64, "sat_count")
+    _check(_lib.intsgd_step_fused_static(desc.ref(), _ptr_array(grads), _ptr(alpha), float(eta),
+                                         float(eta if eta_next is None else eta_next), _ptr(x),
+                                         _ptr(r), float(beta), float(eps), _ptr(norm_sq_out),
+                                         _ptr(sat_count), _stream(stream)),
+           "intsgd_step_fused_static")
 
 
 def intsgd_decode_update_momentum(desc, sum_, alpha, eta, mu, weight_decay, x, m, norm_sq_out,

@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime_api.h>
 
+#include <algorithm>
 #include <atomic>
 #include <cmath>
 #include <cstdint>
@@ -167,9 +168,9 @@ struct WorkspaceLayout {
   size_t norm_off, mid_off, hint_off, any_off, rows_off, total;
 };
 
-WorkspaceLayout workspace_layout(const intsgd_desc* desc) {
+// Layout for at most max_tiles work tiles (or workgroups, whichever is larger).
+WorkspaceLayout workspace_layout_for(const intsgd_desc* desc, uint64_t max_tiles) {
   WorkspaceLayout w;
-  const uint64_t max_tiles = tiles_of(desc->d, kMinTile) + desc->num_blocks;
   w.norm_off = 0;
   w.mid_off = w.norm_off + round_up((size_t)max_tiles * sizeof(double), kAlign);
   w.hint_off = w.mid_off + round_up((size_t)(max_tiles / 4096 + 2) * sizeof(double), kAlign);
@@ -177,6 +178,11 @@ WorkspaceLayout workspace_layout(const intsgd_desc* desc) {
   w.rows_off = w.any_off + round_up((size_t)max_tiles * sizeof(uint32_t), kAlign);
   w.total = w.rows_off + round_up((size_t)max_tiles * desc->n * sizeof(uint64_t), kAlign);
   return w;
+}
+
+// The caller-owned workspace: sized for the smallest tile, so valid under any launch options.
+WorkspaceLayout workspace_layout(const intsgd_desc* desc) {
+  return workspace_layout_for(desc, tiles_of(desc->d, kMinTile) + desc->num_blocks);
 }
 
 intsgd_status validate_workspace(const intsgd_desc* desc, void* ws, size_t bytes) {
@@ -232,8 +238,9 @@ void free_plan(DevicePlan& p) {
   if (have_cur) (void)hipSetDevice(cur);
 }
 
-// Looks up or builds the device table of a multi-block partition.
-intsgd_status get_plan(const intsgd_desc* desc, uint32_t tile, const DevicePlan** out) {
+// Looks up or (if may_build) builds the device table of a multi-block partition.
+intsgd_status get_plan(const intsgd_desc* desc, uint32_t tile, const DevicePlan** out,
+                       bool may_build = true) {
   int device = 0;
   hipError_t e = hipGetDevice(&device);
   if (e != hipSuccess) return hip_fail(e);
@@ -246,6 +253,7 @@ intsgd_status get_plan(const intsgd_desc* desc, uint32_t tile, const DevicePlan*
       return INTSGD_OK;
     }
   }
+  if (!may_build) return INTSGD_ENOPLAN;
   std::vector<TileEntry> table;
   std::vector<uint32_t> prefix(B + 1);
   for (uint32_t l = 0; l < B; ++l) {
@@ -304,7 +312,7 @@ uint32_t compress_tile(const intsgd_desc* desc) {
 }
 
 intsgd_status make_tiling(const intsgd_desc* desc, void* stream, Tiling* t,
-                          uint32_t automatic_tile = 0) {
+                          uint32_t automatic_tile = 0, bool may_build = true) {
   const Tuning tune = effective_tuning(desc);
   // a kernel may have its own automatic tile; an explicit override still wins
   const uint32_t tile =
@@ -318,7 +326,7 @@ intsgd_status make_tiling(const intsgd_desc* desc, void* stream, Tiling* t,
     t->offsets_dev = nullptr;
   } else {
     const DevicePlan* plan = nullptr;
-    const intsgd_status st = get_plan(desc, tile, &plan);
+    const intsgd_status st = get_plan(desc, tile, &plan, may_build);
     if (st != INTSGD_OK) return st;
     t->tm.num_tiles = plan->num_tiles;
     t->tm.table = plan->table;
@@ -348,8 +356,8 @@ uint32_t next_launch_id() {
 // The end-of-kernel reduction descriptor.  norm_sq_out / sat_count may be null when the
 // kernel does not produce them.
 Finish make_finish(const intsgd_desc* desc, const Tiling& t, void* ws, double* norm_sq_out,
-                   uint64_t* sat_count) {
-  const WorkspaceLayout w = workspace_layout(desc);
+                   uint64_t* sat_count, const WorkspaceLayout* layout = nullptr) {
+  const WorkspaceLayout w = layout ? *layout : workspace_layout(desc);
   Finish f{};
   f.norm_partial = ws_at<double>(ws, w.norm_off);
   f.norm_mid = ws_at<double>(ws, w.mid_off);
@@ -404,11 +412,15 @@ intsgd_status two_phase_shape(const intsgd_desc* desc, PhasedShape* ps, bool* ph
   return INTSGD_OK;
 }
 
+// use_static_scratch: the variant that must not allocate.  Its scratch is the library's
+// static device array (workspace arguments ignored), laid out for the tiling this very call
+// uses, and a partition's tile table is looked up but never built.
 intsgd_status step_fused_impl(const intsgd_desc* desc, const float* const* grads,
                               const float* alpha, double eta, float* x, double* norm_sq_out,
                               uint64_t* sat_count, void* workspace, size_t workspace_bytes,
                               void* hip_stream, double* r, float* alpha_out, double beta,
-                              double eps, double eta_next, const Momentum* mom = nullptr) {
+                              double eps, double eta_next, const Momentum* mom = nullptr,
+                              bool use_static_scratch = false) {
   INTSGD_TRY(validate_desc(desc));
   INTSGD_TRY(validate_worker_ptrs((const void* const*)grads, desc->n));
   INTSGD_TRY(validate_vec(x));
@@ -416,15 +428,22 @@ intsgd_status step_fused_impl(const intsgd_desc* desc, const float* const* grads
   INTSGD_TRY(validate_rule(beta, eps, eta));
   if (r != nullptr) INTSGD_TRY(validate_rule(beta, eps, eta_next));
   INTSGD_TRY(validate_momentum(mom));
-  INTSGD_TRY(validate_workspace(desc, workspace, workspace_bytes));
+  if (!use_static_scratch) INTSGD_TRY(validate_workspace(desc, workspace, workspace_bytes));
   Tiling t;
-  INTSGD_TRY(make_tiling(desc, hip_stream, &t));
+  INTSGD_TRY(make_tiling(desc, hip_stream, &t, 0, /*may_build=*/!use_static_scratch));
   PhasedShape ps{0};
   bool phased = false;
   INTSGD_TRY(two_phase_shape(desc, &ps, &phased));
+  WorkspaceLayout layout = workspace_layout(desc);
+  if (use_static_scratch) {
+    layout = workspace_layout_for(desc, std::max<uint64_t>(t.tm.num_tiles, phased ? ps.grid : 0u));
+    if (layout.total > INTSGD_STATIC_SCRATCH_BYTES) return INTSGD_EWORKSPACE;
+    const hipError_t e = static_scratch(&workspace);
+    if (e != hipSuccess) return hip_fail(e);
+  }
   WorkerPtrs g;
   fill_ptrs(&g, (const void* const*)grads, desc->n);
-  Finish fin = make_finish(desc, t, workspace, norm_sq_out, sat_count);
+  Finish fin = make_finish(desc, t, workspace, norm_sq_out, sat_count, &layout);
   // Algorithm 1's scaling-factor line pairs alpha_{k+1} with eta_{k+1}
   if (r != nullptr) fin.rule = AlphaRule{r, alpha_out, t.offsets_dev, beta, eps, eta_next};
   if (phased)
@@ -444,6 +463,13 @@ size_t intsgd_workspace_bytes(const intsgd_desc* desc) {
 
 intsgd_status intsgd_prepare(const intsgd_desc* desc) {
   INTSGD_TRY(validate_desc(desc));
+  {   // resolve this device's static scratch array now, so that intsgd_step_fused_static only enqueues
+    void* scratch = nullptr;
+    uint32_t cus = 0;
+    const hipError_t e = static_scratch(&scratch);
+    if (e != hipSuccess) return hip_fail(e);
+    INTSGD_TRY(compute_units(&cus));
+  }
   if (desc->num_blocks == 1) return INTSGD_OK;
   const DevicePlan* plan = nullptr;
   const uint32_t sweep_tile = effective_tuning(desc).tile_coords;
@@ -665,6 +691,15 @@ intsgd_status intsgd_step_fused_next_alpha(const intsgd_desc* desc, const float*
                          workspace_bytes, hip_stream, r, alpha, beta, eps, eta_next);
 }
 
+intsgd_status intsgd_step_fused_static(const intsgd_desc* desc, const float* const* grads,
+                                       float* alpha, double eta, double eta_next, float* x,
+                                       double* r, double beta, double eps, double* norm_sq_out,
+                                       uint64_t* sat_count, void* hip_stream) {
+  if (r == nullptr) return INTSGD_EINVAL;
+  return step_fused_impl(desc, grads, alpha, eta, x, norm_sq_out, sat_count, nullptr, 0, hip_stream,
+                         r, alpha, beta, eps, eta_next, nullptr, /*use_static_scratch=*/true);
+}
+
 intsgd_status intsgd_diana_step(const intsgd_desc* desc, const float* const* grads,
                                 float* const* h_local, float* alpha, double eta, double eta_next,
                                 float* x, float* h, double* r, double beta, double eps,
@@ -721,6 +756,7 @@ const char* intsgd_status_string(int status) {
     case INTSGD_ERANGE: return "value out of range";
     case INTSGD_EHIP: return "HIP runtime error";
     case INTSGD_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case INTSGD_ENOPLAN: return "partition not prepared (intsgd_prepare) and this call must not allocate";
   }
   return "unknown status";
 }

@@ -91,6 +91,10 @@ struct Finish {
   AlphaRule rule;
 };
 
+// Address, on the current device, of the library's static device scratch array of
+// INTSGD_STATIC_SCRATCH_BYTES (resolved once per device, then cached).  Allocates nothing.
+hipError_t static_scratch(void** ptr);
+
 // Every launcher only enqueues; the return value is hipGetLastError() after the launch.
 hipError_t launch_compress(const TileMap& tm, const LaunchShape& ls, uint32_t n, int32_t wire,
                            const RoundSpec& rs, const WorkerPtrs& grads, const float* alpha,

@@ -33,9 +33,38 @@
 #include <hip/hip_ext.h>
 #include <stdint.h>
 
+#include <mutex>
+#include <vector>
+
 #include "intsgd_internal.h"
 
+// Scratch memory of intsgd_step_fused_static, the entry point for callers that cannot
+// allocate: norm partials, clip flags and clip-count rows of one call.  Every GPU that loads
+// the library holds its own copy of this array, at its own address, until the process ends.
+// In host code the name below is only a stand-in for the symbol: kernels get the address
+// that hipGetSymbolAddress returns for the current device (static_scratch()).
+static __device__ __align__(256) unsigned char scratch[INTSGD_STATIC_SCRATCH_BYTES];
+
 namespace intsgd {
+
+hipError_t static_scratch(void** ptr) {
+  static std::mutex m;
+  static std::vector<void*> per_device;
+  int device = 0;
+  hipError_t e = hipGetDevice(&device);
+  if (e != hipSuccess) return e;
+  std::lock_guard<std::mutex> lock(m);
+  if ((size_t)device >= per_device.size()) per_device.resize((size_t)device + 1, nullptr);
+  if (per_device[device] == nullptr) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    per_device[device] = p;
+  }
+  *ptr = per_device[device];
+  return hipSuccess;
+}
+
 namespace {
 
 constexpr uint32_t kThreads = INTSGD_THREADS_PER_WORKGROUP;

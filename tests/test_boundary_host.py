@@ -15,7 +15,7 @@ from paper_2102_08374_amd import binding
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 lib = binding._lib
 
-OK, EINVAL, EALIGN, ERANGE, EHIP, EWORKSPACE = 0, -1, -2, -3, -4, -5
+OK, EINVAL, EALIGN, ERANGE, EHIP, EWORKSPACE, ENOPLAN = 0, -1, -2, -3, -4, -5, -6
 FAKE = 0x7F0000001000        # aligned, never dereferenced: validation fails first
 FAKE_ODD = FAKE + 4
 
@@ -199,6 +199,26 @@ def test_whole_step_call_validation():
     assert f(*ok_args(desc=None)) == EINVAL
 
 
+def test_static_scratch_call_validation():
+    """The entry point that must not allocate: same checks, and a problem whose scratch need
+    exceeds the static array is refused before any device call."""
+    f = lib.intsgd_step_fused_static
+    desc = P.Desc(1000, 4, rounding=P.ROUND_STOCHASTIC)
+    args = lambda **kw: [kw.get("desc", desc.ref()), kw.get("g", ptrs(4)), kw.get("alpha", FAKE),
+                         kw.get("eta", 0.1), kw.get("eta_next", 0.1), kw.get("x", FAKE),
+                         kw.get("r", FAKE), kw.get("beta", 0.9), 1e-8, kw.get("ns", FAKE),
+                         kw.get("sat", FAKE), None]
+    assert f(*args(r=None)) == EINVAL
+    assert f(*args(x=FAKE_ODD)) == EALIGN
+    assert f(*args(eta_next=0.0)) == EINVAL
+    assert f(*args(desc=None)) == EINVAL
+    n = 128
+    big = P.Desc(1 << 26, n, rounding=P.ROUND_STOCHASTIC, clip=1000, opts=P.LaunchOpts(tile_coords=1024))
+    assert (12 + 8 * n) * ((1 << 26) // 1024) > P.STATIC_SCRATCH_BYTES
+    a = args(desc=big.ref(), g=ptrs(n))
+    assert f(*a) == EWORKSPACE
+
+
 def test_momentum_calls_validation():
     desc = P.Desc(1000, 4)
     need = P.intsgd_workspace_bytes(desc)
@@ -252,7 +272,7 @@ def test_heuristic_alpha_validation():
 
 
 def test_status_strings():
-    for st in (0, -1, -2, -3, -4, -5):
+    for st in (0, -1, -2, -3, -4, -5, -6):
         assert P.intsgd_status_string(st) not in ("", "unknown status")
     assert P.intsgd_status_string(-99) == "unknown status"
     with pytest.raises(P.IntSGDError):
