@@ -68,6 +68,13 @@ def parse():
                     help="IntDIANA step (Algorithm 3): n local shifts + a global shift in HBM")
     ap.add_argument("--momentum", action="store_true",
                     help="momentum 0.9 / weight decay 1e-4 form of the update (fused mode)")
+    ap.add_argument("--row-skew", type=int, default=0, metavar="BYTES",
+                    help="extra bytes (a multiple of 256) between the workers' gradient rows")
+    ap.add_argument("--per-set", action="store_true",
+                    help="also report the sweep kernel's mean time per resident gradient set")
+    ap.add_argument("--no-placement", action="store_true",
+                    help="leave the written state (x, m, shifts) wherever the allocator puts it "
+                         "instead of probing for an HBM region apart from the gradients")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
                     help="run five plain copies of this size and exit (calibrates FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
@@ -215,30 +222,48 @@ def run_workload(args, hip, cfg, *, cpu_legs):
     desc = P.Desc(w.d, w.n, rounding=w.rounding, wire=w.wire, clip=w.clip, seed=w.philox_seed,
                   block_offsets=w.block_offsets, opts=opts)
     st = Stepper(desc, eta=w.eta, beta=w.beta, eps=w.eps, device=dev)
-    x = W.make_params(w, dev)
 
     grad_bytes = 4 * w.n * w.d
-    free, _ = torch.cuda.mem_get_info()
-    pool = args.pool or max(1, min(steps + args.warmup, 16, int(0.45 * free // grad_bytes)))
-    sets = [W.make_gradients(w, s + 1, dev) for s in range(pool)]
-    sum_buf = torch.empty(w.d, dtype=torch.int32, device=dev) if args.mode != "fused" else None
-    q_bufs = x_old_buf = None
-    if args.mode == "unfused":
-        qdt = torch.int8 if w.wire == 8 else torch.int32
-        qbuf = torch.empty((w.n, W.row_stride(w.d)), dtype=qdt, device=dev)
-        q_bufs = [qbuf[i, :w.d] for i in range(w.n)]
-        x_old_buf = torch.empty_like(x)
-    mom = torch.zeros_like(x) if args.momentum else None
-    if args.diana:
-        hbuf = torch.zeros((w.n, W.row_stride(w.d)), dtype=torch.float32, device=dev)
-        h_local = [hbuf[i, :w.d] for i in range(w.n)]
-        h_global = torch.zeros_like(x)
-    torch.cuda.synchronize()
+    free_mem, total_mem = torch.cuda.mem_get_info()
+    region = total_mem // P.HBM_REGIONS
+    # Resident gradient sets, cycled step by step so that nothing of a small set survives in
+    # the 256 MB memory-side cache.  A set larger than a tenth of the memory cannot be cached
+    # anyway; of those, three are generated and the placement probe below keeps the ONE that
+    # goes best with the chosen place of x (a trainer holds one set of gradient buffers and
+    # refills it step after step).
+    pool = args.pool or max(1, min(steps + args.warmup, 16, int(0.45 * free_mem // grad_bytes)))
+    keep_sets = pool if (args.pool or args.no_placement or 10 * grad_bytes < total_mem) else 1
+    settle_ms = 60.0
+    sets = [W.make_gradients(w, s + 1, dev, skew_bytes=args.row_skew) for s in range(pool)]
     stream = torch.cuda.current_stream().cuda_stream     # every library call below launches here
 
-    def one_step(k, tap=None):
-        """One step; `tap` = a pair of events to attach to the step's (first) sweep kernel."""
-        rows = sets[(k - 1) % pool][1]
+    # The written state of the step: x, the momentum buffer, IntDIANA's shifts, the integer
+    # buffers of the unfused forms.  It goes into one arena whose place in HBM is chosen by
+    # timing (placement.py: written and read-only streams in different regions of the memory).
+    stride = W.row_stride(w.d)
+    fields = [("x", w.d, torch.float32)]
+    if args.momentum:
+        fields.append(("m", w.d, torch.float32))
+    if args.diana:
+        fields += [("h", w.d, torch.float32), ("h_local", w.n * stride, torch.float32)]
+    if args.mode != "fused":
+        fields.append(("sum", w.d, torch.int32))
+    if args.mode == "unfused":
+        fields += [("q", w.n * stride, torch.int8 if w.wire == 8 else torch.int32),
+                   ("x_old", w.d, torch.float32)]
+    offsets, total = {}, 0
+    for name, numel, dt in fields:
+        offsets[name] = total
+        total += (numel * torch.empty(0, dtype=dt).element_size() + 255) // 256 * 256
+
+    def carve(arena):
+        return {name: arena[offsets[name]: offsets[name] + numel * torch.empty(0, dtype=dt).element_size()]
+                .view(dt) for name, numel, dt in fields}
+
+    def run_step(v, rows, k, tap=None):
+        """One step on the written state `v` (views of an arena); `tap` = a pair of events to
+        attach to the step's (first) sweep kernel."""
+        x = v["x"]
         opts.set_events(None, None)
         if args.heuristic:
             nb = 7 if w.wire == 8 else 31
@@ -249,31 +274,94 @@ def run_workload(args, hip, cfg, *, cpu_legs):
         if args.heuristic:
             st.step_fused(rows, x, k, chain_alpha=False)
         elif args.diana:
-            P.intsgd_diana_step(desc, rows, h_local, st.alpha, st.eta, x, h_global, st.r, st.beta,
+            hl = [v["h_local"][i * stride: i * stride + w.d] for i in range(w.n)]
+            P.intsgd_diana_step(desc, rows, hl, st.alpha, st.eta, x, v["h"], st.r, st.beta,
                                 st.eps, st.norm_sq, st.sat_count, st.workspace)
         elif args.momentum:
-            st.step_momentum(rows, x, mom, k, 0.9, 1e-4)  # a1-a8 with the momentum update
+            st.step_momentum(rows, x, v["m"], k, 0.9, 1e-4)   # a1-a8 with the momentum update
         elif args.mode == "fused":
             st.step_fused(rows, x, k)                    # a1-a8, one call
         elif args.mode == "two_pass":                    # F1, F2, a8 (Stepper.step_two_pass)
-            P.intsgd_compress_sum(desc, rows, st.alpha, sum_buf, st.sat_count, st.workspace)
+            P.intsgd_compress_sum(desc, rows, st.alpha, v["sum"], st.sat_count, st.workspace)
             opts.set_events(None, None)
-            P.intsgd_decode_update_norm(desc, sum_buf, st.alpha, st.eta, x, st.norm_sq, st.workspace)
+            P.intsgd_decode_update_norm(desc, v["sum"], st.alpha, st.eta, x, st.norm_sq, st.workspace)
             st.next_alpha()
         else:                                            # five calls + a copy of x (Stepper.step_unfused)
-            P.intsgd_compress(desc, rows, st.alpha, q_bufs, st.sat_count, st.workspace)
+            q = [v["q"][i * stride: i * stride + w.d] for i in range(w.n)]
+            P.intsgd_compress(desc, rows, st.alpha, q, st.sat_count, st.workspace)
             opts.set_events(None, None)
-            P.intsgd_int_sum(desc, q_bufs, sum_buf)
-            x_old_buf.copy_(x)
-            P.intsgd_decode_update(desc, sum_buf, st.alpha, st.eta, x, None)
-            P.intsgd_update_norm(desc, x, x_old_buf, st.norm_sq, st.workspace)
+            P.intsgd_int_sum(desc, q, v["sum"])
+            v["x_old"].copy_(x)
+            P.intsgd_decode_update(desc, v["sum"], st.alpha, st.eta, x, None)
+            P.intsgd_update_norm(desc, x, v["x_old"], st.norm_sq, st.workspace)
             st.next_alpha()
+
+    placement = None
+    # a state that fits the memory-side cache is read and written there: its place in HBM is moot
+    if args.no_placement or total <= (256 << 20):
+        arena = torch.zeros(total, dtype=torch.uint8, device=dev)
+    else:
+        probe_sets = list(range(pool)) if pool <= 3 else sorted({0, pool // 2, pool - 1})
+        probe_warm = 1 if 4 * w.d > (1 << 30) else 4      # a cache-resident x has to settle first
+
+        def probe_ms(candidate):
+            """Time of the step's calls with `candidate` as the written state, per probed set."""
+            v = carve(candidate)
+            st.start(w.first_normsq)
+            a, b = hip.create(), hip.create()
+            per_set = []
+            for s_idx in probe_sets:
+                total_ms = 0.0
+                for timed in [False] * probe_warm + [True, True]:
+                    if timed:
+                        hip.record(a, stream)
+                    run_step(v, sets[s_idx][1], 1)
+                    if timed:
+                        hip.record(b, stream)
+                        torch.cuda.synchronize()
+                        total_ms += hip.elapsed_ms(a, b)
+                per_set.append(total_ms / 2)
+            hip.destroy(a)
+            hip.destroy(b)
+            return per_set
+
+        def best_sets(t):           # the keep_sets probed sets that go best with one candidate
+            return sorted(range(len(t)), key=lambda i: t[i])[:min(keep_sets, len(t))]
+
+        def choose(timings):
+            return min(range(len(timings)),
+                       key=lambda c: sum(timings[c][i] for i in best_sets(timings[c])))
+
+        placement = []
+        arena = P.allocate_apart(total, dev, probe_ms, spread_bytes=region // 2, choose=choose,
+                                 report=placement)
+        arena.zero_()
+        if keep_sets < pool:        # (only when every set was probed)
+            kept = best_sets(placement[choose(placement)])
+            sets = [sets[i] for i in sorted(kept)]
+            pool = len(sets)
+            torch.cuda.empty_cache()
+    state = carve(arena)
+    x = W.make_params(w, dev, out=state["x"])
+    torch.cuda.synchronize()
+
+    def one_step(k, tap=None):
+        run_step(state, sets[(k - 1) % pool][1], k, tap)
 
     st.start(w.first_normsq)
     alpha0 = st.alpha.cpu().numpy().copy()
     x0 = x.clone() if cpu_legs else None
 
+    # Untimed: first enough steps for clocks and caches to settle after the set-up work (at
+    # least settle_ms of them), then the W warm-up steps.
     k = 0
+    t_settle = time.perf_counter()
+    while (time.perf_counter() - t_settle) * 1e3 < settle_ms:
+        for _ in range(4):
+            k += 1
+            one_step(k)
+        torch.cuda.synchronize()
+    settle_steps = k
     for _ in range(args.warmup):
         k += 1
         one_step(k)
@@ -298,6 +386,13 @@ def run_workload(args, hip, cfg, *, cpu_legs):
         event_ms.append(hip.elapsed_ms(e0, e1) / steps)
     opts.set_events(None, None)
 
+    per_set = None
+    if taps and args.per_set:        # step k of the first region used set (settle + warmup + k) % pool
+        raw = [hip.elapsed_ms(a, b) for a, b in taps]
+        per_set = {}
+        for i, ms in enumerate(raw):
+            per_set.setdefault((settle_steps + args.warmup + i) % pool, []).append(ms)
+        per_set = {str(s): sum(v) / len(v) for s, v in sorted(per_set.items())}
     kernel_ms = sorted(hip.elapsed_ms(a, b) for a, b in taps) if taps else None
     for a, b in taps + loop_ev:
         hip.destroy(a)
@@ -355,6 +450,8 @@ def run_workload(args, hip, cfg, *, cpu_legs):
         "kernel_ms_median": median(kernel_ms) if kernel_ms else None,
         "claim": claim,
     }
+    if per_set is not None:
+        roofline["kernel_ms_per_gradient_set"] = per_set
     result = {
         "metric": "fp32 gradient GB/s per IntSGD step (n workers)",
         "value": grad_bytes / (host_ms[0] * 1e-3) / 1e9,
@@ -374,10 +471,16 @@ def run_workload(args, hip, cfg, *, cpu_legs):
             "clip": w.clip, "grad_dist": w.grad_kind,
             "mode": "heuristic-alpha+fused" if args.heuristic else "diana" if args.diana else args.mode + ("+momentum" if args.momentum else ""),
             "gradient_sets": pool,
+            "untimed_settling_steps_before_warmup": settle_steps,
             "launch_options": {"tile_coords": args.tile, "max_workgroups": args.grid,
                                "workgroups_per_cu": args.wgs_per_cu, "two_phase": args.two_phase},
             "alpha_last": alpha_last,
             "clipped_last_step": sat,
+            "state_placement": ("allocator's choice" if placement is None else
+                                {"rule": "written state where the step ran fastest: timed probe over "
+                                         "candidate buffers spread across device memory, one row per "
+                                         "candidate, one column per probed gradient set",
+                                 "candidate_ms": placement}),
         },
         "timing": {
             "regions": len(loop_ev), "steps_per_region": steps,
@@ -411,7 +514,7 @@ def run_workload(args, hip, cfg, *, cpu_legs):
     }
     if "cpu_baseline" in result:
         entry["cpu_baseline_gbs_1_core"] = result["cpu_baseline"]["value"]
-    del sets, x, st
+    del sets, x, st, state, arena
     torch.cuda.empty_cache()
     return result, entry
 

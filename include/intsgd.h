@@ -260,10 +260,11 @@ INTSGD_API intsgd_status intsgd_step_fused_next_alpha(const intsgd_desc* desc,
  * with its scratch in a static device array of INTSGD_STATIC_SCRATCH_BYTES that every GPU
  * running the library holds until the process ends.  Same arguments (minus the workspace)
  * and the same results.  It calls no hipMalloc / hipFree and no allocating routine.
- *   - The scratch must hold 12 + 8 n bytes per work tile (4096 coordinates with randomized
- *     rounding, 2048 with nearest-even, or desc->launch->tile_coords) plus 1 KiB; a larger
- *     problem is refused with INTSGD_EWORKSPACE and nothing is launched (32 MiB covers
- *     d = 1.3e9 at n = 8, or d = 2.5e8 at n = 128 nearest-even).
+ *   - The scratch must hold 12 + 8 n bytes per work tile (2048 coordinates, or
+ *     desc->launch->tile_coords), or per compute unit when the call takes the two-phase
+ *     form, plus 1 KiB; a larger problem is refused with INTSGD_EWORKSPACE and nothing is
+ *     launched.  32 MiB covers d = 9.0e8 at n = 8 (d = 1.3e9 with tile_coords = 4096),
+ *     d = 6.6e7 at n = 128 in the tile form, and any d in the two-phase form.
  *   - num_blocks > 1 needs the partition's tile table, which only intsgd_prepare builds:
  *     without it the call returns INTSGD_ENOPLAN.  Calling intsgd_prepare(desc) once per
  *     device beforehand (with the launch options the later calls use) also resolves the

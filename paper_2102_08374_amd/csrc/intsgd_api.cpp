@@ -4,7 +4,6 @@
 
 #include <hip/hip_runtime_api.h>
 
-#include <algorithm>
 #include <atomic>
 #include <cmath>
 #include <cstdint>
@@ -39,17 +38,17 @@ Tuning requested_tuning(const intsgd_desc* desc) {
   return Tuning{o->tile_coords, o->max_workgroups, o->workgroups_per_cu, o->two_phase};
 }
 
-// Automatic choices of the tile sweeps, measured on MI355X.  Nearest-even rounding is bound by
-// HBM: 8 KB per stream and workgroup, and as few resident workgroups as keep enough loads in
-// flight: two of 512 threads per CU when a thread has two groups of eight worker loads to
+// Automatic choices of the tile sweeps, measured on MI355X: 8 KB per stream and workgroup (one
+// quad per thread) in both rounding modes, and as few resident workgroups as keep enough loads
+// in flight: two of 512 threads per CU when a thread has two groups of eight worker loads to
 // issue (n > 8), four when it has at most one (at n = 8: 82 % of peak against 76 %).
-// Randomized rounding is co-bound by the integer ALU (Philox): 16 KB tiles and the
-// reservation for four, of which the kernel's 70 VGPRs let three be resident (two measured
-// 4 % slower on 8 x 25.6 M; a build squeezed into 64 VGPRs so that four fit, 3-5 % slower).
+// Randomized rounding: the reservation is for four, of which the kernel's 75 VGPRs let three be
+// resident; with its per-coordinate clamp and clip test gone (fast path) it no longer gains
+// from 16 KB tiles (8 KB: 1-2.5 % faster on 8 x 25.6 M, 8 x 108 M and 8 x 1.3 B).
 Tuning effective_tuning(const intsgd_desc* desc) {
   const bool random = desc->rounding == INTSGD_ROUND_STOCHASTIC;
   Tuning t = requested_tuning(desc);
-  if (t.tile_coords == 0) t.tile_coords = random ? 4096 : 2048;
+  if (t.tile_coords == 0) t.tile_coords = 2048;
   if (t.max_workgroups == 0) t.max_workgroups = kMaxGrid;
   if (t.workgroups_per_cu == 0) t.workgroups_per_cu = (random || desc->n <= 8) ? 4 : 2;
   return t;
@@ -206,6 +205,10 @@ RoundSpec round_spec(const intsgd_desc* desc) {
   float thr = (float)bound;
   if ((double)thr < bound) thr = std::nextafterf(thr, INFINITY);
   rs.sat_threshold = thr;
+  // largest fp32 <= L (L >= 1): a scaled value below it in magnitude rounds into [-L, L] either way
+  float lim = (float)desc->clip;
+  if ((double)lim > (double)desc->clip) lim = std::nextafterf(lim, 0.0f);
+  std::memcpy(&rs.fast_limit_bits, &lim, sizeof(lim));
   rs.key0 = (uint32_t)desc->seed;
   rs.key1 = (uint32_t)(desc->seed >> 32);
   rs.step = desc->step;
@@ -436,7 +439,7 @@ intsgd_status step_fused_impl(const intsgd_desc* desc, const float* const* grads
   INTSGD_TRY(two_phase_shape(desc, &ps, &phased));
   WorkspaceLayout layout = workspace_layout(desc);
   if (use_static_scratch) {
-    layout = workspace_layout_for(desc, std::max<uint64_t>(t.tm.num_tiles, phased ? ps.grid : 0u));
+    layout = workspace_layout_for(desc, phased ? ps.grid : t.tm.num_tiles);
     if (layout.total > INTSGD_STATIC_SCRATCH_BYTES) return INTSGD_EWORKSPACE;
     const hipError_t e = static_scratch(&workspace);
     if (e != hipSuccess) return hip_fail(e);

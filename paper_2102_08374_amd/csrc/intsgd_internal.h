@@ -39,6 +39,7 @@ struct RoundSpec {
   int32_t rounding;      // intsgd_rounding
   int32_t clip;          // L
   float sat_threshold;   // smallest fp32 >= L+1: an integer-valued fp32 r is clipped iff !(|r| < it)
+  uint32_t fast_limit_bits;  // bits of the largest fp32 <= L: |t| below it cannot clip whichever way t is rounded
   uint32_t key0, key1;   // lo32(seed), hi32(seed)
   uint32_t step;
 };

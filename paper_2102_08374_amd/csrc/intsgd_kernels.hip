@@ -93,6 +93,10 @@ constexpr int kStreamOut = 18;     // nt + sc1: written through and not kept (ve
 #ifndef INTSGD_X_STORE_POLICY
 #define INTSGD_X_STORE_POLICY kWriteThrough
 #endif
+// 0 = randomized rounding clamps and tests every coordinate (A/B builds only)
+#ifndef INTSGD_RANDOM_FAST_PATH
+#define INTSGD_RANDOM_FAST_PATH 1
+#endif
 
 // ------------------------------------------------------------------ buffer access
 // Raw buffer descriptor over [base, base+bytes): dword 3 = 0x00020000 selects the
@@ -246,6 +250,49 @@ __device__ __forceinline__ int32_t round_random_clip(float t, uint32_t word, con
   return qc;
 }
 
+// The same randomized rounding for values that are known not to clip: floor(t) + [u < p] is
+// ADDED to the running sum S (the compare's carry rides on the add), with no clamp and no
+// clip test.  Valid only while |t| < L (then the result lies in [-L, L]); the caller tracks
+// the range of its t's with a RangeWatch and redoes the quad with round_random_clip if
+// any of them might clip or is not finite.
+__device__ __forceinline__ void round_random_add(float t, uint32_t word, int32_t& S) {
+  const float f = __builtin_floorf(t);
+  const float p = t - f;
+  const float scaled_p = p * 16777216.0f;
+  const float u = (float)(word >> 8);
+  const int32_t q = cvt_i32_saturating(f);
+  // S += q + [u < p 2^24] as compare + add-with-carry (the compiler makes a select and a
+  // three-way add of it, one instruction more per coordinate)
+  asm("v_cmp_gt_f32_e32 vcc, %2, %3\n\tv_addc_co_u32_e32 %0, vcc, %0, %1, vcc"
+      : "+v"(S)
+      : "v"(q), "v"(scaled_p), "v"(u)
+      : "vcc");
+}
+
+// Largest |t| seen, kept as two integer maxima of the raw bit patterns: as signed integers
+// the non-negative floats (and +NaN) order like their values and beat every negative one;
+// as unsigned integers the negative floats (and -NaN) order by magnitude and beat every
+// non-negative one.  Two three-way maxima per four values, and NaN / Inf cannot hide.
+struct RangeWatch {
+  int32_t pos;      // max over raw bits as signed
+  uint32_t neg;     // max over raw bits as unsigned
+};
+__device__ __forceinline__ RangeWatch range_watch_init() { return RangeWatch{INT32_MIN, 0u}; }
+__device__ __forceinline__ void watch(RangeWatch& rw, const vf4& t) {
+  const vi4 b = __builtin_bit_cast(vi4, t);
+  rw.pos = max(max(rw.pos, b.x), b.y);
+  rw.pos = max(max(rw.pos, b.z), b.w);
+  rw.neg = max(max(rw.neg, (uint32_t)b.x), (uint32_t)b.y);
+  rw.neg = max(max(rw.neg, (uint32_t)b.z), (uint32_t)b.w);
+}
+// Lanes whose quad must be redone exactly: some |t| >= the largest fp32 <= L, or not finite.
+constexpr int kIcmpUnsignedGe = 35;
+constexpr int kIcmpSignedGe = 39;
+__device__ __forceinline__ LaneMask out_of_fast_range(const RangeWatch& rw, const RoundSpec& rs) {
+  return __builtin_amdgcn_sicmp(rw.pos, (int32_t)rs.fast_limit_bits, kIcmpSignedGe) |
+         __builtin_amdgcn_uicmp(rw.neg, rs.fast_limit_bits | 0x80000000u, kIcmpUnsignedGe);
+}
+
 template <int ROUND>
 __device__ __forceinline__ int32_t round_clip(float t, uint32_t word, const RoundSpec& rs,
                                               LaneMask& sat) {
@@ -384,6 +431,59 @@ __device__ __forceinline__ void accumulate_workers(const WorkerPtrs& grads, uint
       any |= (s0 | s1) | (s2 | s3);
     }
   }
+}
+
+// Randomized rounding of workers [i0, i0+W) for one lane quad without clamp or clip test
+// (round_random_add); `rw` collects the range of the scaled values.
+template <int W>
+__device__ __forceinline__ void accumulate_workers_fast(const WorkerPtrs& grads, uint32_t i0,
+                                                        uint64_t q0, uint32_t nq, uint32_t ql,
+                                                        float alpha, const RoundSpec& rs, vi4& S,
+                                                        RangeWatch& rw) {
+  vf4 g[W];
+#pragma unroll
+  for (int w = 0; w < W; ++w) {
+    const __amdgpu_buffer_rsrc_t src = make_stream((const vf4*)grads.p[i0 + w] + q0, nq * 16u);
+    g[w] = as_f(load128<INTSGD_GRAD_LOAD_POLICY>(src, ql * 16u));
+  }
+  const uint64_t quad = q0 + ql;
+#pragma unroll
+  for (int w = 0; w < W; ++w) {
+    const vu4 word = philox4x32_10((uint32_t)quad, (uint32_t)(quad >> 32), i0 + w, rs.step, rs.key0, rs.key1);
+    const vf4 t = vf4{alpha * g[w].x, alpha * g[w].y, alpha * g[w].z, alpha * g[w].w};
+    int32_t s0 = S.x, s1 = S.y, s2 = S.z, s3 = S.w;
+    round_random_add(t.x, word.x, s0);
+    round_random_add(t.y, word.y, s1);
+    round_random_add(t.z, word.z, s2);
+    round_random_add(t.w, word.w, s3);
+    S = vi4{s0, s1, s2, s3};
+    watch(rw, t);
+    // one worker after the other: left to itself the scheduler interleaves several workers'
+    // Philox chains, which costs 25 more VGPRs (and two resident wavefronts per SIMD)
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+// The n workers of one lane quad by the fast path; `redo` = lanes whose result is not valid
+// (something may clip or is not finite): the caller then runs aggregate_quad<.., true>.
+__device__ __forceinline__ vi4 aggregate_quad_fast(const WorkerPtrs& grads, uint32_t n, uint64_t q0,
+                                                   uint32_t nq, uint32_t ql, float alpha,
+                                                   const RoundSpec& rs, LaneMask& redo) {
+  vi4 S = vi4{0, 0, 0, 0};
+  RangeWatch rw = range_watch_init();
+  uint32_t i = 0;
+  for (; i + 8 <= n; i += 8) accumulate_workers_fast<8>(grads, i, q0, nq, ql, alpha, rs, S, rw);
+  if (n - i >= 4) {
+    accumulate_workers_fast<4>(grads, i, q0, nq, ql, alpha, rs, S, rw);
+    i += 4;
+  }
+  if (n - i >= 2) {
+    accumulate_workers_fast<2>(grads, i, q0, nq, ql, alpha, rs, S, rw);
+    i += 2;
+  }
+  if (n - i >= 1) accumulate_workers_fast<1>(grads, i, q0, nq, ql, alpha, rs, S, rw);
+  redo = out_of_fast_range(rw, rs);
+  return S;
 }
 
 template <int ROUND, bool COUNT>
@@ -661,8 +761,8 @@ struct AggregateOp {
   uint64_t q0;
   uint32_t nq;
   LaneMask any;                 // lanes of this wavefront that clipped somewhere in the tile body
-  // Randomized rounding counts clip events as it goes: the branch-free form costs it
-  // registers (Philox temporaries across more loads in flight) and with them occupancy.
+  // Randomized rounding takes the fast path (no clamp, no clip test per coordinate) and
+  // redoes, counting as it goes, the rare quad of a wavefront in which something may clip.
   static constexpr bool kCountInline = ROUND == INTSGD_ROUND_STOCHASTIC;
   __amdgpu_buffer_rsrc_t out;   // x (F3) or the aggregate (F1) of this tile body
   __amdgpu_buffer_rsrc_t mom;   // momentum buffer of this tile body
@@ -703,7 +803,17 @@ struct AggregateOp {
     vf4 xv = vf4{0.f, 0.f, 0.f, 0.f}, mv = vf4{0.f, 0.f, 0.f, 0.f};
     if (FUSED) xv = as_f(load128<XL>(out, ql * 16u));
     if (MOMENTUM) mv = as_f(load128<XL>(mom, ql * 16u));
-    const vi4 S = aggregate_quad<ROUND, kCountInline>(a.grads, a.n, q0, nq, ql, alpha, a.rs, lds.sat, any);
+    vi4 S;
+    if (ROUND == INTSGD_ROUND_STOCHASTIC && INTSGD_RANDOM_FAST_PATH) {
+      LaneMask redo;
+      S = aggregate_quad_fast(a.grads, a.n, q0, nq, ql, alpha, a.rs, redo);
+      if (redo != 0ull)     // wave-uniform and rare: the exact path, which also counts per worker
+        S = aggregate_quad<ROUND, true>(a.grads, a.n, q0, nq, ql, alpha, a.rs, lds.sat, any);
+    } else if (ROUND == INTSGD_ROUND_STOCHASTIC) {
+      S = aggregate_quad<ROUND, true>(a.grads, a.n, q0, nq, ql, alpha, a.rs, lds.sat, any);
+    } else {
+      S = aggregate_quad<ROUND, false>(a.grads, a.n, q0, nq, ql, alpha, a.rs, lds.sat, any);
+    }
     if (MOMENTUM) {
       const vf4 xn = momentum_quad(xv, mv, S, rule, acc);
       store128<XS>(mom, ql * 16u, as_u(mv));

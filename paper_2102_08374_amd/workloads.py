@@ -135,9 +135,10 @@ def _generator(w: Workload, step: int, worker: int, device):
     return g
 
 
-def make_params(w: Workload, device) -> torch.Tensor:
-    """x^k ~ iid N(0, 1), fp32."""
-    x = torch.empty(w.d, dtype=torch.float32, device=device)
+def make_params(w: Workload, device, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """x^k ~ iid N(0, 1), fp32 (written into `out`, d floats, if given)."""
+    x = out if out is not None else torch.empty(w.d, dtype=torch.float32, device=device)
+    assert x.shape == (w.d,) and x.dtype == torch.float32
     g = _generator(w, 0, 1 << 20, device)
     for a in range(0, w.d, _CHUNK):
         x[a:a + _CHUNK].normal_(0.0, 1.0, generator=g)
@@ -171,16 +172,18 @@ def fill_gradient(w: Workload, step: int, worker: int, out: torch.Tensor):
     return out
 
 
-def row_stride(d: int) -> int:
+def row_stride(d: int, skew_bytes: int = 0) -> int:
     """Floats between the starts of two workers' gradients in one buffer: d rounded up
     so that every row starts on a 256-byte boundary (each worker would own a separately
-    allocated, aligned gradient buffer)."""
-    return (d + 63) // 64 * 64
+    allocated, aligned gradient buffer), plus an optional skew (a multiple of 256 bytes)."""
+    assert skew_bytes % 256 == 0
+    return (d + 63) // 64 * 64 + skew_bytes // 4
 
 
-def make_gradients(w: Workload, step: int, device, out: Optional[torch.Tensor] = None):
+def make_gradients(w: Workload, step: int, device, out: Optional[torch.Tensor] = None,
+                   skew_bytes: int = 0):
     """-> (buffer [n, row_stride(d)], list of the n row views of d floats)."""
-    stride = row_stride(w.d)
+    stride = row_stride(w.d, skew_bytes)
     buf = out if out is not None else torch.empty((w.n, stride), dtype=torch.float32, device=device)
     assert buf.shape == (w.n, stride)
     rows = [buf[i, :w.d] for i in range(w.n)]
