@@ -333,16 +333,18 @@ struct ReduceLds {
   unsigned long long sat[INTSGD_MAX_WORKERS];
 };
 
-// Sum over the workgroup; the result is valid in thread 0 only.  `slot` must
-// alternate between consecutive calls (double-buffered LDS, one barrier per call).
+// Sum over the workgroup, a two-level tree: DPP / lane reads within each wavefront, the wave
+// sums through LDS, and the same wavefront tree once more over them in the first wavefront
+// (fixed order).  The result is valid in thread 0 only.  `slot` must alternate between
+// consecutive calls (double-buffered LDS, one barrier per call).
 __device__ __forceinline__ double block_sum(double v, ReduceLds& lds, uint32_t slot) {
   const double w = wave_sum(v);
   if ((threadIdx.x & 63u) == 0) lds.red[slot][threadIdx.x >> 6] = w;
   __syncthreads();
   double total = 0.0;
-  if (threadIdx.x == 0) {
+  if (threadIdx.x < 64u) {          // the whole first wavefront: wave_sum needs all 64 lanes
     const uint32_t waves = blockDim.x >> 6;
-    for (uint32_t k = 0; k < waves; ++k) total += lds.red[slot][k];
+    total = wave_sum(threadIdx.x < waves ? lds.red[slot][threadIdx.x] : 0.0);
   }
   return total;
 }
@@ -1083,19 +1085,36 @@ struct DianaOp {
     const uint64_t quad = q0 + ql;
 #pragma unroll
     for (int w = 0; w < W; ++w) {
-      vu4 rw = vu4{0u, 0u, 0u, 0u};
+      vu4 word = vu4{0u, 0u, 0u, 0u};
       if (ROUND == INTSGD_ROUND_STOCHASTIC)
-        rw = philox4x32_10((uint32_t)quad, (uint32_t)(quad >> 32), i0 + w, a.rs.step, a.rs.key0,
-                           a.rs.key1);
-      LaneMask s0, s1, s2, s3;
-      vi4 q;
-      q.x = round_clip<ROUND>(alpha * (g[w].x - hl[w].x), rw.x, a.rs, s0);
-      q.y = round_clip<ROUND>(alpha * (g[w].y - hl[w].y), rw.y, a.rs, s1);
-      q.z = round_clip<ROUND>(alpha * (g[w].z - hl[w].z), rw.z, a.rs, s2);
-      q.w = round_clip<ROUND>(alpha * (g[w].w - hl[w].w), rw.w, a.rs, s3);
-      const uint32_t cnt = count_lanes(s0, s1, s2, s3);
-      if (cnt != 0 && (threadIdx.x & 63u) == 0)
-        atomicAdd(&lds.sat[i0 + w], (unsigned long long)cnt);
+        word = philox4x32_10((uint32_t)quad, (uint32_t)(quad >> 32), i0 + w, a.rs.step, a.rs.key0,
+                             a.rs.key1);
+      const vf4 t = vf4{alpha * (g[w].x - hl[w].x), alpha * (g[w].y - hl[w].y),
+                        alpha * (g[w].z - hl[w].z), alpha * (g[w].w - hl[w].w)};
+      vi4 q = vi4{0, 0, 0, 0};
+      LaneMask redo = ~0ull;
+      if (ROUND == INTSGD_ROUND_STOCHASTIC && INTSGD_RANDOM_FAST_PATH) {
+        // fast path: no clamp, no clip test; redone below if something may clip or is not finite
+        int32_t q0i = 0, q1i = 0, q2i = 0, q3i = 0;
+        round_random_add(t.x, word.x, q0i);
+        round_random_add(t.y, word.y, q1i);
+        round_random_add(t.z, word.z, q2i);
+        round_random_add(t.w, word.w, q3i);
+        q = vi4{q0i, q1i, q2i, q3i};
+        RangeWatch watched = range_watch_init();
+        watch(watched, t);
+        redo = out_of_fast_range(watched, a.rs);
+      }
+      if (redo != 0ull) {         // nearest-even always; randomized: wave-uniform and rare
+        LaneMask s0, s1, s2, s3;
+        q.x = round_clip<ROUND>(t.x, word.x, a.rs, s0);
+        q.y = round_clip<ROUND>(t.y, word.y, a.rs, s1);
+        q.z = round_clip<ROUND>(t.z, word.z, a.rs, s2);
+        q.w = round_clip<ROUND>(t.w, word.w, a.rs, s3);
+        const uint32_t cnt = count_lanes(s0, s1, s2, s3);
+        if (cnt != 0 && (threadIdx.x & 63u) == 0)
+          atomicAdd(&lds.sat[i0 + w], (unsigned long long)cnt);
+      }
       const vf4 hn = vf4{shift_local(hl[w].x, q.x, inv_alpha), shift_local(hl[w].y, q.y, inv_alpha),
                          shift_local(hl[w].z, q.z, inv_alpha), shift_local(hl[w].w, q.w, inv_alpha)};
       store128<kNonTemporal>(hs[w], ql * 16u, as_u(hn));      // n d floats: never cache resident
@@ -1290,14 +1309,30 @@ struct CompressOp {
     if (ROUND == INTSGD_ROUND_STOCHASTIC)
       rw = philox4x32_10((uint32_t)quad, (uint32_t)(quad >> 32), worker, a.rs.step, a.rs.key0,
                          a.rs.key1);
-    LaneMask s0, s1, s2, s3;
-    vi4 v;
-    v.x = round_clip<ROUND>(alpha * gv.x, rw.x, a.rs, s0);
-    v.y = round_clip<ROUND>(alpha * gv.y, rw.y, a.rs, s1);
-    v.z = round_clip<ROUND>(alpha * gv.z, rw.z, a.rs, s2);
-    v.w = round_clip<ROUND>(alpha * gv.w, rw.w, a.rs, s3);
-    const uint32_t cnt = count_lanes(s0, s1, s2, s3);
-    if (cnt != 0 && (threadIdx.x & 63u) == 0) atomicAdd(&lds.sat[0], (unsigned long long)cnt);
+    vi4 v = vi4{0, 0, 0, 0};
+    LaneMask redo = ~0ull;
+    if (ROUND == INTSGD_ROUND_STOCHASTIC && INTSGD_RANDOM_FAST_PATH) {
+      // fast path: no clamp, no clip test; redone below if something may clip or is not finite
+      const vf4 t = vf4{alpha * gv.x, alpha * gv.y, alpha * gv.z, alpha * gv.w};
+      int32_t v0 = 0, v1 = 0, v2 = 0, v3 = 0;
+      round_random_add(t.x, rw.x, v0);
+      round_random_add(t.y, rw.y, v1);
+      round_random_add(t.z, rw.z, v2);
+      round_random_add(t.w, rw.w, v3);
+      v = vi4{v0, v1, v2, v3};
+      RangeWatch watched = range_watch_init();
+      watch(watched, t);
+      redo = out_of_fast_range(watched, a.rs);
+    }
+    if (redo != 0ull) {           // nearest-even always; randomized: wave-uniform and rare
+      LaneMask s0, s1, s2, s3;
+      v.x = round_clip<ROUND>(alpha * gv.x, rw.x, a.rs, s0);
+      v.y = round_clip<ROUND>(alpha * gv.y, rw.y, a.rs, s1);
+      v.z = round_clip<ROUND>(alpha * gv.z, rw.z, a.rs, s2);
+      v.w = round_clip<ROUND>(alpha * gv.w, rw.w, a.rs, s3);
+      const uint32_t cnt = count_lanes(s0, s1, s2, s3);
+      if (cnt != 0 && (threadIdx.x & 63u) == 0) atomicAdd(&lds.sat[0], (unsigned long long)cnt);
+    }
     if (WIRE == INTSGD_WIRE_INT8) {
       const uint32_t packed = ((uint32_t)v.x & 0xFFu) | (((uint32_t)v.y & 0xFFu) << 8) |
                               (((uint32_t)v.z & 0xFFu) << 16) | (((uint32_t)v.w & 0xFFu) << 24);
