@@ -73,8 +73,11 @@ def parse():
     ap.add_argument("--per-set", action="store_true",
                     help="also report the sweep kernel's mean time per resident gradient set")
     ap.add_argument("--no-placement", action="store_true",
-                    help="leave the written state (x, m, shifts) wherever the allocator puts it "
-                         "instead of probing for an HBM region apart from the gradients")
+                    help="leave every buffer wherever the allocator puts it instead of keeping "
+                         "gradients and written state in different regions of one arena")
+    ap.add_argument("--place", default="", metavar="FIELD=REGION,...",
+                    help="move state fields (x, m, h, h_local, sum, q, x_old) to HBM region 0, 1 or 2 "
+                         "of the arena (the gradient sets fill region 0, then 2)")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
                     help="run five plain copies of this size and exit (calibrates FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
@@ -206,7 +209,7 @@ def median(v):
     return s[len(s) // 2] if len(s) % 2 else 0.5 * (s[len(s) // 2 - 1] + s[len(s) // 2])
 
 
-def run_workload(args, hip, cfg, *, cpu_legs):
+def run_workload(args, hip, cfg, *, cpu_legs, arena):
     """Times one workload; returns (top-level result dict, per_config entry)."""
     import torch
 
@@ -224,23 +227,13 @@ def run_workload(args, hip, cfg, *, cpu_legs):
     st = Stepper(desc, eta=w.eta, beta=w.beta, eps=w.eps, device=dev)
 
     grad_bytes = 4 * w.n * w.d
-    free_mem, total_mem = torch.cuda.mem_get_info()
-    region = total_mem // P.HBM_REGIONS
-    # Resident gradient sets, cycled step by step so that nothing of a small set survives in
-    # the 256 MB memory-side cache.  A set larger than a tenth of the memory cannot be cached
-    # anyway; of those, three are generated and the placement probe below keeps the ONE that
-    # goes best with the chosen place of x (a trainer holds one set of gradient buffers and
-    # refills it step after step).
-    pool = args.pool or max(1, min(steps + args.warmup, 16, int(0.45 * free_mem // grad_bytes)))
-    keep_sets = pool if (args.pool or args.no_placement or 10 * grad_bytes < total_mem) else 1
+    stride = W.row_stride(w.d, args.row_skew)
+    set_bytes = 4 * w.n * stride
     settle_ms = 60.0
-    sets = [W.make_gradients(w, s + 1, dev, skew_bytes=args.row_skew) for s in range(pool)]
     stream = torch.cuda.current_stream().cuda_stream     # every library call below launches here
 
     # The written state of the step: x, the momentum buffer, IntDIANA's shifts, the integer
-    # buffers of the unfused forms.  It goes into one arena whose place in HBM is chosen by
-    # timing (placement.py: written and read-only streams in different regions of the memory).
-    stride = W.row_stride(w.d)
+    # buffers of the unfused forms.
     fields = [("x", w.d, torch.float32)]
     if args.momentum:
         fields.append(("m", w.d, torch.float32))
@@ -251,14 +244,47 @@ def run_workload(args, hip, cfg, *, cpu_legs):
     if args.mode == "unfused":
         fields += [("q", w.n * stride, torch.int8 if w.wire == 8 else torch.int32),
                    ("x_old", w.d, torch.float32)]
-    offsets, total = {}, 0
-    for name, numel, dt in fields:
-        offsets[name] = total
-        total += (numel * torch.empty(0, dtype=dt).element_size() + 255) // 256 * 256
+    if cpu_legs:
+        fields.append(("x0", w.d, torch.float32))        # copy of x^0 for the CPU legs
 
-    def carve(arena):
-        return {name: arena[offsets[name]: offsets[name] + numel * torch.empty(0, dtype=dt).element_size()]
-                .view(dt) for name, numel, dt in fields}
+    def nbytes(numel, dt):
+        return numel * torch.empty(0, dtype=dt).element_size()
+
+    # Placement in HBM (placement.py): the gradient sets, which the sweeps only read, fill
+    # region 0 of the arena (then region 2); x goes into region 1, and a second written stream
+    # (momentum buffer, local shifts) into a region other than x's: measured, two written
+    # streams in one region cost 4-6 %, x in the gradients' region 3-6 %.  --place moves
+    # single fields; --no-placement leaves it all to the allocator.
+    # Resident gradient sets are cycled step by step so that nothing of a small set survives
+    # in the 256 MB memory-side cache.
+    default_region = {"x": 1, "m": 2, "h": 0, "h_local": 2, "sum": 1, "q": 2, "x_old": 2, "x0": 2}
+    state_region = {name: default_region[name] for name, _, _ in fields}
+    for item in (args.place.split(",") if args.place else []):
+        name, region = item.split("=")
+        assert name in state_region, "--place: no field %r in this mode" % name
+        state_region[name] = int(region)
+    want = args.pool or min(steps + args.warmup, 16)
+    state, sets, set_regions = {}, [], []
+    if arena is not None:
+        arena.reset()
+        for name, numel, dt in fields:
+            state[name] = arena.take(nbytes(numel, dt), state_region[name]).view(dt)
+            state[name].zero_()
+        for s_idx in range(want):
+            region = next((r for r in (0, 2) if arena.free_in(r) >= set_bytes), None)
+            if region is None:
+                break
+            buf = arena.take(set_bytes, region).view(torch.float32).view(w.n, stride)
+            sets.append(W.make_gradients(w, s_idx + 1, dev, out=buf, skew_bytes=args.row_skew))
+            set_regions.append(region)
+        assert sets, "the arena has no room for one gradient set"
+    else:
+        free_mem, _ = torch.cuda.mem_get_info()
+        for name, numel, dt in fields:
+            state[name] = torch.zeros(numel, dtype=dt, device=dev)
+        for s_idx in range(max(1, min(want, int(0.45 * free_mem // set_bytes)))):
+            sets.append(W.make_gradients(w, s_idx + 1, dev, skew_bytes=args.row_skew))
+    pool = len(sets)
 
     def run_step(v, rows, k, tap=None):
         """One step on the written state `v` (views of an arena); `tap` = a pair of events to
@@ -296,52 +322,6 @@ def run_workload(args, hip, cfg, *, cpu_legs):
             P.intsgd_update_norm(desc, x, v["x_old"], st.norm_sq, st.workspace)
             st.next_alpha()
 
-    placement = None
-    # a state that fits the memory-side cache is read and written there: its place in HBM is moot
-    if args.no_placement or total <= (256 << 20):
-        arena = torch.zeros(total, dtype=torch.uint8, device=dev)
-    else:
-        probe_sets = list(range(pool)) if pool <= 3 else sorted({0, pool // 2, pool - 1})
-        probe_warm = 1 if 4 * w.d > (1 << 30) else 4      # a cache-resident x has to settle first
-
-        def probe_ms(candidate):
-            """Time of the step's calls with `candidate` as the written state, per probed set."""
-            v = carve(candidate)
-            st.start(w.first_normsq)
-            a, b = hip.create(), hip.create()
-            per_set = []
-            for s_idx in probe_sets:
-                total_ms = 0.0
-                for timed in [False] * probe_warm + [True, True]:
-                    if timed:
-                        hip.record(a, stream)
-                    run_step(v, sets[s_idx][1], 1)
-                    if timed:
-                        hip.record(b, stream)
-                        torch.cuda.synchronize()
-                        total_ms += hip.elapsed_ms(a, b)
-                per_set.append(total_ms / 2)
-            hip.destroy(a)
-            hip.destroy(b)
-            return per_set
-
-        def best_sets(t):           # the keep_sets probed sets that go best with one candidate
-            return sorted(range(len(t)), key=lambda i: t[i])[:min(keep_sets, len(t))]
-
-        def choose(timings):
-            return min(range(len(timings)),
-                       key=lambda c: sum(timings[c][i] for i in best_sets(timings[c])))
-
-        placement = []
-        arena = P.allocate_apart(total, dev, probe_ms, spread_bytes=region // 2, choose=choose,
-                                 report=placement)
-        arena.zero_()
-        if keep_sets < pool:        # (only when every set was probed)
-            kept = best_sets(placement[choose(placement)])
-            sets = [sets[i] for i in sorted(kept)]
-            pool = len(sets)
-            torch.cuda.empty_cache()
-    state = carve(arena)
     x = W.make_params(w, dev, out=state["x"])
     torch.cuda.synchronize()
 
@@ -350,7 +330,7 @@ def run_workload(args, hip, cfg, *, cpu_legs):
 
     st.start(w.first_normsq)
     alpha0 = st.alpha.cpu().numpy().copy()
-    x0 = x.clone() if cpu_legs else None
+    x0 = state["x0"].copy_(x) if cpu_legs else None
 
     # Untimed: first enough steps for clocks and caches to settle after the set-up work (at
     # least settle_ms of them), then the W warm-up steps.
@@ -476,11 +456,12 @@ def run_workload(args, hip, cfg, *, cpu_legs):
                                "workgroups_per_cu": args.wgs_per_cu, "two_phase": args.two_phase},
             "alpha_last": alpha_last,
             "clipped_last_step": sat,
-            "state_placement": ("allocator's choice" if placement is None else
-                                {"rule": "written state where the step ran fastest: timed probe over "
-                                         "candidate buffers spread across device memory, one row per "
-                                         "candidate, one column per probed gradient set",
-                                 "candidate_ms": placement}),
+            "placement": ("allocator's choice" if arena is None else
+                          {"rule": "one arena over the free device memory, read as three regions of "
+                                   "a third of the HBM each: gradient sets (only read) in one region, "
+                                   "written state in another",
+                           "gradient_set_regions": set_regions,
+                           "state_regions": {k: v for k, v in state_region.items() if k != "x0"}}),
         },
         "timing": {
             "regions": len(loop_ev), "steps_per_region": steps,
@@ -514,7 +495,7 @@ def run_workload(args, hip, cfg, *, cpu_legs):
     }
     if "cpu_baseline" in result:
         entry["cpu_baseline_gbs_1_core"] = result["cpu_baseline"]["value"]
-    del sets, x, st, state, arena
+    del sets, x, st, state
     torch.cuda.empty_cache()
     return result, entry
 
@@ -536,16 +517,20 @@ def main():
     hip = HipEvents()
     widened = args.heuristic or args.diana or args.momentum
     cpu = not args.no_cpu_baseline and not widened
-    # CPU legs: about 5 s of single-core oracle work; the all-cores leg gives every thread as much
-    big_legs = {"one_core_wc": 1 << 27, "all_cores_wc_per_thread": 1 << 27}
+    # CPU legs: about 10 s of single-core oracle work; the all-cores leg gives every thread a quarter of it
+    big_legs = {"one_core_wc": 1 << 29, "all_cores_wc_per_thread": 1 << 27}
+    import paper_2102_08374_amd as P
+    arena = None if args.no_placement else P.Arena("cuda:0", keep_free=8 << 30)
     if args.config:
-        result, _ = run_workload(args, hip, args.config, cpu_legs=big_legs if cpu else None)
+        result, _ = run_workload(args, hip, args.config, cpu_legs=big_legs if cpu else None, arena=arena)
         print(json.dumps(result))
         return
-    result, head_entry = run_workload(args, hip, HEADLINE_CONFIG, cpu_legs=big_legs if cpu else None)
+    result, head_entry = run_workload(args, hip, HEADLINE_CONFIG, cpu_legs=big_legs if cpu else None,
+                                      arena=arena)
     per_config = []
     for cfg in (1, 2, 3, 4):
-        _, entry = run_workload(args, hip, cfg, cpu_legs={"one_core_wc": 1 << 26} if cpu else None)
+        _, entry = run_workload(args, hip, cfg, cpu_legs={"one_core_wc": 1 << 26} if cpu else None,
+                                arena=arena)
         per_config.append(entry)
     per_config.append(head_entry)
     result["per_config"] = per_config

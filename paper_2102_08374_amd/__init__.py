@@ -5,4 +5,4 @@ marshals arguments.  PyTorch is used for device memory and streams.
 """
 from .binding import *  # noqa: F401,F403
 from .binding import __all__  # noqa: F401
-from .placement import HBM_REGIONS, allocate_apart  # noqa: F401
+from .placement import HBM_REGIONS, Arena  # noqa: F401
