@@ -331,7 +331,8 @@ def test_traffic_table_keys_match_workload_names():
                         "traffic.json")
     with open(path) as fh:
         table = json.load(fh)
-    names = {W.config(i).name for i in range(1, 6)} | {W.config(4, per_bucket=False).name}
+    names = {W.config(i, rounding=r).name for i in range(1, 6) for r in (None, 0, 1)}
+    names.add(W.config(4, per_bucket=False).name)
     keys = [k for k in table if not k.startswith("_")]
     assert keys, "empty traffic table"
     for k in keys:
