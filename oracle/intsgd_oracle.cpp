@@ -331,6 +331,20 @@ uint64_t oracle_diana_step(const float* const* grads, const float* const* h_loca
   return overflow;
 }
 
+// The largest integer in the aggregate (Appendix A.2 reports, per iteration, the max integer
+// in the aggregated vector sum_i Q(g_i); the discussion of IntDIANA is about keeping it
+// bounded): max_j |S_j| per block over a slice, as a running maximum in `largest` (uint32:
+// |S_j| <= n L <= 2^31 - 1, and |INT32_MIN| = 2^31 still fits).
+void oracle_max_abs_sum(const int32_t* sum, uint64_t j0, uint64_t len, const uint64_t* offsets,
+                        uint32_t B, uint32_t* largest) {
+  for (uint64_t t_ = 0; t_ < len; ++t_) {
+    const int64_t v = (int64_t)sum[t_];
+    const uint32_t mag = (uint32_t)(v < 0 ? -v : v);
+    uint32_t& slot = largest[block_of(j0 + t_, offsets, B)];
+    if (mag > slot) slot = mag;
+  }
+}
+
 // Heuristic IntSGD scaling (Section 5.2; the SwitchML rule the paper compares with):
 // alpha = (2^nb - 1) / (n 2^max_exp), max_exp the exponent of the largest absolute value
 // in the package, read here as the smallest integer e with 2^e >= max|g| over all n

@@ -15,7 +15,7 @@ __all__ = [
     "philox4x32_10", "random_word", "int_random", "int_nearest", "saturate", "compress",
     "int_sum", "decode_update", "update_norm", "next_alpha", "step", "decode_update_momentum",
     "step_momentum", "diana_compress", "diana_update", "diana_step",
-    "max_abs", "heuristic_alpha",
+    "max_abs", "heuristic_alpha", "max_abs_sum",
     "ROUND_NEAREST_EVEN", "ROUND_STOCHASTIC",
 ]
 
@@ -74,6 +74,9 @@ _lib.oracle_diana_step.argtypes = [C.POINTER(_f32p), C.POINTER(_f32p), C.c_uint3
 _lib.oracle_diana_step.restype = C.c_uint64
 _lib.oracle_max_abs.argtypes = [_f32p, C.c_uint64, C.c_uint64, _u64p, C.c_uint32, _f32p]
 _lib.oracle_max_abs.restype = None
+_lib.oracle_max_abs_sum.argtypes = [C.POINTER(C.c_int32), C.c_uint64, C.c_uint64, _u64p, C.c_uint32,
+                                    C.POINTER(C.c_uint32)]
+_lib.oracle_max_abs_sum.restype = None
 _lib.oracle_heuristic_alpha.argtypes = [_f32p, C.c_uint32, C.c_uint32, C.c_uint32, _f64p, _f32p]
 _lib.oracle_heuristic_alpha.restype = None
 _lib.oracle_update_norm.argtypes = [_f32p, _f32p, C.c_uint64, C.c_uint64, _u64p, C.c_uint32,
@@ -334,6 +337,15 @@ def max_abs(g, *, j0=0, offsets=None, B=1, out=None):
     off, offp = _offsets(offsets, B)
     m = np.zeros(B, np.float32) if out is None else out
     _lib.oracle_max_abs(_ptr(g, C.c_float), int(j0), g.size, offp, B, _ptr(m, C.c_float))
+    return m
+
+
+def max_abs_sum(S, *, j0=0, offsets=None, B=1, out=None):
+    """Largest |S_j| per block over a slice of the aggregate (running maximum in ``out``)."""
+    S = _arr(S, np.int32)
+    off, offp = _offsets(offsets, B)
+    m = np.zeros(B, np.uint32) if out is None else out
+    _lib.oracle_max_abs_sum(_ptr(S, C.c_int32), int(j0), S.size, offp, B, _ptr(m, C.c_uint32))
     return m
 
 

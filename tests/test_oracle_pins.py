@@ -616,3 +616,44 @@ def test_heuristic_scaling_rule():
         q, cnt = oracle.compress(np.where(np.isfinite(g[0]), g[0], 0).astype(F32), af, rounding=0,
                                  L=2**nb - 1, offsets=offsets)
         assert cnt == 0 and np.abs(q).max() <= math.ceil((2**nb - 1) / n)
+
+
+# ----------------------------------------------------------------------------- largest integer
+def test_largest_integer_in_the_aggregate():
+    """Appendix A.2 reports the max integer in the aggregated vector: planted extremes per
+    block, slices that combine, both ends of int32, a closed form (equal gradients: S = n
+    round(alpha c)), the bound n L with the value attained when every worker clips, and brute
+    force over random aggregates in pure Python."""
+    offsets = np.array([0, 3, 10, 11, 40], np.uint64)
+    S = np.zeros(40, np.int32)
+    S[1], S[2] = 5, -7            # block 0: the negative one wins
+    S[9] = 3                      # block 1: last coordinate of the block
+    S[10] = -1                    # block 2: one coordinate
+    S[11], S[39] = -2**31, 2**31 - 1   # block 3: both ends of the type
+    assert oracle.max_abs_sum(S, offsets=offsets, B=4).tolist() == [7, 3, 1, 2**31]
+    assert oracle.max_abs_sum(S).tolist() == [2**31]
+    assert oracle.max_abs_sum(np.zeros(0, np.int32)).tolist() == [0]
+    # slices in any order give the same running maximum
+    m = np.zeros(4, np.uint32)
+    for a, b in ((25, 40), (0, 2), (2, 25)):
+        oracle.max_abs_sum(S[a:b], j0=a, offsets=offsets, B=4, out=m)
+    assert m.tolist() == [7, 3, 1, 2**31]
+    # equal gradients: S_j = n * round(alpha c)
+    n, c, alpha = 6, F32(0.3), np.array([41.0], F32)
+    g = [np.full(17, c, F32) for _ in range(n)]
+    out = oracle.step(g, alpha, np.zeros(17, F32), rounding=0, L=10**6, eta=0.1)
+    assert oracle.max_abs_sum(out["S"]).tolist() == [n * 12]          # 41 * 0.3 = 12.3 -> 12
+    # every worker clips with the same sign: the bound n L is attained, and never exceeded
+    L = 127
+    g = [np.full(9, F32(-50.0), F32) for _ in range(n)]
+    out = oracle.step(g, np.array([1000.0], F32), np.zeros(9, F32), rounding=1, L=L, eta=0.1, seed=3)
+    assert oracle.max_abs_sum(out["S"]).tolist() == [n * L]
+    rng = np.random.default_rng(101)
+    for trial in range(20):
+        d = int(rng.integers(1, 60))
+        B = int(rng.integers(1, min(d, 5) + 1))
+        cuts = np.sort(rng.choice(np.arange(1, d), B - 1, replace=False)) if B > 1 else []
+        off = np.array([0, *cuts, d], np.uint64)
+        S = rng.integers(-1000, 1000, d).astype(np.int32)
+        want = [max(abs(int(v)) for v in S[int(off[l]):int(off[l + 1])]) for l in range(B)]
+        assert oracle.max_abs_sum(S, offsets=off, B=B).tolist() == want
