@@ -78,6 +78,8 @@ def parse():
     ap.add_argument("--place", default="", metavar="FIELD=REGION,...",
                     help="move state fields (x, m, h, h_local, sum, q, x_old) to HBM region 0, 1 or 2 "
                          "of the arena (the gradient sets fill region 0, then 2)")
+    ap.add_argument("--largest-sum", action="store_true",
+                    help="also ask every step for the largest |S_j| per block (reported for the last step)")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
                     help="run five plain copies of this size and exit (calibrates FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
@@ -225,6 +227,10 @@ def run_workload(args, hip, cfg, *, cpu_legs, arena):
     desc = P.Desc(w.d, w.n, rounding=w.rounding, wire=w.wire, clip=w.clip, seed=w.philox_seed,
                   block_offsets=w.block_offsets, opts=opts)
     st = Stepper(desc, eta=w.eta, beta=w.beta, eps=w.eps, device=dev)
+    largest = None
+    if args.largest_sum:
+        largest = torch.zeros(w.num_blocks, dtype=torch.int32, device=dev)
+        desc.largest_sum = largest
 
     grad_bytes = 4 * w.n * w.d
     stride = W.row_stride(w.d, args.row_skew)
@@ -456,6 +462,8 @@ def run_workload(args, hip, cfg, *, cpu_legs, arena):
                                "workgroups_per_cu": args.wgs_per_cu, "two_phase": args.two_phase},
             "alpha_last": alpha_last,
             "clipped_last_step": sat,
+            "largest_sum_last_step": (int(largest.cpu().numpy().view("uint32").max())
+                                      if largest is not None else None),
             "placement": ("allocator's choice" if arena is None else
                           {"rule": "one arena over the free device memory, read as three regions of "
                                    "a third of the HBM each: gradient sets (only read) in one region, "

@@ -138,6 +138,12 @@ typedef struct intsgd_desc {
   uint32_t step;
   uint64_t seed;
   const intsgd_launch_opts* launch;
+  /* Optional output, DEVICE uint32_t[B] (4-byte aligned) or NULL.  The calls whose sweep forms
+   * the aggregate S (intsgd_compress_sum, intsgd_step_fused, intsgd_step_fused_next_alpha,
+   * intsgd_step_fused_static, intsgd_step_momentum, intsgd_diana_step) overwrite it with
+   * max_j |S_j| over each block's coordinates: the largest integer in the aggregated vector,
+   * which Appendix A.2 reports per iteration.  Every other call ignores it. */
+  uint32_t* largest_sum;
 } intsgd_desc;
 
 /* Bytes of DEVICE scratch (256-byte aligned) that any entry point taking a
@@ -260,7 +266,7 @@ INTSGD_API intsgd_status intsgd_step_fused_next_alpha(const intsgd_desc* desc,
  * with its scratch in a static device array of INTSGD_STATIC_SCRATCH_BYTES that every GPU
  * running the library holds until the process ends.  Same arguments (minus the workspace)
  * and the same results.  It calls no hipMalloc / hipFree and no allocating routine.
- *   - The scratch must hold 12 + 8 n bytes per work tile (2048 coordinates, or
+ *   - The scratch must hold 16 + 8 n bytes per work tile (2048 coordinates, or
  *     desc->launch->tile_coords), or per compute unit when the call takes the two-phase
  *     form, plus 1 KiB; a larger problem is refused with INTSGD_EWORKSPACE and nothing is
  *     launched.  32 MiB covers d = 9.0e8 at n = 8 (d = 1.3e9 with tile_coords = 4096),

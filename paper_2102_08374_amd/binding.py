@@ -71,7 +71,8 @@ class _CDesc(C.Structure):
     _fields_ = [("d", C.c_uint64), ("n", C.c_uint32), ("num_blocks", C.c_uint32),
                 ("block_offsets", C.POINTER(C.c_uint64)), ("rounding", C.c_int32),
                 ("wire", C.c_int32), ("clip", C.c_int32), ("step", C.c_uint32),
-                ("seed", C.c_uint64), ("launch", C.POINTER(_CLaunchOpts))]
+                ("seed", C.c_uint64), ("launch", C.POINTER(_CLaunchOpts)),
+                ("largest_sum", C.c_void_p)]
 
 
 _P = C.c_void_p
@@ -160,7 +161,7 @@ class Desc:
     options alive)."""
 
     def __init__(self, d, n, *, rounding=ROUND_NEAREST_EVEN, wire=WIRE_INT32, clip=None, seed=0,
-                 step=0, block_offsets=None, opts=None):
+                 step=0, block_offsets=None, opts=None, largest_sum=None):
         self._offsets = None
         num_blocks = 1
         ptr = None
@@ -172,8 +173,9 @@ class Desc:
         if clip is None:
             clip = default_clip(n, WIRE_INT32)
         self.c = _CDesc(int(d), int(n), int(num_blocks), ptr, int(rounding), int(wire), int(clip),
-                        int(step) & 0xFFFFFFFF, int(seed) & 0xFFFFFFFFFFFFFFFF, None)
+                        int(step) & 0xFFFFFFFF, int(seed) & 0xFFFFFFFFFFFFFFFF, None, None)
         self.opts = opts
+        self.largest_sum = largest_sum
 
     d = property(lambda self: self.c.d)
     n = property(lambda self: self.c.n)
@@ -197,6 +199,21 @@ class Desc:
         """A LaunchOpts (kept alive by this object) or None = automatic."""
         self._opts = opts
         self.c.launch = C.pointer(opts.c) if opts is not None else None
+
+    @property
+    def largest_sum(self):
+        return self._largest_sum
+
+    @largest_sum.setter
+    def largest_sum(self, t):
+        """Optional output of the calls whose sweep forms the aggregate: a device int32 tensor
+        of B elements that receives max |S_j| per block (read it as unsigned), or None.  Kept
+        alive by this object."""
+        if t is not None:
+            assert t.is_cuda and t.is_contiguous() and t.dtype == torch.int32, "largest_sum: int32 on the device"
+            assert t.numel() >= self.c.num_blocks, "largest_sum: one element per block"
+        self._largest_sum = t
+        self.c.largest_sum = None if t is None else t.data_ptr()
 
     def ref(self):
         return C.byref(self.c)

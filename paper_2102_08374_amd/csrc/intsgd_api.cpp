@@ -132,6 +132,7 @@ intsgd_status validate_desc(const intsgd_desc* desc) {
     for (uint32_t l = 0; l < desc->num_blocks; ++l)
       if (off[l + 1] <= off[l]) return INTSGD_EINVAL;
   }
+  if ((reinterpret_cast<uintptr_t>(desc->largest_sum) & 3u) != 0) return INTSGD_EALIGN;
   return validate_launch_opts(desc->launch);
 }
 
@@ -164,7 +165,7 @@ uint64_t tiles_of(uint64_t len, uint32_t tile) { return (len + tile - 1) / tile;
 // smallest tile so that it is valid under any tuning (the grid never exceeds the
 // number of tiles).
 struct WorkspaceLayout {
-  size_t norm_off, mid_off, hint_off, any_off, rows_off, total;
+  size_t norm_off, mid_off, hint_off, any_off, rows_off, big_off, bigmid_off, total;
 };
 
 // Layout for at most max_tiles work tiles (or workgroups, whichever is larger).
@@ -175,7 +176,9 @@ WorkspaceLayout workspace_layout_for(const intsgd_desc* desc, uint64_t max_tiles
   w.hint_off = w.mid_off + round_up((size_t)(max_tiles / 4096 + 2) * sizeof(double), kAlign);
   w.any_off = w.hint_off + kAlign;
   w.rows_off = w.any_off + round_up((size_t)max_tiles * sizeof(uint32_t), kAlign);
-  w.total = w.rows_off + round_up((size_t)max_tiles * desc->n * sizeof(uint64_t), kAlign);
+  w.big_off = w.rows_off + round_up((size_t)max_tiles * desc->n * sizeof(uint64_t), kAlign);
+  w.bigmid_off = w.big_off + round_up((size_t)max_tiles * sizeof(uint32_t), kAlign);
+  w.total = w.bigmid_off + round_up((size_t)(max_tiles / 4096 + 2) * sizeof(uint32_t), kAlign);
   return w;
 }
 
@@ -378,6 +381,9 @@ Finish make_finish(const intsgd_desc* desc, const Tiling& t, void* ws, double* n
   f.n_workers = desc->n;
   f.d = desc->d;
   f.rule = AlphaRule{nullptr, nullptr, nullptr, 0.0, 0.0, 0.0};
+  f.big_partial = ws_at<uint32_t>(ws, w.big_off);
+  f.big_mid = ws_at<uint32_t>(ws, w.bigmid_off);
+  f.big_out = nullptr;            // set by the calls whose sweep forms the aggregate
   return f;
 }
 
@@ -447,6 +453,7 @@ intsgd_status step_fused_impl(const intsgd_desc* desc, const float* const* grads
   WorkerPtrs g;
   fill_ptrs(&g, (const void* const*)grads, desc->n);
   Finish fin = make_finish(desc, t, workspace, norm_sq_out, sat_count, &layout);
+  fin.big_out = desc->largest_sum;
   // Algorithm 1's scaling-factor line pairs alpha_{k+1} with eta_{k+1}
   if (r != nullptr) fin.rule = AlphaRule{r, alpha_out, t.offsets_dev, beta, eps, eta_next};
   if (phased)
@@ -620,7 +627,8 @@ intsgd_status intsgd_compress_sum(const intsgd_desc* desc, const float* const* g
   INTSGD_TRY(make_tiling(desc, hip_stream, &t));
   WorkerPtrs g;
   fill_ptrs(&g, (const void* const*)grads, desc->n);
-  const Finish fin = make_finish(desc, t, workspace, nullptr, sat_count);
+  Finish fin = make_finish(desc, t, workspace, nullptr, sat_count);
+  fin.big_out = desc->largest_sum;
   PhasedShape ps{0};
   bool phased = false;
   INTSGD_TRY(two_phase_shape(desc, &ps, &phased));
@@ -725,6 +733,7 @@ intsgd_status intsgd_diana_step(const intsgd_desc* desc, const float* const* gra
   std::memset(&hl, 0, sizeof(hl));
   for (uint32_t i = 0; i < desc->n; ++i) hl.p[i] = h_local[i];
   Finish fin = make_finish(desc, t, workspace, norm_sq_out, sat_count);
+  fin.big_out = desc->largest_sum;
   if (r != nullptr) fin.rule = AlphaRule{r, alpha, t.offsets_dev, beta, eps, eta_next};
   return done(launch_diana_step(t.tm, t.ls, desc->n, round_spec(desc), g, hl, alpha, eta, x, h, fin));
 }

@@ -90,6 +90,9 @@ struct Finish {
   uint32_t n_workers;             // n of the problem (alpha rule)
   uint64_t d;
   AlphaRule rule;
+  uint32_t* big_partial;          // one slot per tile: largest |S_j| of the tile (used only with big_out)
+  uint32_t* big_mid;              // first-level maxima when the tile list is very long
+  uint32_t* big_out;              // B, or null: the largest |S_j| per block is not asked for
 };
 
 // Address, on the current device, of the library's static device scratch array of

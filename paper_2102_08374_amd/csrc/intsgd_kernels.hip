@@ -331,6 +331,7 @@ __device__ __forceinline__ double wave_sum(double v) {
 struct ReduceLds {
   double red[2][kMaxWaves];         // double-buffered wave sums
   unsigned long long sat[INTSGD_MAX_WORKERS];
+  uint32_t big[2][kMaxWaves];       // double-buffered wave maxima
 };
 
 // Sum over the workgroup, a two-level tree: DPP / lane reads within each wavefront, the wave
@@ -347,6 +348,73 @@ __device__ __forceinline__ double block_sum(double v, ReduceLds& lds, uint32_t s
     total = wave_sum(threadIdx.x < waves ? lds.red[slot][threadIdx.x] : 0.0);
   }
   return total;
+}
+
+// Largest and smallest aggregate a thread has seen: the largest |S_j| is max(hi, -lo).
+// Kept as two signed extremes so that a quad costs four three-input min / max instructions.
+struct Extremes {
+  int32_t hi, lo;
+};
+__device__ __forceinline__ Extremes extremes_init() { return Extremes{0, 0}; }
+__device__ __forceinline__ void note(Extremes& e, int32_t S) {
+  e.hi = max(e.hi, S);
+  e.lo = min(e.lo, S);
+}
+__device__ __forceinline__ void note(Extremes& e, const vi4& S) {
+  e.hi = max(max(e.hi, S.x), S.y);
+  e.hi = max(max(e.hi, S.z), S.w);
+  e.lo = min(min(e.lo, S.x), S.y);
+  e.lo = min(min(e.lo, S.z), S.w);
+}
+__device__ __forceinline__ uint32_t magnitude(const Extremes& e) {
+  const uint32_t neg = 0u - (uint32_t)e.lo;       // |lo| without overflow at INT32_MIN
+  return max((uint32_t)e.hi, neg);
+}
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_move_u32(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, false);
+}
+
+// Maximum over the workgroup (same tree as block_sum; exact in any order).  Valid in thread 0;
+// `slot` alternates between consecutive calls.
+__device__ __forceinline__ uint32_t wave_max(uint32_t v) {
+  v = max(v, dpp_move_u32<0xB1>(v));
+  v = max(v, dpp_move_u32<0x4E>(v));
+  v = max(v, dpp_move_u32<0x141>(v));
+  v = max(v, dpp_move_u32<0x140>(v));
+  return max(max((uint32_t)__builtin_amdgcn_readlane((int)v, 0), (uint32_t)__builtin_amdgcn_readlane((int)v, 16)),
+             max((uint32_t)__builtin_amdgcn_readlane((int)v, 32), (uint32_t)__builtin_amdgcn_readlane((int)v, 48)));
+}
+__device__ __forceinline__ uint32_t block_max(uint32_t v, ReduceLds& lds, uint32_t slot) {
+  const uint32_t w = wave_max(v);
+  if ((threadIdx.x & 63u) == 0) lds.big[slot][threadIdx.x >> 6] = w;
+  __syncthreads();
+  uint32_t total = 0u;
+  if (threadIdx.x < 64u) {
+    const uint32_t waves = blockDim.x >> 6;
+    total = wave_max(threadIdx.x < waves ? lds.big[slot][threadIdx.x] : 0u);
+  }
+  return total;
+}
+
+// block_sum and block_max behind one barrier (valid in thread 0).
+__device__ __forceinline__ void block_sum_and_max(double v, uint32_t m, ReduceLds& lds, uint32_t slot,
+                                                  double& total, uint32_t& best) {
+  const double w = wave_sum(v);
+  const uint32_t wm = wave_max(m);
+  if ((threadIdx.x & 63u) == 0) {
+    lds.red[slot][threadIdx.x >> 6] = w;
+    lds.big[slot][threadIdx.x >> 6] = wm;
+  }
+  __syncthreads();
+  total = 0.0;
+  best = 0u;
+  if (threadIdx.x < 64u) {
+    const uint32_t waves = blockDim.x >> 6;
+    total = wave_sum(threadIdx.x < waves ? lds.red[slot][threadIdx.x] : 0.0);
+    best = wave_max(threadIdx.x < waves ? lds.big[slot][threadIdx.x] : 0u);
+  }
 }
 
 // ------------------------------------------------------------------ tiles
@@ -656,33 +724,64 @@ __device__ __forceinline__ double ordered_sum(const double* partial, uint32_t t0
   return block_sum(acc, lds, 0);
 }
 
-// First level for very long partial lists (one block only): workgroup c sums chunk c.
+// Maximum of big[t0, t1) by the whole workgroup (valid in thread 0).
+__device__ __forceinline__ uint32_t range_max(const uint32_t* big, uint32_t t0, uint32_t t1,
+                                              ReduceLds& lds) {
+  uint32_t best = 0u;
+  uint32_t t = t0 + threadIdx.x;
+  for (; t + 7u * kThreads < t1; t += 8u * kThreads) {
+    uint32_t v[8];
+#pragma unroll
+    for (uint32_t u = 0; u < 8; ++u) v[u] = big[t + u * kThreads];
+#pragma unroll
+    for (uint32_t u = 0; u < 8; ++u) best = max(best, v[u]);
+  }
+  for (; t < t1; t += kThreads) best = max(best, big[t]);
+  return block_max(best, lds, 0);
+}
+
+// First level for very long partial lists (one block only): workgroup c sums chunk c of the
+// norm partials (if any) and takes the maximum of chunk c of the largest-|S| partials (if any).
 __global__ __launch_bounds__(kThreads) void k_finish_chunks(const double* partial, uint32_t count,
-                                                            uint32_t chunk, double* mid) {
+                                                            uint32_t chunk, double* mid,
+                                                            const uint32_t* big, uint32_t* big_mid) {
   __shared__ ReduceLds lds;
   const uint32_t t0 = blockIdx.x * chunk;
   const uint32_t t1 = (count - t0 < chunk) ? count : t0 + chunk;
-  const double total = ordered_sum(partial, t0, t1, lds);
-  if (threadIdx.x == 0) mid[blockIdx.x] = total;
+  if (partial != nullptr) {
+    const double total = ordered_sum(partial, t0, t1, lds);
+    if (threadIdx.x == 0) mid[blockIdx.x] = total;
+  }
+  if (big != nullptr) {
+    const uint32_t best = range_max(big, t0, t1, lds);
+    if (threadIdx.x == 0) big_mid[blockIdx.x] = best;
+  }
 }
 
 // Workgroups [0, norm_blocks) sum the norm partials of one block each in a fixed order and
-// apply the optional alpha rule to it; the n workgroups after them total one worker's clip
+// apply the optional alpha rule to it (WITH_NORM), and take the block's largest |S_j| (if
+// asked for); the n workgroups after them total one worker's clip
 // counts each (reading the table only if this launch's id is in the hint word, i.e. if
 // something clipped; a stale or uninitialised hint can at worst cause a needless read).
 template <bool WITH_NORM, bool WITH_SAT>
 __global__ __launch_bounds__(kThreads) void k_finish(const Finish f) {
   __shared__ ReduceLds lds;
   const uint32_t tid = threadIdx.x;
-  const uint32_t norm_blocks = WITH_NORM ? f.B : 0u;
-  if (WITH_NORM && blockIdx.x < norm_blocks) {
+  const uint32_t norm_blocks = (WITH_NORM || f.big_out != nullptr) ? f.B : 0u;
+  if (blockIdx.x < norm_blocks) {
     const uint32_t l = blockIdx.x;
     const uint32_t t0 = (f.B == 1) ? 0u : f.tile_prefix[l];
     const uint32_t t1 = (f.B == 1) ? f.num_tiles : f.tile_prefix[l + 1];
-    const double total = ordered_sum(f.norm_partial, t0, t1, lds);
-    if (tid == 0) {
-      f.norm_sq_out[l] = total;
-      if (f.rule.r != nullptr) apply_alpha_rule(f.rule, f.B, f.n_workers, f.d, l, total);
+    if (WITH_NORM) {
+      const double total = ordered_sum(f.norm_partial, t0, t1, lds);
+      if (tid == 0) {
+        f.norm_sq_out[l] = total;
+        if (f.rule.r != nullptr) apply_alpha_rule(f.rule, f.B, f.n_workers, f.d, l, total);
+      }
+    }
+    if (f.big_out != nullptr) {
+      const uint32_t best = range_max(f.big_partial, t0, t1, lds);
+      if (tid == 0) f.big_out[l] = best;
     }
     return;
   }
@@ -754,7 +853,10 @@ struct AggregateArgs {
   WorkerPtrs grads;
 };
 
-template <int ROUND, bool FUSED, bool MOMENTUM, int XSTORE>
+// LARGEST: also track the largest |S_j| of the tile.  A template parameter, not a run-time flag:
+// the randomized sweep runs close to its vector-ALU ceiling, and the flag's branch and registers
+// cost it 1-2 % even when nothing is asked for.
+template <int ROUND, bool FUSED, bool MOMENTUM, int XSTORE, bool LARGEST>
 struct AggregateOp {
   const AggregateArgs& a;
   ReduceLds& lds;
@@ -763,6 +865,8 @@ struct AggregateOp {
   uint64_t q0;
   uint32_t nq;
   LaneMask any;                 // lanes of this wavefront that clipped somewhere in the tile body
+  Extremes ext;                 // of the aggregates this thread formed in the tile (if asked for)
+  static constexpr bool want_largest = LARGEST;
   // Randomized rounding takes the fast path (no clamp, no clip test per coordinate) and
   // redoes, counting as it goes, the rare quad of a wavefront in which something may clip.
   static constexpr bool kCountInline = ROUND == INTSGD_ROUND_STOCHASTIC;
@@ -772,16 +876,19 @@ struct AggregateOp {
   bool keep;                    // this tile's part of x (and m) is to stay in the last-level cache
 
   __device__ __forceinline__ AggregateOp(const AggregateArgs& args, ReduceLds& l)
-      : a(args), lds(l), alpha(0.f), c(0.0), acc(0.0), q0(0), nq(0), any(0ull) {}
+      : a(args), lds(l), alpha(0.f), c(0.0), acc(0.0), q0(0), nq(0), any(0ull),
+        ext(extremes_init()) {}
   __device__ __forceinline__ void begin_tile(uint32_t blk) {
     alpha = a.alpha[blk];
     any = 0ull;
+    ext = extremes_init();
     if (FUSED && !MOMENTUM) c = decode_constant(a.eta, a.n, alpha);
     if (MOMENTUM) rule = MomentumRule{1.0 / ((double)a.n * (double)alpha), a.eta, a.mu, a.wd};
     acc = 0.0;
   }
   __device__ __forceinline__ void scalar(uint64_t j) {
     const int32_t S = aggregate_scalar<ROUND>(a.grads, a.n, j, alpha, a.rs, lds.sat);
+    if (want_largest) note(ext, S);
     if (MOMENTUM) {
       float mj = a.m[j];
       a.x[j] = momentum_coord(a.x[j], mj, S, rule, acc);
@@ -816,6 +923,7 @@ struct AggregateOp {
     } else {
       S = aggregate_quad<ROUND, false>(a.grads, a.n, q0, nq, ql, alpha, a.rs, lds.sat, any);
     }
+    if (want_largest) note(ext, S);
     if (MOMENTUM) {
       const vf4 xn = momentum_quad(xv, mv, S, rule, acc);
       store128<XS>(mom, ql * 16u, as_u(mv));
@@ -839,19 +947,30 @@ struct AggregateOp {
       for (uint32_t ql = threadIdx.x; ql < nq; ql += kThreads)
         (void)aggregate_quad<ROUND, true>(a.grads, a.n, q0, nq, ql, alpha, a.rs, lds.sat, unused);
     }
-    if (FUSED) {
+    if (FUSED && want_largest) {
+      double total;
+      uint32_t best;
+      block_sum_and_max(acc, magnitude(ext), lds, iter & 1u, total, best);
+      if (threadIdx.x == 0) {
+        a.fin.norm_partial[t] = total;
+        a.fin.big_partial[t] = best;
+      }
+    } else if (FUSED) {
       const double total = block_sum(acc, lds, iter & 1u);
       if (threadIdx.x == 0) a.fin.norm_partial[t] = total;
+    } else if (want_largest) {
+      const uint32_t best = block_max(magnitude(ext), lds, iter & 1u);
+      if (threadIdx.x == 0) a.fin.big_partial[t] = best;
     }
   }
 };
 
 // XSTORE: cache policy of the x / m (or S) stores, chosen by the launcher from the vector's size.
-template <int ROUND, bool FUSED, bool MOMENTUM, int XSTORE>
+template <int ROUND, bool FUSED, bool MOMENTUM, int XSTORE, bool LARGEST>
 __global__ __launch_bounds__(kThreads) void k_aggregate(const AggregateArgs a) {
   __shared__ ReduceLds lds;
   zero_sat(lds);
-  AggregateOp<ROUND, FUSED, MOMENTUM, XSTORE> op(a, lds);
+  AggregateOp<ROUND, FUSED, MOMENTUM, XSTORE, LARGEST> op(a, lds);
   drive_tiles(a.tm, op);
   __syncthreads();
   if (threadIdx.x == 0) publish_sat(a.fin, lds, blockIdx.x);
@@ -919,6 +1038,8 @@ __global__ __launch_bounds__(kPhasedThreads) void k_aggregate_phased(const Phase
   const uint32_t slab_row = gridDim.x * kPhasedThreads;           // quads per iteration k, chip-wide
   const uint64_t per_round = (uint64_t)slab_row * kPhasedQuads;
   double acc = 0.0;
+  const bool want_largest = a.fin.big_out != nullptr;      // wave-uniform
+  Extremes ext = extremes_init();
   for (uint64_t r0 = 0; r0 < nquads; r0 += per_round) {
     const uint64_t rest = nquads - r0;
     const uint32_t nq = rest < per_round ? (uint32_t)rest : (uint32_t)per_round;
@@ -932,6 +1053,10 @@ __global__ __launch_bounds__(kPhasedThreads) void k_aggregate_phased(const Phase
         S[k] = aggregate_quad<ROUND, false>(a.grads, a.n, r0, nq,
                                             (k * gridDim.x + blockIdx.x) * kPhasedThreads + tid,
                                             alpha, a.rs, lds.sat, any);
+    }
+    if (want_largest) {           // lanes past the round hold zeros
+#pragma clang loop unroll(full)
+      for (uint32_t k = 0; k < kPhasedQuads; ++k) note(ext, S[k]);
     }
     if (any != 0ull) {            // rare: something clipped in this wavefront's quads
       // Counted per worker here.  A lane past the round scales its zeros by 0 instead of
@@ -972,6 +1097,7 @@ __global__ __launch_bounds__(kPhasedThreads) void k_aggregate_phased(const Phase
   if (blockIdx.x == 0 && tid < (uint32_t)(a.d & 3u)) {      // the d mod 4 coordinates after the last quad
     const uint64_t j = (a.d & ~(uint64_t)3) + tid;
     const int32_t Sj = aggregate_scalar<ROUND>(a.grads, a.n, j, alpha, a.rs, lds.sat);
+    if (want_largest) note(ext, Sj);
     if (MODE == kPhasedSumOnly) {
       a.sum_out[j] = Sj;
     } else if (MOMENTUM) {
@@ -983,8 +1109,11 @@ __global__ __launch_bounds__(kPhasedThreads) void k_aggregate_phased(const Phase
     }
   }
   const double total = block_sum(acc, lds, 0);
+  uint32_t best = 0u;
+  if (want_largest) best = block_max(magnitude(ext), lds, 0);
   if (tid == 0) {
     if (MODE != kPhasedSumOnly) a.fin.norm_partial[blockIdx.x] = total;
+    if (want_largest) a.fin.big_partial[blockIdx.x] = best;
     publish_sat(a.fin, lds, blockIdx.x);
   }
 }
@@ -1033,14 +1162,18 @@ struct DianaOp {
   uint64_t q0;
   uint32_t nq;
   __amdgpu_buffer_rsrc_t x_s, h_s;
+  Extremes ext;                 // of the aggregates this thread formed in the tile (if asked for)
+  const bool want_largest;      // wave-uniform
 
   __device__ __forceinline__ DianaOp(const DianaArgs& args, ReduceLds& l)
-      : a(args), lds(l), alpha(0.f), inv_alpha(0.0), cg(0.0), acc(0.0), q0(0), nq(0) {}
+      : a(args), lds(l), alpha(0.f), inv_alpha(0.0), cg(0.0), acc(0.0), q0(0), nq(0),
+        ext(extremes_init()), want_largest(args.fin.big_out != nullptr) {}
   __device__ __forceinline__ void begin_tile(uint32_t blk) {
     alpha = a.alpha[blk];
     inv_alpha = 1.0 / (double)alpha;
     cg = 1.0 / ((double)a.n * (double)alpha);
     acc = 0.0;
+    ext = extremes_init();
   }
   __device__ __forceinline__ void scalar(uint64_t j) {
     int32_t S = 0;
@@ -1061,6 +1194,7 @@ struct DianaOp {
       hl[j] = shift_local(hv, q, inv_alpha);
       S += q;
     }
+    if (want_largest) note(ext, S);
     float hj = a.h[j];
     a.x[j] = diana_coord(a.x[j], hj, S, cg, a.eta, acc);
     a.h[j] = hj;
@@ -1129,6 +1263,7 @@ struct DianaOp {
     for (; i + 4 <= a.n; i += 4) workers<4>(i, ql, S);
     if (a.n - i >= 2) { workers<2>(i, ql, S); i += 2; }
     if (a.n - i >= 1) workers<1>(i, ql, S);
+    if (want_largest) note(ext, S);
     vf4 xn;
     float h0 = hv.x, h1 = hv.y, h2 = hv.z, h3 = hv.w;
     xn.x = diana_coord(xv.x, h0, S.x, cg, a.eta, acc);
@@ -1141,6 +1276,10 @@ struct DianaOp {
   __device__ __forceinline__ void end_tile(uint32_t t, uint32_t iter) {
     const double total = block_sum(acc, lds, iter & 1u);
     if (threadIdx.x == 0) a.fin.norm_partial[t] = total;
+    if (want_largest) {
+      const uint32_t best = block_max(magnitude(ext), lds, iter & 1u);
+      if (threadIdx.x == 0) a.fin.big_partial[t] = best;
+    }
   }
 };
 
@@ -1703,16 +1842,19 @@ constexpr uint32_t kTwoLevelFrom = 2 * kChunk;
 
 hipError_t finish(hipStream_t stream, const Finish& fin_in, bool with_norm, bool with_sat) {
   Finish fin = fin_in;
-  if (with_norm && fin.B == 1 && fin.num_tiles > kTwoLevelFrom) {
+  const bool with_big = fin.big_out != nullptr;
+  if ((with_norm || with_big) && fin.B == 1 && fin.num_tiles > kTwoLevelFrom) {
     const uint32_t chunks = (fin.num_tiles + kChunk - 1) / kChunk;
-    hipLaunchKernelGGL(k_finish_chunks, dim3(chunks), dim3(kThreads), 0, stream, fin.norm_partial,
-                       fin.num_tiles, kChunk, fin.norm_mid);
+    hipLaunchKernelGGL(k_finish_chunks, dim3(chunks), dim3(kThreads), 0, stream,
+                       with_norm ? fin.norm_partial : nullptr, fin.num_tiles, kChunk, fin.norm_mid,
+                       with_big ? fin.big_partial : nullptr, fin.big_mid);
     const hipError_t e = after_launch();
     if (e != hipSuccess) return e;
     fin.norm_partial = fin.norm_mid;
+    fin.big_partial = fin.big_mid;
     fin.num_tiles = chunks;
   }
-  const dim3 grid((with_norm ? fin.B : 0u) + (with_sat ? fin.n : 0u)), block(kThreads);
+  const dim3 grid(((with_norm || with_big) ? fin.B : 0u) + (with_sat ? fin.n : 0u)), block(kThreads);
   if (with_norm && with_sat) hipLaunchKernelGGL((k_finish<true, true>), grid, block, 0, stream, fin);
   else if (with_norm) hipLaunchKernelGGL((k_finish<true, false>), grid, block, 0, stream, fin);
   else hipLaunchKernelGGL((k_finish<false, true>), grid, block, 0, stream, fin);
@@ -1791,13 +1933,20 @@ hipError_t launch_compress_sum(const TileMap& tm, const LaunchShape& ls, uint32_
   AggregateArgs a{tm, rs, n, alpha, 0.0, nullptr, sum_out, nullptr, 0.0, 0.0, 0, fin, grads};
   const dim3 grid(ls.grid), block(kThreads);
   const bool random = rs.rounding == INTSGD_ROUND_STOCHASTIC;
+  const bool largest = fin.big_out != nullptr;
+#define INTSGD_LAUNCH_F1(R, XS)                                                                        \
+  do {                                                                                                 \
+    if (largest) launch_sweep(ls, (k_aggregate<R, false, false, XS, true>), grid, block, ls.lds_reserve, a); \
+    else launch_sweep(ls, (k_aggregate<R, false, false, XS, false>), grid, block, ls.lds_reserve, a);  \
+  } while (0)
   if (sums_stay_resident(tm.d)) {
-    if (random) launch_sweep(ls, (k_aggregate<1, false, false, kWriteThrough>), grid, block, ls.lds_reserve, a);
-    else launch_sweep(ls, (k_aggregate<0, false, false, kWriteThrough>), grid, block, ls.lds_reserve, a);
+    if (random) INTSGD_LAUNCH_F1(1, kWriteThrough);
+    else INTSGD_LAUNCH_F1(0, kWriteThrough);
   } else {      // streamed: the sums would only push x out of the cache
-    if (random) launch_sweep(ls, (k_aggregate<1, false, false, kStreamOut>), grid, block, ls.lds_reserve, a);
-    else launch_sweep(ls, (k_aggregate<0, false, false, kStreamOut>), grid, block, ls.lds_reserve, a);
+    if (random) INTSGD_LAUNCH_F1(1, kStreamOut);
+    else INTSGD_LAUNCH_F1(0, kStreamOut);
   }
+#undef INTSGD_LAUNCH_F1
   hipError_t e = after_launch();
   if (e != hipSuccess) return e;
   return finish(ls.stream, fin, false, true);
@@ -1833,10 +1982,16 @@ hipError_t launch_step_fused(const TileMap& tm, const LaunchShape& ls, uint32_t 
   // faster with nt + sc1 stores than with plain write-through ones.
   a.keep_quads = state_keep_quads(tm.d, mom != nullptr);
   const bool big = a.keep_quads != ~0ull;
-#define INTSGD_LAUNCH_AGG(R, M)                                                                   \
-  do {                                                                                            \
-    if (big) launch_sweep(ls, (k_aggregate<R, true, M, kStreamOut>), grid, block, ls.lds_reserve, a); \
-    else launch_sweep(ls, (k_aggregate<R, true, M, kWriteThrough>), grid, block, ls.lds_reserve, a);  \
+  const bool largest = fin.big_out != nullptr;
+#define INTSGD_LAUNCH_AGG_L(R, M, L)                                                                   \
+  do {                                                                                                 \
+    if (big) launch_sweep(ls, (k_aggregate<R, true, M, kStreamOut, L>), grid, block, ls.lds_reserve, a); \
+    else launch_sweep(ls, (k_aggregate<R, true, M, kWriteThrough, L>), grid, block, ls.lds_reserve, a);  \
+  } while (0)
+#define INTSGD_LAUNCH_AGG(R, M)              \
+  do {                                       \
+    if (largest) INTSGD_LAUNCH_AGG_L(R, M, true); \
+    else INTSGD_LAUNCH_AGG_L(R, M, false);   \
   } while (0)
   if (mom) {
     if (random) INTSGD_LAUNCH_AGG(1, true);
@@ -1846,6 +2001,7 @@ hipError_t launch_step_fused(const TileMap& tm, const LaunchShape& ls, uint32_t 
     else INTSGD_LAUNCH_AGG(0, false);
   }
 #undef INTSGD_LAUNCH_AGG
+#undef INTSGD_LAUNCH_AGG_L
   hipError_t e = after_launch();
   if (e != hipSuccess) return e;
   return finish(ls.stream, fin, true, true);

@@ -153,6 +153,19 @@ def test_launch_options_are_validated_per_descriptor():
     assert P.intsgd_workspace_bytes(desc) == a
 
 
+def test_largest_sum_output_is_validated():
+    """The optional per-block output of the descriptor: NULL or a 4-byte aligned device pointer."""
+    desc = P.Desc(1000, 4)
+    need = P.intsgd_workspace_bytes(desc)
+    desc.c.largest_sum = FAKE + 2
+    assert call_step_fused(desc) == EALIGN
+    assert lib.intsgd_prepare(desc.ref()) == EALIGN
+    assert P.intsgd_workspace_bytes(desc) == 0
+    desc.c.largest_sum = FAKE + 4
+    assert call_step_fused(desc, ws=None) == EWORKSPACE          # passed validation
+    assert P.intsgd_workspace_bytes(desc) == need                # the size does not depend on it
+
+
 def test_two_callers_hold_different_options():
     """No process-wide state: the same query answers per descriptor, in any interleaving."""
     big = 1 << 22

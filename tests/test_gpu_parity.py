@@ -381,6 +381,8 @@ def whole_vector_check(w: W.Workload, steps, mode="fused", chunk=1 << 26, launch
     r_lock, ad, _, _ = oracle.next_alpha(w.first_normsq, np.zeros(w.num_blocks), **kw)
     assert rel_err(host(st.alpha), ad) <= ALPHA_RTOL
     total_sat = 0
+    largest_gpu = torch.full((w.num_blocks,), -1, dtype=torch.int32, device=DEV)
+    desc.largest_sum = largest_gpu          # the largest |S_j| per block rides along
     with ThreadPoolExecutor(ORACLE_THREADS) as pool:
         for k in range(1, steps + 1):
             _, rows = W.make_gradients(w, k, DEV, out=buf)
@@ -393,6 +395,7 @@ def whole_vector_check(w: W.Workload, steps, mode="fused", chunk=1 << 26, launch
             torch.cuda.synchronize()
             sat = np.zeros(w.n, np.uint64)
             normsq = np.zeros(w.num_blocks)
+            largest = np.zeros(w.num_blocks, np.uint32)
             for c0 in range(0, w.d, chunk):
                 c1 = min(w.d, c0 + chunk)
                 xn, S, sat_c, ns_c = oracle_step_sliced(
@@ -404,7 +407,9 @@ def whole_vector_check(w: W.Workload, steps, mode="fused", chunk=1 << 26, launch
                     assert np.array_equal(host(sum_buf[c0:c1]), S), "S[%d:%d] at step %d" % (c0, c1, k)
                 sat += sat_c
                 normsq += ns_c
+                oracle.max_abs_sum(S, j0=c0, offsets=off_np, B=w.num_blocks, out=largest)
             del x_old
+            assert host(largest_gpu).view(np.uint32).tolist() == largest.tolist(), "largest |S| at step %d" % k
             assert u64(st.sat_count).tolist() == sat.tolist(), "clip counts at step %d" % k
             assert rel_err(host(st.norm_sq), normsq) <= NORM_RTOL, "norm at step %d" % k
             total_sat += int(sat.sum())
