@@ -206,6 +206,20 @@ def copy_probe(mib):
                                      "write_bytes_per_launch": n * 4}}))
 
 
+def device_state():
+    """Clock and power mode as rocm-smi shows them (a child process; sampled right after the
+    timed work, so sclk may already have dropped back), or None when the tool is not there."""
+    import subprocess
+    try:
+        out = subprocess.run(["rocm-smi", "--showclocks", "--showperflevel", "--json"], timeout=20,
+                             stdout=subprocess.PIPE, stderr=subprocess.DEVNULL).stdout.decode()
+        card = json.loads(out[out.index("{"):])["card0"]
+        return {"mclk": card.get("mclk clock speed:"), "sclk_after_run": card.get("sclk clock speed:"),
+                "performance_level": card.get("Performance Level")}
+    except Exception:        # noqa: BLE001 (reporting aid only)
+        return None
+
+
 def median(v):
     s = sorted(v)
     return s[len(s) // 2] if len(s) % 2 else 0.5 * (s[len(s) // 2 - 1] + s[len(s) // 2])
@@ -531,6 +545,7 @@ def main():
     arena = None if args.no_placement else P.Arena("cuda:0", keep_free=8 << 30)
     if args.config:
         result, _ = run_workload(args, hip, args.config, cpu_legs=big_legs if cpu else None, arena=arena)
+        result["device"] = device_state()
         print(json.dumps(result))
         return
     result, head_entry = run_workload(args, hip, HEADLINE_CONFIG, cpu_legs=big_legs if cpu else None,
@@ -542,6 +557,7 @@ def main():
         per_config.append(entry)
     per_config.append(head_entry)
     result["per_config"] = per_config
+    result["device"] = device_state()
     print(json.dumps(result))
 
 

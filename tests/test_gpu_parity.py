@@ -339,6 +339,15 @@ def test_config3_full_size_two_steps():
     assert sat > 0
 
 
+def test_config3_full_size_with_the_papers_clip_rule():
+    """Workload 3 with L = floor(127 / n) = 15 (Section 5.1: clip locally so that the int8
+    AGGREGATE cannot overflow) instead of L = 127: many more values clip, counts stay exact."""
+    import dataclasses
+    w = W.config(3)
+    sat = lockstep_run(dataclasses.replace(w, clip=127 // w.n), steps=1, free_running=False)
+    assert sat > 0
+
+
 ORACLE_THREADS = 16          # a one-GPU box's share of its host
 
 
