@@ -78,6 +78,8 @@ def parse():
     ap.add_argument("--place", default="", metavar="FIELD=REGION,...",
                     help="move state fields (x, m, h, h_local, sum, q, x_old) to HBM region 0, 1 or 2 "
                          "of the arena (the gradient sets fill region 0, then 2)")
+    ap.add_argument("--workers", type=int, default=0,
+                    help="override the workload's worker count n (1 = the per-GPU shape of a real all-reduce)")
     ap.add_argument("--largest-sum", action="store_true",
                     help="also ask every step for the largest |S_j| per block (reported for the last step)")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
@@ -236,6 +238,14 @@ def run_workload(args, hip, cfg, *, cpu_legs, arena):
     dev = "cuda:0"
     rounding = {"config": None, "nearest": 0, "stochastic": 1}[args.rounding]
     w = W.config(cfg, per_bucket=not args.global_alpha, rounding=rounding)
+    if args.workers and args.workers != w.n:
+        # the same recipe with another worker count; --workers 1 is the shape a GPU sees around a
+        # real all-reduce (its own gradient only)
+        import dataclasses
+        w = dataclasses.replace(
+            w, n=args.workers, name="%s-n%d" % (w.name, args.workers),
+            clip=w.clip if w.wire == 8 else P.default_clip(args.workers),
+            first_normsq=[v * w.n / args.workers for v in w.first_normsq])
     steps = args.steps or DEFAULT_STEPS[cfg]
     opts = P.LaunchOpts(args.tile, args.grid, args.wgs_per_cu, args.two_phase)
     desc = P.Desc(w.d, w.n, rounding=w.rounding, wire=w.wire, clip=w.clip, seed=w.philox_seed,
