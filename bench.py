@@ -352,6 +352,33 @@ def run_workload(args, hip, cfg, *, cpu_legs, arena):
             P.intsgd_update_norm(desc, x, v["x_old"], st.norm_sq, st.workspace)
             st.next_alpha()
 
+    # Evidence for the layout, taken at set-up (untimed): the same step with x moved into the
+    # first gradient set's region.  Only for a plain fused step on a state the cache cannot hold.
+    placement_check = None
+    if (arena is not None and args.mode == "fused" and not (args.momentum or args.diana or args.heuristic)
+            and 4 * w.d > (256 << 20) and state_region["x"] != set_regions[0]
+            and arena.free_in(set_regions[0]) >= 4 * w.d):
+        beside = dict(state)
+        beside["x"] = arena.take(4 * w.d, set_regions[0]).view(torch.float32)
+        beside["x"].zero_()
+        st.start(w.first_normsq)
+        e0, e1 = hip.create(), hip.create()
+        placement_check = {}
+        for label, v in (("x_apart_ms", state), ("x_beside_gradients_ms", beside),
+                         ("x_apart_again_ms", state)):
+            for _ in range(3):            # the cache-resident prefix of x has to settle first
+                run_step(v, sets[0][1], 1)
+            hip.record(e0, stream)
+            for _ in range(3):
+                run_step(v, sets[0][1], 1)
+            hip.record(e1, stream)
+            torch.cuda.synchronize()
+            placement_check[label] = hip.elapsed_ms(e0, e1) / 3
+        hip.destroy(e0)
+        hip.destroy(e1)
+        state["x"].zero_()
+        del beside
+
     x = W.make_params(w, dev, out=state["x"])
     torch.cuda.synchronize()
 
@@ -492,6 +519,7 @@ def run_workload(args, hip, cfg, *, cpu_legs, arena):
                           {"rule": "one arena over the free device memory, read as three regions of "
                                    "a third of the HBM each: gradient sets (only read) in one region, "
                                    "written state in another",
+                           "check_at_setup": placement_check,
                            "gradient_set_regions": set_regions,
                            "state_regions": {k: v for k, v in state_region.items() if k != "x0"}}),
         },
