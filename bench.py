@@ -297,11 +297,18 @@ def run_workload(args, hip, cfg, *, cpu_legs, arena):
     state, sets, set_regions = {}, [], []
     if arena is not None:
         arena.reset()
-        for name, numel, dt in fields:
-            state[name] = arena.take(nbytes(numel, dt), state_region[name]).view(dt)
+        for name, numel, dt in fields:      # the preferred region, or whichever has room
+            need = nbytes(numel, dt)
+            prefer = state_region[name]
+            region = next((r for r in (prefer, *range(P.HBM_REGIONS)) if arena.free_in(r) >= need), None)
+            assert region is not None, "the arena has no room for %s (%d bytes)" % (name, need)
+            state_region[name] = region
+            state[name] = arena.take(need, region).view(dt)
             state[name].zero_()
         for s_idx in range(want):
             region = next((r for r in (0, 2) if arena.free_in(r) >= set_bytes), None)
+            if region is None and not sets:      # a small arena: anywhere rather than nowhere
+                region = 1 if arena.free_in(1) >= set_bytes else None
             if region is None:
                 break
             buf = arena.take(set_bytes, region).view(torch.float32).view(w.n, stride)

@@ -60,6 +60,12 @@ Tuning effective_tuning(const intsgd_desc* desc) {
 // 3..8 workers, where a thread of the tile sweep has all its loads in one group and four
 // resident workgroups per CU stream as fast or faster (n = 8: 81-85 % against 78-82 %).
 constexpr uint64_t kMinPhasedD = 1ull << 22;
+// Far beyond the caches (workload 5: 635 K tiles) the sweeps that read the gradient streams run
+// 1-10 % faster when each XCD takes runs of 16 consecutive tiles instead of every eighth tile
+// (a1-a3 most, the fused sweep least); at 50 K tiles and below it makes no difference or costs
+// 0.5 %, and the decode kernels are slower with it at any size.
+constexpr uint32_t kXcdRunFromTiles = 1u << 17;
+constexpr uint32_t kXcdRunShift = 4;
 bool use_two_phase(const intsgd_desc* desc, const Tuning& t) {
   if (desc->num_blocks != 1 || desc->d < kMinPhasedD || t.two_phase == 1) return false;
   if (t.two_phase == 2) return true;
@@ -302,6 +308,10 @@ struct Tiling {
   const uint64_t* offsets_dev;
 };
 
+void use_xcd_runs(Tiling* t) {
+  if (t->tm.num_tiles >= kXcdRunFromTiles) t->tm.xcd_shift = kXcdRunShift;
+}
+
 // Dynamic LDS that makes exactly k workgroups fit a CU (0 when k is no cap).
 uint32_t lds_reserve_for(uint32_t k) {
   if (k == 0 || k >= 8) return 0;
@@ -339,6 +349,7 @@ intsgd_status make_tiling(const intsgd_desc* desc, void* stream, Tiling* t,
     t->tile_prefix = plan->tile_prefix;
     t->offsets_dev = plan->offsets_dev;
   }
+  t->tm.xcd_shift = 0;
   t->ls.grid = t->tm.num_tiles < tune.max_workgroups ? t->tm.num_tiles : tune.max_workgroups;
   t->ls.lds_reserve = lds_reserve_for(tune.workgroups_per_cu);
   t->ls.stream = static_cast<hipStream_t>(stream);
@@ -440,6 +451,7 @@ intsgd_status step_fused_impl(const intsgd_desc* desc, const float* const* grads
   if (!use_static_scratch) INTSGD_TRY(validate_workspace(desc, workspace, workspace_bytes));
   Tiling t;
   INTSGD_TRY(make_tiling(desc, hip_stream, &t, 0, /*may_build=*/!use_static_scratch));
+  use_xcd_runs(&t);
   PhasedShape ps{0};
   bool phased = false;
   INTSGD_TRY(two_phase_shape(desc, &ps, &phased));
@@ -505,6 +517,7 @@ intsgd_status intsgd_compress(const intsgd_desc* desc, const float* const* grads
   INTSGD_TRY(validate_workspace(desc, workspace, workspace_bytes));
   Tiling t;
   INTSGD_TRY(make_tiling(desc, hip_stream, &t, compress_tile(desc)));
+  use_xcd_runs(&t);
   WorkerPtrs g;
   WorkerOutPtrs q;
   fill_ptrs(&g, (const void* const*)grads, desc->n);
@@ -625,6 +638,7 @@ intsgd_status intsgd_compress_sum(const intsgd_desc* desc, const float* const* g
   INTSGD_TRY(validate_workspace(desc, workspace, workspace_bytes));
   Tiling t;
   INTSGD_TRY(make_tiling(desc, hip_stream, &t));
+  use_xcd_runs(&t);
   WorkerPtrs g;
   fill_ptrs(&g, (const void* const*)grads, desc->n);
   Finish fin = make_finish(desc, t, workspace, nullptr, sat_count);
@@ -727,6 +741,7 @@ intsgd_status intsgd_diana_step(const intsgd_desc* desc, const float* const* gra
   INTSGD_TRY(validate_workspace(desc, workspace, workspace_bytes));
   Tiling t;
   INTSGD_TRY(make_tiling(desc, hip_stream, &t));
+  use_xcd_runs(&t);
   WorkerPtrs g;
   WorkerOutPtrs hl;
   fill_ptrs(&g, (const void* const*)grads, desc->n);

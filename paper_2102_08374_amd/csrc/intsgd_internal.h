@@ -24,6 +24,7 @@ struct TileMap {
   uint32_t tile;
   uint32_t num_tiles;
   const TileEntry* table;
+  uint32_t xcd_shift;    // 0, or log2 of the run of consecutive tiles each XCD takes (see drive_tiles)
 };
 
 // Per-worker device pointers, passed to kernels by value in the kernarg segment.
