@@ -60,11 +60,13 @@ Tuning effective_tuning(const intsgd_desc* desc) {
 // 3..8 workers, where a thread of the tile sweep has all its loads in one group and four
 // resident workgroups per CU stream as fast or faster (n = 8: 81-85 % against 78-82 %).
 constexpr uint64_t kMinPhasedD = 1ull << 22;
-// Far beyond the caches (workload 5: 635 K tiles) the sweeps that read the gradient streams run
-// 1-10 % faster when each XCD takes runs of 16 consecutive tiles instead of every eighth tile
-// (a1-a3 most, the fused sweep least); at 50 K tiles and below it makes no difference or costs
-// 0.5 %, and the decode kernels are slower with it at any size.
-constexpr uint32_t kXcdRunFromTiles = 1u << 17;
+// Consecutive workgroups go to the 8 XCDs in turn.  The sweeps that read the gradient streams run
+// faster when each XCD takes runs of 16 consecutive tiles instead of every eighth tile: a1-a3 by
+// 3 % (108 M coordinates) to 10 % (1.3 G), F1, the momentum form, IntDIANA and the nearest-even
+// fused sweep by 1-3 %.  The randomized fused sweep gains 1.5-2 % at 635 K tiles, 1 % at 53 K and
+// nothing at 12 K (-0.3 %); the decode kernels are slower with runs at any size.
+constexpr uint32_t kXcdRunFromTiles = 1u << 10;
+constexpr uint32_t kXcdRunFromTilesRandomFused = 1u << 15;
 constexpr uint32_t kXcdRunShift = 4;
 bool use_two_phase(const intsgd_desc* desc, const Tuning& t) {
   if (desc->num_blocks != 1 || desc->d < kMinPhasedD || t.two_phase == 1) return false;
@@ -308,8 +310,8 @@ struct Tiling {
   const uint64_t* offsets_dev;
 };
 
-void use_xcd_runs(Tiling* t) {
-  if (t->tm.num_tiles >= kXcdRunFromTiles) t->tm.xcd_shift = kXcdRunShift;
+void use_xcd_runs(Tiling* t, uint32_t from_tiles = kXcdRunFromTiles) {
+  if (t->tm.num_tiles >= from_tiles) t->tm.xcd_shift = kXcdRunShift;
 }
 
 // Dynamic LDS that makes exactly k workgroups fit a CU (0 when k is no cap).
@@ -451,7 +453,8 @@ intsgd_status step_fused_impl(const intsgd_desc* desc, const float* const* grads
   if (!use_static_scratch) INTSGD_TRY(validate_workspace(desc, workspace, workspace_bytes));
   Tiling t;
   INTSGD_TRY(make_tiling(desc, hip_stream, &t, 0, /*may_build=*/!use_static_scratch));
-  use_xcd_runs(&t);
+  use_xcd_runs(&t, (desc->rounding == INTSGD_ROUND_STOCHASTIC && mom == nullptr)
+                       ? kXcdRunFromTilesRandomFused : kXcdRunFromTiles);
   PhasedShape ps{0};
   bool phased = false;
   INTSGD_TRY(two_phase_shape(desc, &ps, &phased));

@@ -447,16 +447,17 @@ template <class Op>
 __device__ __forceinline__ void drive_tiles(const TileMap& tm, Op& op) {
   const uint32_t tid = threadIdx.x;
   uint32_t iter = 0;
-  for (uint32_t t0 = blockIdx.x; t0 < tm.num_tiles; t0 += gridDim.x, ++iter) {
-    uint32_t t = t0;
-    if (tm.xcd_shift != 0u) {
-      // Consecutive workgroups go to the 8 XCDs in turn.  Within every group of 8 << xcd_shift
-      // tiles, give each XCD a run of 1 << xcd_shift consecutive tiles instead of every eighth
-      // one (a permutation of the group; an incomplete last group keeps the plain order).
-      const uint32_t gs = 3u + tm.xcd_shift;
-      const uint32_t g = t0 >> gs, r = t0 & ((1u << gs) - 1u);
-      if (((g + 1u) << gs) <= tm.num_tiles) t = (g << gs) + ((r & 7u) << tm.xcd_shift) + (r >> 3);
-    }
+  uint32_t first = blockIdx.x;
+  if (tm.xcd_shift != 0u && gridDim.x == tm.num_tiles) {
+    // One tile per workgroup, and consecutive workgroups go to the 8 XCDs in turn.  Within every
+    // group of 8 << xcd_shift tiles, give each XCD a run of 1 << xcd_shift consecutive tiles
+    // instead of every eighth one (a permutation of the group; an incomplete last group keeps
+    // the plain order).  Done before the loop so that nothing of it stays live inside.
+    const uint32_t gs = 3u + tm.xcd_shift;
+    const uint32_t g = first >> gs, r = first & ((1u << gs) - 1u);
+    if (((g + 1u) << gs) <= tm.num_tiles) first = (g << gs) + ((r & 7u) << tm.xcd_shift) + (r >> 3);
+  }
+  for (uint32_t t = first; t < tm.num_tiles; t += gridDim.x, ++iter) {
     const Tile tl = locate(tm, t);
     const uint64_t s = tl.start, e = tl.start + tl.len;
     uint64_t a = (s + 3) & ~(uint64_t)3;
