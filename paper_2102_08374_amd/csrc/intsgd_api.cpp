@@ -55,10 +55,11 @@ Tuning effective_tuning(const intsgd_desc* desc) {
 }
 
 // The two-phase sweep needs one block and enough coordinates to give every CU a chunk.
-// Automatic choice: nearest-even rounding only (randomized rounding is co-bound by the
-// integer ALU in its read phase and gains nothing from separating the phases), and not for
-// 3..8 workers, where a thread of the tile sweep has all its loads in one group and four
-// resident workgroups per CU stream as fast or faster (n = 8: 81-85 % against 78-82 %).
+// Automatic choice: nearest-even rounding only (randomized rounding fills the read phase with
+// arithmetic and gains nothing from separating the phases), and only up to 5 workers: a thread
+// of the tile sweep then has too few loads in flight (n = 1: 50-52 % of peak against 69-74 %,
+// n = 4: 79 % against 81-82 %), while from 6 workers on the tile sweep streams as fast or
+// faster (n = 8: 87-89 % against 83 %, n = 16: 87 % against 85 %).
 constexpr uint64_t kMinPhasedD = 1ull << 22;
 // Consecutive workgroups go to the 8 XCDs in turn.  The sweeps that read the gradient streams run
 // faster when each XCD takes runs of 16 consecutive tiles instead of every eighth tile: a1-a3 by
@@ -71,7 +72,7 @@ constexpr uint32_t kXcdRunShift = 4;
 bool use_two_phase(const intsgd_desc* desc, const Tuning& t) {
   if (desc->num_blocks != 1 || desc->d < kMinPhasedD || t.two_phase == 1) return false;
   if (t.two_phase == 2) return true;
-  return desc->rounding == INTSGD_ROUND_NEAREST_EVEN && (desc->n > 8 || desc->n <= 2);
+  return desc->rounding == INTSGD_ROUND_NEAREST_EVEN && desc->n <= 5;
 }
 
 thread_local std::string t_hip_error;

@@ -938,7 +938,7 @@ def test_graph_replay_of_a_whole_step(d):
     replayed with fresh gradients: every replay equals the eager result (no memset nodes,
     no allocation, nothing zeroed between launches).  Both forms of the sweep."""
     w = W.config(2).scaled(d)
-    desc = P.Desc(w.d, w.n, clip=w.clip)
+    desc = P.Desc(w.d, w.n, clip=w.clip, opts=opts(two_phase=2) if d >= (1 << 22) else None)
     assert P.intsgd_fused_step_form(desc) == (2 if d >= (1 << 22) else 1)
     P.intsgd_prepare(desc)
     st_g = Stepper(desc, eta=w.eta, device=DEV)
