@@ -82,6 +82,8 @@ typedef enum {
  * are not part of the numerical contract: results do not depend on them except for the
  * summation order of the norm.  Read during the call only.
  *   tile_coords        coordinates per work tile, a multiple of 1024 in [1024, 65536]
+ *                      (automatic: per kernel, 1024 to 16384; the sweeps over the n gradient
+ *                      streams take 8192 at n = 1, 4096 up to n = 5, else 2048)
  *   max_workgroups     cap of the launch grid, in [1, 1048576]; tiles beyond it are
  *                      taken by striding
  *   workgroups_per_cu  residency cap of the streaming kernels, 2..8 (8 = no cap)
@@ -89,8 +91,8 @@ typedef enum {
  *                      intsgd_step_momentum, intsgd_compress_sum; one block, d >= 2^22):
  *                      1 = always the tile sweep, 2 = always the two-phase sweep (gradient
  *                      reads, then the write-back, with the integer sums held in registers
- *                      in between), 0 = automatic (two-phase for nearest-even rounding
- *                      with more than 8 or fewer than 3 workers).
+ *                      in between), 0 = automatic (the tile sweep: it measured as fast or
+ *                      faster for every worker count).
  *                      intsgd_int_sum follows it too: automatic = two-phase for any wire
  *                      (d >= 2^22), 1 = its tile form
  *   start_event, stop_event   profiling aid: hipEvent_t handles passed as void*, both set or
@@ -266,7 +268,7 @@ INTSGD_API intsgd_status intsgd_step_fused_next_alpha(const intsgd_desc* desc,
  * with its scratch in a static device array of INTSGD_STATIC_SCRATCH_BYTES that every GPU
  * running the library holds until the process ends.  Same arguments (minus the workspace)
  * and the same results.  It calls no hipMalloc / hipFree and no allocating routine.
- *   - The scratch must hold 16 + 8 n bytes per work tile (2048 coordinates, or
+ *   - The scratch must hold 16 + 8 n bytes per work tile (the automatic tile of the sweep, or
  *     desc->launch->tile_coords), or per compute unit when the call takes the two-phase
  *     form, plus 1 KiB; a larger problem is refused with INTSGD_EWORKSPACE and nothing is
  *     launched.  32 MiB covers d = 9.0e8 at n = 8 (d = 1.3e9 with tile_coords = 4096),

@@ -54,12 +54,13 @@ Tuning effective_tuning(const intsgd_desc* desc) {
   return t;
 }
 
-// The two-phase sweep needs one block and enough coordinates to give every CU a chunk.
-// Automatic choice: nearest-even rounding only (randomized rounding fills the read phase with
-// arithmetic and gains nothing from separating the phases), and only up to 5 workers: a thread
-// of the tile sweep then has too few loads in flight (n = 1: 50-52 % of peak against 69-74 %,
-// n = 4: 79 % against 81-82 %), while from 6 workers on the tile sweep streams as fast or
-// faster (n = 8: 87-89 % against 83 %, n = 16: 87 % against 85 %).
+// The two-phase sweep needs one block and enough coordinates to give every CU a chunk.  It is
+// never the automatic choice: with the XCD-aware tile order and a tile sized by the worker
+// count the tile sweep streams as fast or faster for every n measured (nearest-even, d = 25.6 M
+// and 108 M; n = 1: 75-81 % of peak against 69-75 %, n = 2: 81-83 % against 77-81 %, n = 5:
+// 84-85 % against 80-81 %, n = 8: 87-89 % against 83 %, n = 16: 87 % against 85 %; n = 4 at
+// 108 M is the one tie), and randomized rounding fills the read phase with arithmetic anyway.
+// Callers ask for it with two_phase = 2.
 constexpr uint64_t kMinPhasedD = 1ull << 22;
 // Consecutive workgroups go to the 8 XCDs in turn.  The sweeps that read the gradient streams run
 // faster when each XCD takes runs of 16 consecutive tiles instead of every eighth tile: a1-a3 by
@@ -72,7 +73,7 @@ constexpr uint32_t kXcdRunShift = 4;
 bool use_two_phase(const intsgd_desc* desc, const Tuning& t) {
   if (desc->num_blocks != 1 || desc->d < kMinPhasedD || t.two_phase == 1) return false;
   if (t.two_phase == 2) return true;
-  return desc->rounding == INTSGD_ROUND_NEAREST_EVEN && desc->n <= 5;
+  return false;
 }
 
 thread_local std::string t_hip_error;
@@ -330,6 +331,22 @@ uint32_t compress_tile(const intsgd_desc* desc) {
   return random ? 8192u : 2048u;
 }
 
+// Automatic tiles of the other kernels (an explicit tile_coords in the launch options wins).
+// Measured on MI355X at d = 108 M and d = 25.6 M, fraction of the HBM peak:
+// the sweeps over the n gradient streams (F3, F1, momentum form) want more coordinates per
+// workgroup the fewer streams a thread has to load from: n = 1: 52 % with 2048, 77 % with 4096,
+// 81 % with 8192, 80 % with 16384; n = 2: 66 / 83 / 82 %; n = 4: 79 / 81 / 80 %; n = 5: 84 % with
+// 4096, 80 % with 8192; n = 6 and 8: 84 and 87 % with 2048, 81 % with 4096.
+uint32_t sweep_tile(const intsgd_desc* desc) {
+  return desc->n == 1 ? 8192u : desc->n <= 5 ? 4096u : 2048u;
+}
+// a5-a6, F2 and a7 (two loads and at most one store per coordinate; d = 108 M): 209 / 194 / 201 us,
+// 233 / 195 / 200 us and 149 / 128 / 137 us with 2048 / 4096 / 8192.
+constexpr uint32_t kDecodeTile = 4096;
+// Algorithm 3's sweep has 2n + 2 loads and n + 2 stores per coordinate: at n = 8, 1.96 ms with
+// 1024, 2.04 ms with 2048, 2.07 ms with 4096.
+uint32_t diana_tile(const intsgd_desc* desc) { return desc->n >= 8 ? 1024u : 2048u; }
+
 intsgd_status make_tiling(const intsgd_desc* desc, void* stream, Tiling* t,
                           uint32_t automatic_tile = 0, bool may_build = true) {
   const Tuning tune = effective_tuning(desc);
@@ -453,7 +470,7 @@ intsgd_status step_fused_impl(const intsgd_desc* desc, const float* const* grads
   INTSGD_TRY(validate_momentum(mom));
   if (!use_static_scratch) INTSGD_TRY(validate_workspace(desc, workspace, workspace_bytes));
   Tiling t;
-  INTSGD_TRY(make_tiling(desc, hip_stream, &t, 0, /*may_build=*/!use_static_scratch));
+  INTSGD_TRY(make_tiling(desc, hip_stream, &t, sweep_tile(desc), /*may_build=*/!use_static_scratch));
   use_xcd_runs(&t, (desc->rounding == INTSGD_ROUND_STOCHASTIC && mom == nullptr)
                        ? kXcdRunFromTilesRandomFused : kXcdRunFromTiles);
   PhasedShape ps{0};
@@ -498,11 +515,13 @@ intsgd_status intsgd_prepare(const intsgd_desc* desc) {
   }
   if (desc->num_blocks == 1) return INTSGD_OK;
   const DevicePlan* plan = nullptr;
-  const uint32_t sweep_tile = effective_tuning(desc).tile_coords;
-  INTSGD_TRY(get_plan(desc, sweep_tile, &plan));
-  // the compress kernel picks its own tile unless the tuning fixes one
-  const uint32_t other = requested_tuning(desc).tile_coords == 0 ? compress_tile(desc) : sweep_tile;
-  return other == sweep_tile ? INTSGD_OK : get_plan(desc, other, &plan);
+  const uint32_t fixed = requested_tuning(desc).tile_coords;
+  if (fixed != 0) return get_plan(desc, fixed, &plan);
+  // every automatic tile an entry point may pick for this descriptor
+  const uint32_t tiles[] = {sweep_tile(desc), compress_tile(desc), kDecodeTile, diana_tile(desc),
+                            effective_tuning(desc).tile_coords};
+  for (uint32_t tile : tiles) INTSGD_TRY(get_plan(desc, tile, &plan));
+  return INTSGD_OK;
 }
 
 void intsgd_release(void) {
@@ -569,7 +588,7 @@ intsgd_status intsgd_decode_update(const intsgd_desc* desc, const int32_t* sum,
   if (alpha == nullptr) return INTSGD_EINVAL;
   INTSGD_TRY(validate_rule(0.0, 0.0, eta));
   Tiling t;
-  INTSGD_TRY(make_tiling(desc, hip_stream, &t));
+  INTSGD_TRY(make_tiling(desc, hip_stream, &t, kDecodeTile));
   return done(launch_decode_update(t.tm, t.ls, desc->n, sum, alpha, eta, x, gtilde_out));
 }
 
@@ -582,7 +601,7 @@ intsgd_status intsgd_update_norm(const intsgd_desc* desc, const float* x_new, co
   if (norm_sq_out == nullptr) return INTSGD_EINVAL;
   INTSGD_TRY(validate_workspace(desc, workspace, workspace_bytes));
   Tiling t;
-  INTSGD_TRY(make_tiling(desc, hip_stream, &t));
+  INTSGD_TRY(make_tiling(desc, hip_stream, &t, kDecodeTile));
   return done(launch_update_norm(t.tm, t.ls, x_new, x_old,
                                  make_finish(desc, t, workspace, norm_sq_out, nullptr)));
 }
@@ -641,7 +660,7 @@ intsgd_status intsgd_compress_sum(const intsgd_desc* desc, const float* const* g
   if (alpha == nullptr || sat_count == nullptr) return INTSGD_EINVAL;
   INTSGD_TRY(validate_workspace(desc, workspace, workspace_bytes));
   Tiling t;
-  INTSGD_TRY(make_tiling(desc, hip_stream, &t));
+  INTSGD_TRY(make_tiling(desc, hip_stream, &t, sweep_tile(desc)));
   use_xcd_runs(&t);
   WorkerPtrs g;
   fill_ptrs(&g, (const void* const*)grads, desc->n);
@@ -667,7 +686,7 @@ intsgd_status intsgd_decode_update_norm(const intsgd_desc* desc, const int32_t* 
   INTSGD_TRY(validate_rule(0.0, 0.0, eta));
   INTSGD_TRY(validate_workspace(desc, workspace, workspace_bytes));
   Tiling t;
-  INTSGD_TRY(make_tiling(desc, hip_stream, &t));
+  INTSGD_TRY(make_tiling(desc, hip_stream, &t, kDecodeTile));
   return done(launch_decode_update_norm(t.tm, t.ls, desc->n, sum, alpha, eta, x, nullptr,
                                         make_finish(desc, t, workspace, norm_sq_out, nullptr)));
 }
@@ -686,7 +705,7 @@ intsgd_status intsgd_decode_update_momentum(const intsgd_desc* desc, const int32
   INTSGD_TRY(validate_momentum(&mom));
   INTSGD_TRY(validate_workspace(desc, workspace, workspace_bytes));
   Tiling t;
-  INTSGD_TRY(make_tiling(desc, hip_stream, &t));
+  INTSGD_TRY(make_tiling(desc, hip_stream, &t, kDecodeTile));
   return done(launch_decode_update_norm(t.tm, t.ls, desc->n, sum, alpha, eta, x, &mom,
                                         make_finish(desc, t, workspace, norm_sq_out, nullptr)));
 }
@@ -744,7 +763,7 @@ intsgd_status intsgd_diana_step(const intsgd_desc* desc, const float* const* gra
   if (r != nullptr) INTSGD_TRY(validate_rule(beta, eps, eta_next));
   INTSGD_TRY(validate_workspace(desc, workspace, workspace_bytes));
   Tiling t;
-  INTSGD_TRY(make_tiling(desc, hip_stream, &t));
+  INTSGD_TRY(make_tiling(desc, hip_stream, &t, diana_tile(desc)));
   use_xcd_runs(&t);
   WorkerPtrs g;
   WorkerOutPtrs hl;

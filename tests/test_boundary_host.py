@@ -173,7 +173,7 @@ def test_two_callers_hold_different_options():
     tile = P.Desc(big, 2, rounding=P.ROUND_NEAREST_EVEN, opts=P.LaunchOpts(two_phase=1))
     phased = P.Desc(big, 8, rounding=P.ROUND_STOCHASTIC, opts=P.LaunchOpts(two_phase=2))
     for _ in range(3):
-        assert P.intsgd_fused_step_form(auto) == 2
+        assert P.intsgd_fused_step_form(auto) == 1
         assert P.intsgd_fused_step_form(tile) == 1
         assert P.intsgd_fused_step_form(phased) == 2
     assert not hasattr(lib, "intsgd_set_tuning") and not hasattr(lib, "intsgd_tap_next_launch")
@@ -316,12 +316,13 @@ def test_host_alpha_rule_equals_the_oracle():
 def test_fused_step_form_policy():
     """Host-only query of which sweep the fused step would launch."""
     big, small = 1 << 22, (1 << 22) - 1
-    assert P.intsgd_fused_step_form(P.Desc(big, 4, rounding=P.ROUND_NEAREST_EVEN)) == 2
-    assert P.intsgd_fused_step_form(P.Desc(small, 4, rounding=P.ROUND_NEAREST_EVEN)) == 1
+    four = P.LaunchOpts(two_phase=2)
+    assert P.intsgd_fused_step_form(P.Desc(big, 4, rounding=P.ROUND_NEAREST_EVEN, opts=four)) == 2
+    assert P.intsgd_fused_step_form(P.Desc(small, 4, rounding=P.ROUND_NEAREST_EVEN, opts=four)) == 1
     assert P.intsgd_fused_step_form(P.Desc(big, 8, rounding=P.ROUND_STOCHASTIC)) == 1
     blocks = P.Desc(big, 8, rounding=P.ROUND_NEAREST_EVEN, block_offsets=[0, 1000, big])
     assert P.intsgd_fused_step_form(blocks) == 1
-    for n, form in [(1, 2), (2, 2), (3, 2), (5, 2), (6, 1), (8, 1), (9, 1), (16, 1), (128, 1)]:
+    for n, form in [(1, 1), (2, 1), (5, 1), (8, 1), (16, 1), (128, 1)]:       # automatic: the tile sweep
         assert P.intsgd_fused_step_form(P.Desc(big, n, rounding=P.ROUND_NEAREST_EVEN)) == form
     two = P.LaunchOpts(two_phase=2)
     assert P.intsgd_fused_step_form(P.Desc(big, 8, rounding=P.ROUND_STOCHASTIC, opts=two)) == 2

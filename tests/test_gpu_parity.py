@@ -671,7 +671,8 @@ def test_coordinates_beyond_32_bit_quad_index(rounding):
     if free < 160e9:
         pytest.skip("needs 160 GB of free device memory (the 288 GB MI355X)")
     d, n = (1 << 34) + 4099, 1
-    desc = P.Desc(d, n, rounding=rounding, clip=P.default_clip(1), seed=(5 << 32) | 7, step=3)
+    desc = P.Desc(d, n, rounding=rounding, clip=P.default_clip(1), seed=(5 << 32) | 7, step=3,
+                  opts=None if rounding == P.ROUND_STOCHASTIC else opts(two_phase=2))
     assert P.intsgd_fused_step_form(desc) == (1 if rounding == P.ROUND_STOCHASTIC else 2)
     ws = P.new_workspace(desc, DEV)
     g = torch.empty(d, dtype=torch.float32, device=DEV)
