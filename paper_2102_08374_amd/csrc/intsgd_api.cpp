@@ -343,9 +343,14 @@ uint32_t sweep_tile(const intsgd_desc* desc) {
 // a5-a6, F2 and a7 (two loads and at most one store per coordinate; d = 108 M): 209 / 194 / 201 us,
 // 233 / 195 / 200 us and 149 / 128 / 137 us with 2048 / 4096 / 8192.
 constexpr uint32_t kDecodeTile = 4096;
-// Algorithm 3's sweep has 2n + 2 loads and n + 2 stores per coordinate: at n = 8, 1.96 ms with
-// 1024, 2.04 ms with 2048, 2.07 ms with 4096.
-uint32_t diana_tile(const intsgd_desc* desc) { return desc->n >= 8 ? 1024u : 2048u; }
+// Algorithm 3's sweep has 2n + 2 loads and n + 2 stores per coordinate.  n = 8: 1.96 ms with 1024,
+// 2.04 ms with 2048, 2.07 ms with 4096 at d = 108 M (and 0.427 against 0.439 ms at d = 25.6 M);
+// n = 4 and n = 16 are 1-5 % faster with 2048; a vector of more than 2^20 tiles of 1024 would
+// exceed the launch grid and lose the one-tile-per-workgroup order (d = 1.3 G: 24.9 against 24.3 ms).
+uint32_t diana_tile(const intsgd_desc* desc) {
+  const bool mid = desc->n >= 6 && desc->n <= 12;
+  return (mid && tiles_of(desc->d, 1024u) + desc->num_blocks <= kMaxGrid) ? 1024u : 2048u;
+}
 
 intsgd_status make_tiling(const intsgd_desc* desc, void* stream, Tiling* t,
                           uint32_t automatic_tile = 0, bool may_build = true) {
