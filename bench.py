@@ -26,6 +26,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
+# vector ALU: 256 compute units x 64 lanes x 2.4 GHz lane-instructions per second (one wavefront
+# VALU instruction per CU and cycle); the chip sustains about 2.0 GHz under the randomized sweep
+ALU_PEAK_LANE_OPS = 256 * 64 * 2.4e9
 HEADLINE_CONFIG = 5
 # State that the sweeps leave in the 256 MB memory-side cache from one step to the next (the
 # library's policy: a state vector up to 192 MB whole, of a larger one the first 224 MB).
@@ -488,6 +491,10 @@ def run_workload(args, hip, cfg, *, cpu_legs, arena):
                           "summary of this kernel and workload, not measured in this run",
         "dram_only_frac": dram_only_frac,
         "valu_busy": counters.get("valu_busy"),
+        "alu_frac": (counters["valu_insts_per_launch"] * 64 / (avg_kernel_ms * 1e-3) / ALU_PEAK_LANE_OPS
+                     if kernel_ms and counters.get("valu_insts_per_launch") else None),
+        "alu_note": "vector lane-instructions per second (SQ_INSTS_VALU of the committed profile x 64 "
+                    "/ this run's kernel time) against 256 CUs x 64 lanes x 2.4 GHz",
         "kernel": kernel_name,
         "algorithmic_bytes_per_launch": algo_bytes,
         "kernel_ms_avg": avg_kernel_ms, "kernel_ms_min": kernel_ms[0] if kernel_ms else None,
@@ -558,6 +565,7 @@ def run_workload(args, hip, cfg, *, cpu_legs, arena):
         "frac": roofline["frac"] if claim else None,
         "dram_only_frac": dram_only_frac if claim else None,
         "valu_busy": counters.get("valu_busy"),
+        "alu_frac": roofline["alu_frac"] if claim else None,
         "note": None if claim else "no roofline claim: 16 MB of gradients, cache-resident and launch-bound",
     }
     if "cpu_baseline" in result:
