@@ -271,7 +271,7 @@ INTSGD_API intsgd_status intsgd_step_fused_next_alpha(const intsgd_desc* desc,
  *   - The scratch must hold 16 + 8 n bytes per work tile (the automatic tile of the sweep, or
  *     desc->launch->tile_coords), or per compute unit when the call takes the two-phase
  *     form, plus 1 KiB; a larger problem is refused with INTSGD_EWORKSPACE and nothing is
- *     launched.  32 MiB covers d = 9.0e8 at n = 8 (d = 1.3e9 with tile_coords = 4096),
+ *     launched.  32 MiB covers d = 8.5e8 at n = 8 (d = 1.3e9 with tile_coords = 4096),
  *     d = 6.6e7 at n = 128 in the tile form, and any d in the two-phase form.
  *   - num_blocks > 1 needs the partition's tile table, which only intsgd_prepare builds:
  *     without it the call returns INTSGD_ENOPLAN.  Calling intsgd_prepare(desc) once per
