@@ -53,7 +53,7 @@ def _load():
     path = library_path()
     if not os.path.exists(path):
         raise ImportError(
-            "%s is not built; run `python -m paper_2102_08374_amd.build` "
+            "%s is not built; run `python paper_2102_08374_amd/build.py` "
             "(or __graft_entry__.build()) first" % path)
     return C.CDLL(path)
 
