@@ -210,3 +210,55 @@ def test_everything_clips_to_the_bound():
     P.intsgd_step_fused(desc, [dev(g[i]) for i in range(n)], dev(alpha), 0.1,
                         torch.zeros(d, dtype=torch.float32, device=DEV), ns, cnt, ws)
     assert u32(big) == want
+
+
+def test_graph_replay_of_the_static_scratch_step_with_the_largest_entry():
+    """The entry point for callers that cannot allocate, captured in a HIP graph with the
+    largest-entry output attached, replayed with fresh gradients (randomized rounding, blocks):
+    every replay equals the eager workspace form, the step counter being part of the capture."""
+    d, n, offsets = 600_011, 5, [0, 100_003, 100_004, 600_011]
+    B = len(offsets) - 1
+    rng = np.random.default_rng(77)
+    desc_g = P.Desc(d, n, rounding=P.ROUND_STOCHASTIC, clip=P.default_clip(n), seed=3, step=7,
+                    block_offsets=offsets)
+    desc_e = P.Desc(d, n, rounding=P.ROUND_STOCHASTIC, clip=P.default_clip(n), seed=3, step=7,
+                    block_offsets=offsets)
+    P.intsgd_prepare(desc_g)
+    ws = P.new_workspace(desc_e, DEV)
+    big_g, big_e = sentinel(B), sentinel(B)
+    desc_g.largest_sum, desc_e.largest_sum = big_g, big_e
+    rows = [torch.zeros(d, dtype=torch.float32, device=DEV) for _ in range(n)]
+    x_g = torch.zeros(d, dtype=torch.float32, device=DEV)
+    a_g = torch.full((B,), 500.0, dtype=torch.float32, device=DEV)
+    r_g = torch.zeros(B, dtype=torch.float64, device=DEV)
+    ns_g = torch.zeros(B, dtype=torch.float64, device=DEV)
+    cnt_g = torch.zeros(n, dtype=torch.int64, device=DEV)
+    x_e, a_e, r_e, ns_e, cnt_e = x_g.clone(), a_g.clone(), r_g.clone(), ns_g.clone(), cnt_g.clone()
+
+    def call_static():
+        P.intsgd_step_fused_static(desc_g, rows, a_g, 0.1, x_g, r_g, 0.9, 1e-8, ns_g, cnt_g)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        call_static()                              # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    x_g.zero_()
+    a_g.fill_(500.0)
+    r_g.zero_()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        call_static()
+    for k in range(3):
+        fresh = rng.normal(0.0, 0.01, (n, d)).astype(F32)
+        for i in range(n):
+            rows[i].copy_(torch.from_numpy(fresh[i]))      # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        P.intsgd_step_fused_next_alpha(desc_e, rows, a_e, 0.1, x_e, r_e, 0.9, 1e-8, ns_e, cnt_e, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(x_g, x_e), "replay %d" % k
+        assert torch.equal(a_g, a_e) and torch.equal(r_g, r_e) and torch.equal(ns_g, ns_e)
+        assert torch.equal(cnt_g, cnt_e)
+        assert torch.equal(big_g, big_e) and host(big_g).min() > 0
